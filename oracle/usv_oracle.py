@@ -1,0 +1,203 @@
+"""CPU fp64 oracle for dynamic block-sparse video attention.  TEST INFRASTRUCTURE ONLY.
+
+This file is the yardstick the HIP kernels are compared against.  It is not a
+product path: only tests, the smoke check and the benchmark's CPU-baseline leg
+may import it, and it shares no code with the HIP path.  Everything is plain
+NumPy in float64, written so it can be checked against the paper by eye; no
+tiling, no online softmax, no fusion.
+
+What it computes (paper: Section 3.2 "Video Sparse Attention", the unnumbered
+dense-attention and masked-attention equations; Section 2.2's coarse-to-fine
+description; Figure 2's "top-k cube selection"):
+
+  1. block_scores   coarse stage: one score per (query cube, key cube) pair from
+                    the mean-pooled query and key of each 64-token cube.
+  2. select_topk    per query cube, the k best-scoring key cubes -> index list.
+  3. block_sparse_attn
+                    softmax((Q K^T + log M) / sqrt(d_k)) V with the 0/1 mask M
+                    being block-structured: M[r, c] = 1 iff cube(c) is in the
+                    list of cube(r).  Entries with log M = -inf contribute
+                    exp(-inf) = 0, so only the listed cubes' keys are summed.
+  masked_dense_attn the same equation written with the full N x N mask, for
+                    small N (pins the gathered form above).
+  dense_attn        softmax(Q K^T / sqrt(d_k)) V, the keep-all limit.
+
+Every function is pinned by tests/test_oracle_pins.py against something other
+than itself (closed forms, torch's scaled_dot_product_attention in fp64,
+pure-Python brute force, invariants).  No function here is "parity unpinned".
+
+Readings taken where the paper is silent (also listed in the design notes):
+  * score = mean(Q_cube) . mean(K_cube) / sqrt(d); means over valid tokens only;
+    a cube with no valid token scores -inf; result rounded once to fp32.
+  * selection is per (batch, head, query cube); candidates are the cubes that
+    hold at least one valid token; order = (score descending, index ascending)
+    on canonical values (-0 == +0, NaN below -inf); the list is emitted in
+    ascending cube index, unused slots hold -1.
+  * log M is added to the scaled logit (it is 0 or -inf, so where the division
+    by sqrt(d_k) is drawn makes no difference).
+  * padded keys (token >= seq_valid) are masked; padded query rows output 0 and
+    lse = -inf; a query cube with an empty list outputs 0.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+BLOCK = 64
+
+
+def _f64(x):
+    return np.asarray(x, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------- #
+# stage 1: pooled block scores (coarse stage of the coarse-to-fine scheme)
+# --------------------------------------------------------------------------- #
+def block_means(X, seq_valid, block=BLOCK):
+    """Mean over the valid tokens of each block.  X: [..., N, d] -> [..., nb, d] (fp64).
+
+    Blocks without a valid token get NaN means (they have no mean)."""
+    X = _f64(X)
+    N, d = X.shape[-2], X.shape[-1]
+    nb = N // block
+    out = np.full(X.shape[:-2] + (nb, d), np.nan)
+    for i in range(nb):
+        lo, hi = i * block, min((i + 1) * block, seq_valid)
+        if hi > lo:
+            out[..., i, :] = X[..., lo:hi, :].sum(axis=-2) / (hi - lo)
+    return out
+
+
+def block_scores(Q, K, seq_valid, block=BLOCK):
+    """S[b,h,i,j] = mean(Q_blk i) . mean(K_blk j) / sqrt(d), fp64 then rounded once to fp32.
+
+    Q, K: [B, Hh, N, d].  Rows/columns of blocks with no valid token are -inf."""
+    d = Q.shape[-1]
+    qm = block_means(Q, seq_valid, block)
+    km = block_means(K, seq_valid, block)
+    nb = qm.shape[-2]
+    nb_valid = (seq_valid + block - 1) // block
+    S = np.full(qm.shape[:-2] + (nb, nb), -np.inf)
+    S[..., :nb_valid, :nb_valid] = (
+        np.einsum("...id,...jd->...ij", qm[..., :nb_valid, :], km[..., :nb_valid, :]) / math.sqrt(d)
+    )
+    return S.astype(np.float32)
+
+
+# --------------------------------------------------------------------------- #
+# stage 2: top-k key-block selection
+# --------------------------------------------------------------------------- #
+def select_topk_row(scores_row, k, nb_valid):
+    """Indices of the k best of scores_row[:nb_valid], ascending; ties -> lower index."""
+    s = np.asarray(scores_row[:nb_valid], dtype=np.float32)
+    isnan = np.isnan(s)
+    canon = np.where(isnan, -np.inf, s).astype(np.float64) + 0.0  # -0 -> +0
+    # primary: score descending; then NaN after every number (also after -inf); then index ascending
+    order = np.lexsort((np.arange(nb_valid), isnan, -canon))
+    keep = order[: max(0, min(int(k), nb_valid))]
+    return np.sort(keep).astype(np.int32)
+
+
+def select_topk(S, k, seq_valid, budgets=None, kmax=None, block=BLOCK):
+    """S: fp32 [B, Hh, nb, nb].  Returns idx int32 [B,Hh,nb,kmax] (-1 padded) and cnt int32 [B,Hh,nb].
+
+    A row keeps min(budget, kmax, nb_valid) blocks where budget = budgets[b,h,i] if given else k.
+    Query blocks with no valid token keep nothing."""
+    B, Hh, nb, _ = S.shape
+    nb_valid = (seq_valid + block - 1) // block
+    if kmax is None:
+        kmax = int(k)
+    idx = np.full((B, Hh, nb, kmax), -1, dtype=np.int32)
+    cnt = np.zeros((B, Hh, nb), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hh):
+            for i in range(nb_valid):
+                want = int(budgets[b, h, i]) if budgets is not None else int(k)
+                want = max(0, min(want, kmax))
+                sel = select_topk_row(S[b, h, i], want, nb_valid)
+                idx[b, h, i, : len(sel)] = sel
+                cnt[b, h, i] = len(sel)
+    return idx, cnt
+
+
+# --------------------------------------------------------------------------- #
+# stage 3: attention
+# --------------------------------------------------------------------------- #
+def _softmax_rows(L):
+    """Row softmax and log-sum-exp of a logit matrix that may hold -inf entries."""
+    m = L.max(axis=-1, keepdims=True)
+    e = np.exp(L - m)
+    z = e.sum(axis=-1, keepdims=True)
+    return e / z, (m + np.log(z))[..., 0]
+
+
+def dense_attn(Q, K, V, scale=None):
+    """softmax(Q K^T / sqrt(d_k)) V for one head.  Q,K,V: [N, d].  (Dense-attention equation, Sec. 3.2.)"""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    scale = 1.0 / math.sqrt(Q.shape[-1]) if scale is None else scale
+    P, lse = _softmax_rows((Q @ K.T) * scale)
+    return P @ V, lse
+
+
+def masked_dense_attn(Q, K, V, M, scale=None):
+    """softmax(Q K^T / sqrt(d_k) + log M) V for one head, M a full N x N 0/1 mask.  (Masked equation, Sec. 3.2.)
+
+    Every row of M must allow at least one key."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    scale = 1.0 / math.sqrt(Q.shape[-1]) if scale is None else scale
+    with np.errstate(divide="ignore"):
+        logM = np.log(_f64(M))
+    P, lse = _softmax_rows((Q @ K.T) * scale + logM)
+    return P @ V, lse
+
+
+def block_mask(idx, cnt, seq_len, seq_valid, block=BLOCK):
+    """Full N x N 0/1 mask of one head from its index list: M[r,c]=1 iff blk(c) listed for blk(r), c valid."""
+    M = np.zeros((seq_len, seq_len), dtype=np.float64)
+    nb = seq_len // block
+    for i in range(nb):
+        for j in idx[i, : cnt[i]]:
+            M[i * block : (i + 1) * block, j * block : min((j + 1) * block, seq_valid)] = 1.0
+    return M
+
+
+def block_sparse_attn_head(Q, K, V, idx, cnt, seq_valid, scale=None, qblocks=None, block=BLOCK):
+    """Block-masked attention for one head.  Q,K,V: [N, d]; idx [nb,kmax], cnt [nb].
+
+    For each query block i the keys with log M = 0 are exactly the valid tokens of the listed
+    blocks; the softmax is taken over those keys (the others contribute exp(-inf) = 0).
+    Returns O [N, d] fp64 and lse [N] fp64; rows of query blocks not in `qblocks` (default: all)
+    are left at 0 / -inf, as are padded rows and rows of blocks with an empty list."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    N, d = Q.shape
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    O = np.zeros((N, d))
+    lse = np.full((N,), -np.inf)
+    nb = N // block
+    for i in range(nb) if qblocks is None else qblocks:
+        r0, r1 = i * block, min((i + 1) * block, seq_valid)
+        if r1 <= r0 or cnt[i] == 0:
+            continue
+        cols = np.concatenate(
+            [np.arange(j * block, min((j + 1) * block, seq_valid)) for j in idx[i, : cnt[i]]]
+        )
+        if cols.size == 0:
+            continue
+        P, l = _softmax_rows((Q[r0:r1] @ K[cols].T) * scale)
+        O[r0:r1] = P @ V[cols]
+        lse[r0:r1] = l
+    return O, lse
+
+
+def block_sparse_attn(Q, K, V, idx, cnt, seq_valid, scale=None, block=BLOCK):
+    """All heads.  Q,K,V: [B,Hh,N,d]; idx [B,Hh,nb,kmax]; cnt [B,Hh,nb] -> O [B,Hh,N,d], lse [B,Hh,N] (fp64)."""
+    B, Hh, N, d = Q.shape
+    O = np.zeros((B, Hh, N, d))
+    lse = np.full((B, Hh, N), -np.inf)
+    for b in range(B):
+        for h in range(Hh):
+            O[b, h], lse[b, h] = block_sparse_attn_head(
+                Q[b, h], K[b, h], V[b, h], idx[b, h], cnt[b, h], seq_valid, scale, None, block
+            )
+    return O, lse

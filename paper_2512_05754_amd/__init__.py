@@ -1,0 +1,24 @@
+"""MI355X-native dynamic block-sparse video attention (scores -> top-k -> block-sparse flash attention).
+
+The HIP library is loaded lazily on first use of a binding function so that importing the
+package (for example for its input generators) never needs the GPU.
+"""
+
+_BINDING_NAMES = (
+    "block_scores",
+    "select_topk",
+    "block_sparse_attn",
+    "workspace_bytes",
+    "lib",
+    "lib_path",
+    "UsvError",
+    "EXPORTED_SYMBOLS",
+)
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES:
+        from . import binding
+
+        return getattr(binding, name)
+    raise AttributeError(name)

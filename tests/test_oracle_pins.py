@@ -1,0 +1,317 @@
+"""Pins for the CPU oracle: each oracle function is checked against something other than itself.
+
+The paper prints no worked numeric example for the attention path, so the pins are what the
+mathematics fixes: closed forms, a library routine (torch SDPA in fp64), pure-Python brute
+force on tiny inputs, and invariants.  Each test names the mistake it is meant to catch.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import usv_oracle as orc
+from paper_2512_05754_amd import synth
+
+RNG = np.random.default_rng(7)
+
+
+def randn(*shape):
+    return RNG.standard_normal(shape)
+
+
+# --------------------------------------------------------------------------- #
+# stage 1: block scores
+# --------------------------------------------------------------------------- #
+def test_scores_equal_mean_of_dense_logit_tile():
+    """Linearity: mean(Q_i).mean(K_j)/sqrt(d) == mean of the 64x64 tile of QK^T/sqrt(d).
+    Catches a wrong pooling axis, a missing 1/sqrt(d), transposed i/j."""
+    B, Hh, N, d = 1, 2, 256, 32
+    Q, K = randn(B, Hh, N, d), randn(B, Hh, N, d) + 0.3
+    S = orc.block_scores(Q, K, N)
+    for h in range(Hh):
+        L = (Q[0, h] @ K[0, h].T) / math.sqrt(d)
+        tiles = L.reshape(N // 64, 64, N // 64, 64).mean(axis=(1, 3))
+        np.testing.assert_allclose(S[0, h], tiles, rtol=2e-6, atol=2e-7)
+    assert S.dtype == np.float32
+
+
+def test_scores_closed_form_constant_blocks():
+    """Blocks filled with constants a_i (queries) and b_j (keys): S_ij = d*a_i*b_j/sqrt(d)."""
+    d, nb = 16, 3
+    a, b = np.array([1.0, -2.0, 0.5]), np.array([3.0, 0.25, -1.0])
+    Q = np.repeat(a, 64)[:, None] * np.ones((1, d))
+    K = np.repeat(b, 64)[:, None] * np.ones((1, d))
+    S = orc.block_scores(Q[None, None], K[None, None], nb * 64)
+    np.testing.assert_allclose(S[0, 0], np.outer(a, b) * d / math.sqrt(d), rtol=1e-6)
+
+
+def test_scores_pure_python_bruteforce_and_padding():
+    """Triple loop over tokens and channels; padded rows hold garbage that must not enter the means."""
+    d, Nv, N = 4, 100, 128
+    Q, K = randn(1, 1, N, d), randn(1, 1, N, d)
+    Q[..., Nv:, :] = 1e4
+    K[..., Nv:, :] = -1e4
+    S = orc.block_scores(Q, K, Nv)
+    for i, j in itertools.product(range(2), range(2)):
+        ri = range(i * 64, min(i * 64 + 64, Nv))
+        rj = range(j * 64, min(j * 64 + 64, Nv))
+        acc = 0.0
+        for c in range(d):
+            qm = sum(Q[0, 0, r, c] for r in ri) / len(ri)
+            km = sum(K[0, 0, r, c] for r in rj) / len(rj)
+            acc += qm * km
+        assert S[0, 0, i, j] == pytest.approx(acc / math.sqrt(d), rel=1e-6, abs=1e-7)
+
+
+def test_scores_fully_padded_block_is_minus_inf():
+    Q, K = randn(1, 1, 192, 8), randn(1, 1, 192, 8)
+    S = orc.block_scores(Q, K, 70)  # block 2 has no valid token
+    assert np.all(np.isneginf(S[0, 0, 2, :])) and np.all(np.isneginf(S[0, 0, :, 2]))
+    assert np.all(np.isfinite(S[0, 0, :2, :2]))
+
+
+# --------------------------------------------------------------------------- #
+# stage 2: top-k
+# --------------------------------------------------------------------------- #
+def brute_topk(row, k):
+    """Pure-Python: sort (canonical score descending, index ascending), keep k, emit ascending."""
+    def key(j):
+        v = float(row[j])
+        if math.isnan(v):
+            return (2, 0.0, j)  # after everything
+        return (0 if v != -math.inf else 1, -v + 0.0, j)
+
+    order = sorted(range(len(row)), key=key)
+    return sorted(order[:k])
+
+
+@pytest.mark.parametrize("nb,k", [(16, 4), (16, 1), (16, 16), (100, 37), (512, 51)])
+def test_topk_matches_full_sort(nb, k):
+    S = RNG.standard_normal((1, 2, nb, nb)).astype(np.float32)
+    idx, cnt = orc.select_topk(S, k, nb * 64)
+    assert idx.shape == (1, 2, nb, k) and np.all(cnt == k)
+    for h, i in itertools.product(range(2), range(0, nb, max(1, nb // 7))):
+        assert list(idx[0, h, i]) == brute_topk(S[0, h, i], k)
+        assert np.all(np.diff(idx[0, h, i]) > 0)
+
+
+def test_topk_engineered_ties_and_special_values():
+    """all-equal -> first k; duplicates across the k-th place -> lower index; -0 == +0; -inf and NaN last."""
+    nb = 16
+    row = np.zeros(nb, dtype=np.float32)
+    assert list(orc.select_topk_row(row, 5, nb)) == [0, 1, 2, 3, 4]
+    row = np.array([1, 5, 5, 5, 0, 5, 9, 5] + [0] * 8, dtype=np.float32)
+    assert list(orc.select_topk_row(row, 3, nb)) == [1, 2, 6]  # 9, then the first two 5s
+    row = np.array([-0.0, 0.0, -0.0, 0.0] + [-1] * 12, dtype=np.float32)
+    assert list(orc.select_topk_row(row, 2, nb)) == [0, 1]  # signed zeros tie, lower index wins
+    row = np.array([-np.inf, np.nan, 3.0, -np.inf, np.nan, 2.0], dtype=np.float32)
+    assert list(orc.select_topk_row(row, 2, 6)) == [2, 5]
+    assert list(orc.select_topk_row(row, 3, 6)) == [0, 2, 5]  # -inf beats NaN
+    assert list(orc.select_topk_row(row, 5, 6)) == [0, 1, 2, 3, 5]  # first NaN by index
+    for r in (row,):
+        for k in range(7):
+            assert list(orc.select_topk_row(r, k, 6)) == brute_topk(r, k)
+
+
+def test_topk_permutation_equivariance():
+    """Distinct scores: permuting the columns permutes the selected set the same way."""
+    nb, k = 64, 9
+    row = RNG.permutation(nb).astype(np.float32)
+    perm = RNG.permutation(nb)
+    a = set(orc.select_topk_row(row, k, nb).tolist())
+    b = set(orc.select_topk_row(row[perm], k, nb).tolist())
+    assert {int(np.where(perm == j)[0][0]) for j in a} == b
+    assert a == set(np.argsort(-row)[:k].tolist())
+
+
+def test_topk_budgets_padding_and_invalid_blocks():
+    nb, kmax = 8, 5
+    S = RNG.standard_normal((1, 1, nb, nb)).astype(np.float32)
+    budgets = np.array([[[0, 1, 2, 3, 4, 5, 9, 2]]], dtype=np.int32)
+    Nv = 6 * 64 + 10  # 7 valid blocks; block 7 fully padded
+    idx, cnt = orc.select_topk(S, 0, Nv, budgets=budgets, kmax=kmax)
+    assert list(cnt[0, 0]) == [0, 1, 2, 3, 4, 5, 5, 0]
+    for i in range(nb):
+        c = cnt[0, 0, i]
+        assert np.all(idx[0, 0, i, c:] == -1) and np.all(idx[0, 0, i, :c] < 7)
+        assert list(idx[0, 0, i, :c]) == brute_topk(S[0, 0, i, :7], c)
+
+
+# --------------------------------------------------------------------------- #
+# stage 3: attention
+# --------------------------------------------------------------------------- #
+def sdpa64(Q, K, V, mask=None, scale=None):
+    q, k, v = (torch.from_numpy(np.asarray(x, dtype=np.float64))[None, None] for x in (Q, K, V))
+    m = None if mask is None else torch.from_numpy(mask.astype(bool))[None, None]
+    return torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=m, scale=scale)[0, 0].numpy()
+
+
+def random_lists(nb, kmax, rng, ragged=True):
+    idx = np.full((nb, kmax), -1, dtype=np.int32)
+    cnt = np.zeros(nb, dtype=np.int32)
+    for i in range(nb):
+        c = int(rng.integers(1, kmax + 1)) if ragged else kmax
+        idx[i, :c] = np.sort(rng.choice(nb, size=c, replace=False))
+        cnt[i] = c
+    return idx, cnt
+
+
+def test_dense_attn_matches_library_sdpa():
+    """Textbook softmax(QK^T/sqrt(d))V vs torch SDPA in fp64; Q and K have different means so that
+    a swapped Q/K or a transposed product fails."""
+    N, d = 96, 24
+    Q, K, V = randn(N, d) + 0.5, randn(N, d) - 0.25, randn(N, d)
+    O, lse = orc.dense_attn(Q, K, V)
+    np.testing.assert_allclose(O, sdpa64(Q, K, V), rtol=1e-11, atol=1e-12)
+    L = (Q @ K.T) / math.sqrt(d)
+    np.testing.assert_allclose(lse, np.log(np.exp(L).sum(-1)), rtol=1e-12)
+    O2, _ = orc.dense_attn(Q, K, V, scale=0.37)
+    np.testing.assert_allclose(O2, sdpa64(Q, K, V, scale=0.37), rtol=1e-11, atol=1e-12)
+
+
+def test_two_key_closed_form():
+    """One query, two keys with logits ln(1) and ln(3): weights 1/4 and 3/4, lse = ln 4."""
+    d = 4
+    q = np.array([[2.0, 0, 0, 0]])
+    K = np.array([[0.0, 1, 0, 0], [math.log(3.0), 0, 0, 0]])  # logits with scale=1/2: 0 and ln 3
+    V = np.array([[1.0, 0, 0, 8], [0.0, 1, 0, 4]])
+    O, lse = orc.dense_attn(q, K, V)
+    np.testing.assert_allclose(O[0], [0.25, 0.75, 0.0, 5.0], rtol=1e-14)
+    assert lse[0] == pytest.approx(math.log(4.0), rel=1e-14)
+
+
+def test_keep_all_equals_dense():
+    nb, d = 4, 16
+    N = nb * 64
+    Q, K, V = randn(N, d), randn(N, d), randn(N, d)
+    idx = np.tile(np.arange(nb, dtype=np.int32), (nb, 1))
+    cnt = np.full(nb, nb, dtype=np.int32)
+    O, lse = orc.block_sparse_attn_head(Q, K, V, idx, cnt, N)
+    np.testing.assert_allclose(O, sdpa64(Q, K, V), rtol=1e-11, atol=1e-12)
+    Od, lsed = orc.dense_attn(Q, K, V)
+    np.testing.assert_allclose(O, Od, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, lsed, rtol=1e-12)
+
+
+@pytest.mark.parametrize("Nv", [5 * 64, 5 * 64 - 23])
+def test_block_sparse_equals_masked_dense_and_library(Nv):
+    """Any list: equals dense attention with -inf on unselected blocks (own full-mask form and torch SDPA)."""
+    nb, d = 5, 8
+    N = nb * 64
+    rng = np.random.default_rng(11)
+    Q, K, V = randn(N, d), randn(N, d), randn(N, d)
+    Q[Nv:], K[Nv:], V[Nv:] = 1e3, 1e3, 1e3
+    idx, cnt = random_lists(nb, 3, rng)
+    idx[2, : cnt[2]] = idx[2, : cnt[2]][::-1]  # a descending list is still a valid list
+    if Nv < N:
+        idx[1, 0], cnt[1] = nb - 1, 1  # a row whose only block is the partial one
+    O, lse = orc.block_sparse_attn_head(Q, K, V, idx, cnt, Nv)
+    M = orc.block_mask(idx, cnt, N, Nv)
+    Om, lsem = orc.masked_dense_attn(Q[:Nv], K, V, M[:Nv])
+    np.testing.assert_allclose(O[:Nv], Om, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(lse[:Nv], lsem, rtol=1e-12)
+    np.testing.assert_allclose(O[:Nv], sdpa64(Q[:Nv], K, V, mask=M[:Nv]), rtol=1e-10, atol=1e-11)
+    assert np.all(O[Nv:] == 0) and np.all(np.isneginf(lse[Nv:]))
+    # mask structure: block-constant, padded key columns closed
+    assert np.all(M[:, Nv:] == 0)
+    for i in range(nb):
+        assert M[i * 64 : (i + 1) * 64].min(axis=0).tolist() == M[i * 64].tolist()
+
+
+def test_rows_sum_to_one_and_identical_keys_average_values():
+    nb, d = 4, 8
+    N = nb * 64
+    rng = np.random.default_rng(3)
+    idx, cnt = random_lists(nb, 3, rng)
+    Q, K = randn(N, d), randn(N, d)
+    O, _ = orc.block_sparse_attn_head(Q, K, np.ones((N, d)), idx, cnt, N)
+    np.testing.assert_allclose(O, 1.0, rtol=1e-13)
+    V = randn(N, d)
+    Kc = np.tile(randn(1, d), (N, 1))
+    O, _ = orc.block_sparse_attn_head(Q, Kc, V, idx, cnt, N)
+    for i in range(nb):
+        want = np.mean([V[j * 64 : (j + 1) * 64] for j in idx[i, : cnt[i]]], axis=(0, 1))
+        np.testing.assert_allclose(O[i * 64 : (i + 1) * 64], np.tile(want, (64, 1)), rtol=1e-12, atol=1e-13)
+
+
+def test_single_valid_key_returns_its_value_row():
+    """cnt = 1 and the listed block holds exactly one valid token: output = that V row."""
+    d, Nv = 8, 65
+    N = 128
+    Q, K, V = randn(N, d), randn(N, d), randn(N, d)
+    idx = np.array([[1], [1]], dtype=np.int32)
+    cnt = np.array([1, 1], dtype=np.int32)
+    O, lse = orc.block_sparse_attn_head(Q, K, V, idx, cnt, Nv)
+    np.testing.assert_allclose(O[:Nv], np.tile(V[64], (Nv, 1)), rtol=1e-14)
+    np.testing.assert_allclose(lse[:Nv], (Q[:Nv] @ K[64]) / math.sqrt(d), rtol=1e-12)
+
+
+def test_order_invariance_lse_consistency_and_key_shift():
+    nb, d = 6, 16
+    N = nb * 64
+    rng = np.random.default_rng(5)
+    Q, K, V = randn(N, d), randn(N, d), randn(N, d)
+    idx, cnt = random_lists(nb, 4, rng, ragged=False)
+    O, lse = orc.block_sparse_attn_head(Q, K, V, idx, cnt, N)
+    O2, lse2 = orc.block_sparse_attn_head(Q, K, V, idx[:, ::-1].copy(), cnt, N)
+    np.testing.assert_allclose(O, O2, rtol=1e-12, atol=1e-13)
+    # sum over selected keys of exp(logit - lse) == 1
+    for i in (0, nb - 1):
+        cols = np.concatenate([np.arange(j * 64, j * 64 + 64) for j in idx[i]])
+        L = (Q[i * 64 : (i + 1) * 64] @ K[cols].T) / math.sqrt(d)
+        np.testing.assert_allclose(np.exp(L - lse[i * 64 : (i + 1) * 64, None]).sum(-1), 1.0, rtol=1e-12)
+    # K + kappa shifts every logit of a row by the same amount: output unchanged, lse shifted
+    kappa = 30.0 * randn(1, d)
+    O3, lse3 = orc.block_sparse_attn_head(Q, K + kappa, V, idx, cnt, N)
+    np.testing.assert_allclose(O3, O, rtol=1e-9, atol=1e-10)
+    np.testing.assert_allclose(lse3 - lse, (Q @ kappa[0]) / math.sqrt(d), rtol=1e-9, atol=1e-9)
+
+
+def test_pipeline_tiny_config_against_bruteforce():
+    """Config 'tiny' end to end: scores -> top-4 of 16 -> attention, against a dense-mask brute force
+    that selects with a full Python sort of the dense logit-tile means."""
+    w = synth.TINY
+    Q, K, V = synth.gen_qkv(w)
+    S = orc.block_scores(Q, K, w.seq_valid)
+    idx, cnt = orc.select_topk(S, w.keep, w.seq_valid)
+    O, lse = orc.block_sparse_attn(Q, K, V, idx, cnt, w.seq_valid)
+    assert O.shape == (1, 2, 1024, 64) and idx.shape == (1, 2, 16, 4)
+    for h in range(w.heads):
+        q, k, v = (np.asarray(x[0, h], dtype=np.float64) for x in (Q, K, V))
+        L = (q @ k.T) / 8.0
+        tile_mean = L.reshape(16, 64, 16, 64).mean(axis=(1, 3)).astype(np.float32)
+        M = np.zeros((1024, 1024))
+        for i in range(16):
+            keep = brute_topk(tile_mean[i], 4)
+            assert keep == list(idx[0, h, i])
+            for j in keep:
+                M[i * 64 : (i + 1) * 64, j * 64 : (j + 1) * 64] = 1
+        np.testing.assert_allclose(O[0, h], sdpa64(q, k, v, mask=M), rtol=1e-10, atol=1e-11)
+
+
+# --------------------------------------------------------------------------- #
+# input generator (storage formats only)
+# --------------------------------------------------------------------------- #
+def test_bf16_roundtrip_matches_torch():
+    x = np.concatenate([RNG.standard_normal(4096).astype(np.float32) * 5,
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38, 1e-40], dtype=np.float32)])
+    bits = synth.f32_to_bf16_bits(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16)
+    assert np.array_equal(bits, ref.view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(synth.bf16_bits_to_f32(bits), ref.float().numpy())
+
+
+def test_generator_is_deterministic_and_shaped():
+    w = synth.MERGED_RAGGED
+    q1, k1, v1 = synth.gen_head(w, 1, 3)
+    q2, _, _ = synth.gen_head(w, 1, 3)
+    assert q1.dtype == np.uint16 and q1.shape == (16384, 128) and np.array_equal(q1, q2)
+    b = synth.gen_budgets(w)
+    assert b.shape == (2, 12, 256) and b.min() >= 8 and b.max() <= 64
+    w1 = synth.WAN13_480P
+    assert (w1.seq_len, w1.nb, w1.keep) == (32768, 512, 51)
+    assert [synth.sweep(r).keep for r in synth.SWEEP_RATIOS] == [512, 256, 128, 51, 25]
+    assert (synth.WAN14_720P.seq_len, synth.WAN14_720P.nb) == (75648, 1182)
+    assert synth.keep_count(0.05, 1182) == 59
