@@ -1,0 +1,147 @@
+/*
+ * usv.h - C ABI of the MI355X (gfx950) dynamic block-sparse video attention library.
+ *
+ * The library implements the attention hot path of a sparsified video diffusion
+ * transformer in three calls:
+ *
+ *   usv_block_scores      coarse stage: one score per (query cube, key cube) pair
+ *   usv_select_topk       per query cube, the k best key cubes -> compact index list
+ *   usv_block_sparse_attn softmax attention over only the listed key/value cubes
+ *
+ * Tokens are the flattened 3-D video latent, already ordered cube-major: the 64
+ * tokens of one 4x4x4 spatio-temporal cube are consecutive, so "block i" is
+ * tokens [64 i, 64 i + 64).
+ *
+ * Common conventions
+ *   - Every pointer except the usv_shape is a DEVICE pointer to caller-owned
+ *     memory (the library never allocates, frees or keeps a pointer), contiguous
+ *     in the stated layout with the last index fastest, 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it; they never synchronise the host.
+ *   - Arguments are validated on the host before anything is launched; a call
+ *     that returns an error has launched nothing.  Errors are status codes, never
+ *     aborts.  usv_last_error() gives a message for the calling thread's last error.
+ *   - Device contents are not validated (index lists, budgets): see each call.
+ *   - Padded tokens (seq_valid <= token < seq_len) may hold any FINITE values.
+ */
+#ifndef USV_H
+#define USV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  USV_OK = 0,
+  USV_ERR_INVALID_ARG = 1, /* null/misaligned pointer, inconsistent sizes */
+  USV_ERR_UNSUPPORTED = 2, /* block != 64, head_dim not in {64,128}, too many blocks */
+  USV_ERR_WORKSPACE = 3,   /* workspace missing or smaller than usv_workspace_bytes */
+  USV_ERR_HIP = 4          /* the HIP runtime refused a launch */
+} usv_status;
+
+typedef enum { USV_F32 = 0, USV_BF16 = 1 } usv_dtype;
+
+/* Problem shape shared by the three stages (host struct). */
+typedef struct {
+  int32_t batch;     /* B  >= 1 */
+  int32_t heads;     /* Hh >= 1 (attention heads) */
+  int32_t seq_len;   /* N: padded token count, a multiple of `block` */
+  int32_t seq_valid; /* Nv: real tokens, N - block < Nv <= N is typical; 1 <= Nv <= N */
+  int32_t head_dim;  /* d: 64 or 128 */
+  int32_t block;     /* tokens per cube: 64 */
+  int32_t dtype;     /* usv_dtype of Q, K, V */
+} usv_shape;
+
+#define USV_MAX_BLOCKS 4096 /* largest supported N / block */
+
+/* Bytes of device scratch usv_block_scores needs for `shape` (pooled fp32 means
+ * of Q and K: 2 * B * Hh * nb * d * 4).  Returns 0 for an invalid shape. */
+size_t usv_workspace_bytes(const usv_shape* shape);
+
+/*
+ * Stage 1 - pooled block scores (the coarse stage of the coarse-to-fine sparse
+ * attention the paper builds on, Section 2.2 / Section 3.2; Figure 2 "3D cubes").
+ *
+ *   Qm[b,h,i,:] = mean over valid tokens r of block i of Q[b,h,r,:]   (fp32)
+ *   Km[b,h,j,:] likewise
+ *   scores[b,h,i,j] = Qm[b,h,i,:] . Km[b,h,j,:] / sqrt(d)             (fp32)
+ *
+ * q, k   : [B, Hh, N, d] of shape->dtype (device, read only)
+ * scores : [B, Hh, nb, nb] fp32 (device, written); rows and columns of blocks
+ *          that hold no valid token are written as -inf
+ * ws     : device scratch of at least usv_workspace_bytes(shape) bytes; its
+ *          contents on return are unspecified
+ */
+usv_status usv_block_scores(const void* q, const void* k, const usv_shape* shape,
+                            float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 2 - per-query-block top-k key-block selection ("top-k cube selection",
+ * Figure 2).  For every row (b, h, i) with i a block holding a valid token:
+ *   candidates = key blocks j that hold a valid token
+ *   keep       = min(budget, kmax, #candidates), budget = budgets[b,h,i] if
+ *                budgets != NULL else k; a negative budget counts as 0
+ *   order      = score descending, then block index ascending, on canonical
+ *                values: -0 equals +0 and NaN ranks below -inf
+ * The kept indices are written in ASCENDING block index to idx[b,h,i,0..keep),
+ * the remaining slots up to kmax hold -1, and cnt[b,h,i] = keep.  Rows of blocks
+ * without a valid token get cnt = 0.
+ *
+ * scores  : [B, Hh, nb, nb] fp32 (device, read only)
+ * k       : uniform budget (1 <= k <= kmax) when budgets == NULL, else ignored
+ * budgets : NULL or [B, Hh, nb] int32 (device, read only)
+ * kmax    : row stride of idx, 1 <= kmax <= nb
+ * idx     : [B, Hh, nb, kmax] int32 (device, written)
+ * cnt     : [B, Hh, nb] int32 (device, written)
+ * Only shape->batch/heads/seq_len/seq_valid/block are used.
+ */
+usv_status usv_select_topk(const float* scores, const usv_shape* shape, int32_t k,
+                           const int32_t* budgets, int32_t kmax, int32_t* idx, int32_t* cnt,
+                           void* stream);
+
+/*
+ * Stage 3 - block-sparse attention: the masked-attention equation of Section 3.2,
+ *   out = softmax(Q K^T * scale + log M) V,
+ * with M[r, c] = 1 iff block(c) is listed for block(r) and c < seq_valid.
+ * Only the listed K/V blocks are read ("dense attention only within selected
+ * tiles", Section 2.2).  With every block listed this is the dense-attention
+ * equation of the same section.
+ *
+ * q, k, v : [B, Hh, N, d] of shape->dtype (device, read only)
+ * idx     : [B, Hh, nb, kmax] int32; row (b,h,i) holds cnt[b,h,i] DISTINCT block
+ *           ids in [0, ceil(Nv/64)) in its first slots, in any order (ascending
+ *           reads K/V most cache-friendly).  Not validated: an out-of-range id is
+ *           undefined behaviour.
+ * cnt     : [B, Hh, nb] int32, 0 <= cnt <= kmax
+ * scale   : softmax scale; <= 0 selects 1/sqrt(d)
+ * out_dtype : usv_dtype of `out`: shape->dtype, or USV_F32 for bf16 inputs (the
+ *           fp32 accumulator is then stored unrounded; rounding the result to
+ *           bf16 costs up to half a bf16 ulp, 2^-9 relative, on top of the
+ *           kernel's own error)
+ * out     : [B, Hh, N, d] of out_dtype (written).  Rows of padded tokens and of
+ *           query blocks with cnt = 0 are written as 0.
+ * lse     : NULL or [B, Hh, N] fp32 (written): natural-log sum of exp of the
+ *           scaled logits over the row's allowed keys; -inf where out is 0.
+ * bf16 inputs: QK^T and PV run on bf16 MFMA with fp32 accumulation and an fp32
+ * online softmax; the probabilities are rounded to bf16 before PV and the row
+ * sums are taken over the rounded values.
+ * fp32 inputs: everything in fp32 (plain FMA), for accuracy checks.
+ */
+usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v,
+                                 const usv_shape* shape, const int32_t* idx, const int32_t* cnt,
+                                 int32_t kmax, float scale, int32_t out_dtype, void* out, float* lse,
+                                 void* stream);
+
+/* Static string for a status code. */
+const char* usv_status_string(int32_t status);
+
+/* Message describing the calling thread's most recent error ("" if none). */
+const char* usv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* USV_H */

@@ -1,0 +1,191 @@
+"""ctypes binding of libusv.so: argument marshalling only, every step runs in the HIP kernels.
+
+Functions mirror the C ABI (include/usv.h) name for name.  Tensors are torch CUDA(ROCm)
+tensors used purely as device memory; work is enqueued on torch's current stream.
+There is no CPU fallback: a missing library or a CPU tensor raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+BLOCK = 64
+USV_F32, USV_BF16 = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "usv_workspace_bytes",
+    "usv_block_scores",
+    "usv_select_topk",
+    "usv_block_sparse_attn",
+    "usv_status_string",
+    "usv_last_error",
+)
+
+
+class UsvError(RuntimeError):
+    def __init__(self, status: int, name: str, message: str):
+        super().__init__(f"{name} ({status}): {message}")
+        self.status = status
+        self.status_name = name
+
+
+class UsvShape(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32),
+        ("heads", ctypes.c_int32),
+        ("seq_len", ctypes.c_int32),
+        ("seq_valid", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("block", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+    ]
+
+
+def lib_path() -> str:
+    return os.path.join(PKG_DIR, "libusv.so")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libusv.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        from .build import build_library
+
+        build_library(verbose=False)
+    L = ctypes.CDLL(path)
+    vp, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t, ctypes.c_float
+    sp = ctypes.POINTER(UsvShape)
+    L.usv_workspace_bytes.restype, L.usv_workspace_bytes.argtypes = sz, [sp]
+    L.usv_block_scores.restype, L.usv_block_scores.argtypes = i32, [vp, vp, sp, vp, vp, sz, vp]
+    L.usv_select_topk.restype, L.usv_select_topk.argtypes = i32, [vp, sp, i32, vp, i32, vp, vp, vp]
+    L.usv_block_sparse_attn.restype = i32
+    L.usv_block_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, i32, f32, i32, vp, vp, vp]
+    L.usv_status_string.restype, L.usv_status_string.argtypes = ctypes.c_char_p, [i32]
+    L.usv_last_error.restype, L.usv_last_error.argtypes = ctypes.c_char_p, []
+    _lib = L
+    return L
+
+
+def _check(status: int):
+    if status != 0:
+        L = lib()
+        raise UsvError(status, L.usv_status_string(status).decode(), L.usv_last_error().decode())
+
+
+def _dev(t: torch.Tensor, name: str, dtype=None):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor (there is no CPU path)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _shape_of(x: torch.Tensor, seq_valid) -> UsvShape:
+    if x.dim() != 4:
+        raise ValueError("Q/K/V must be [B, Hh, N, d]")
+    if x.dtype == torch.bfloat16:
+        dt = USV_BF16
+    elif x.dtype == torch.float32:
+        dt = USV_F32
+    else:
+        raise TypeError(f"unsupported dtype {x.dtype}")
+    B, Hh, N, d = x.shape
+    return UsvShape(B, Hh, N, N if seq_valid is None else int(seq_valid), d, BLOCK, dt)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def workspace_bytes(batch, heads, seq_len, seq_valid, head_dim, dtype) -> int:
+    dt = USV_BF16 if dtype in (torch.bfloat16, "bf16") else USV_F32
+    sh = UsvShape(batch, heads, seq_len, seq_valid, head_dim, BLOCK, dt)
+    return int(lib().usv_workspace_bytes(ctypes.byref(sh)))
+
+
+def block_scores(q, k, seq_valid=None, out=None, workspace=None):
+    """usv_block_scores: pooled block scores [B, Hh, nb, nb] fp32 of Q, K [B, Hh, N, d]."""
+    sh = _shape_of(q, seq_valid)
+    if k.shape != q.shape or k.dtype != q.dtype:
+        raise ValueError("k must match q in shape and dtype")
+    nb = sh.seq_len // BLOCK
+    if out is None:
+        out = torch.empty((sh.batch, sh.heads, nb, nb), dtype=torch.float32, device=q.device)
+    need = int(lib().usv_workspace_bytes(ctypes.byref(sh)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(
+        lib().usv_block_scores(
+            _dev(q, "q"), _dev(k, "k"), ctypes.byref(sh), _dev(out, "scores", torch.float32),
+            _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream(),
+        )
+    )
+    return out
+
+
+def select_topk(scores, k=0, seq_valid=None, budgets=None, kmax=None, idx=None, cnt=None):
+    """usv_select_topk: scores [B, Hh, nb, nb] fp32 -> idx [B, Hh, nb, kmax] int32 (-1 padded), cnt [B, Hh, nb]."""
+    if scores.dim() != 4 or scores.shape[2] != scores.shape[3]:
+        raise ValueError("scores must be [B, Hh, nb, nb]")
+    B, Hh, nb, _ = scores.shape
+    N = nb * BLOCK
+    sh = UsvShape(B, Hh, N, N if seq_valid is None else int(seq_valid), 0, BLOCK, USV_F32)
+    if kmax is None:
+        kmax = int(k)
+    if idx is None:
+        idx = torch.empty((B, Hh, nb, max(kmax, 1)), dtype=torch.int32, device=scores.device)
+    if cnt is None:
+        cnt = torch.empty((B, Hh, nb), dtype=torch.int32, device=scores.device)
+    bptr = None if budgets is None else _dev(budgets, "budgets", torch.int32)
+    _check(
+        lib().usv_select_topk(
+            _dev(scores, "scores", torch.float32), ctypes.byref(sh), int(k), bptr, int(kmax),
+            _dev(idx, "idx", torch.int32), _dev(cnt, "cnt", torch.int32), _stream(),
+        )
+    )
+    return idx, cnt
+
+
+def block_sparse_attn(q, k, v, idx, cnt, seq_valid=None, scale=0.0, out=None, lse=None, return_lse=False,
+                      out_dtype=None):
+    """usv_block_sparse_attn: attention over the listed K/V blocks.  Returns out (and lse if asked).
+
+    out_dtype: dtype of the result; defaults to q's dtype, torch.float32 is also allowed for bf16 inputs."""
+    sh = _shape_of(q, seq_valid)
+    for name, t in (("k", k), ("v", v)):
+        if t.shape != q.shape or t.dtype != q.dtype:
+            raise ValueError(f"{name} must match q in shape and dtype")
+    nb = sh.seq_len // BLOCK
+    if idx.dim() != 4 or tuple(idx.shape[:3]) != (sh.batch, sh.heads, nb):
+        raise ValueError("idx must be [B, Hh, nb, kmax]")
+    if tuple(cnt.shape) != (sh.batch, sh.heads, nb):
+        raise ValueError("cnt must be [B, Hh, nb]")
+    kmax = idx.shape[3]
+    if out is None:
+        out = torch.empty_like(q, dtype=out_dtype or q.dtype)
+    if out.shape != q.shape:
+        raise ValueError("out must have q's shape")
+    if out.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError(f"unsupported out dtype {out.dtype}")
+    odt = USV_F32 if out.dtype == torch.float32 else USV_BF16
+    if lse is None and return_lse:
+        lse = torch.empty((sh.batch, sh.heads, sh.seq_len), dtype=torch.float32, device=q.device)
+    _check(
+        lib().usv_block_sparse_attn(
+            _dev(q, "q"), _dev(k, "k"), _dev(v, "v"), ctypes.byref(sh),
+            _dev(idx, "idx", torch.int32), _dev(cnt, "cnt", torch.int32), int(kmax), float(scale),
+            odt, _dev(out, "out"), None if lse is None else _dev(lse, "lse", torch.float32), _stream(),
+        )
+    )
+    return (out, lse) if return_lse else out

@@ -1,0 +1,154 @@
+// C ABI of libusv: host-side argument validation and dispatch to the HIP kernels.
+// All checks run before anything is launched, so the error paths need no GPU.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "usv_internal.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+usv_status fail(usv_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks the shape fields the three stages share and fills Dims.
+usv_status check_shape(const usv_shape* sh, bool need_dtype, usv::Dims* out) {
+  if (!sh) return fail(USV_ERR_INVALID_ARG, "shape is NULL");
+  if (sh->batch < 1 || sh->heads < 1) return fail(USV_ERR_INVALID_ARG, "batch and heads must be >= 1");
+  if (sh->block != usv::kBlock) return fail(USV_ERR_UNSUPPORTED, "block must be 64 (got %d)", sh->block);
+  if (sh->seq_len < sh->block || sh->seq_len % sh->block != 0)
+    return fail(USV_ERR_INVALID_ARG, "seq_len (%d) must be a positive multiple of block", sh->seq_len);
+  if (sh->seq_valid < 1 || sh->seq_valid > sh->seq_len)
+    return fail(USV_ERR_INVALID_ARG, "seq_valid (%d) must be in [1, seq_len]", sh->seq_valid);
+  const int nb = sh->seq_len / sh->block;
+  if (nb > USV_MAX_BLOCKS) return fail(USV_ERR_UNSUPPORTED, "more than %d blocks (got %d)", USV_MAX_BLOCKS, nb);
+  if ((long long)sh->batch * sh->heads > 65535) return fail(USV_ERR_UNSUPPORTED, "batch * heads must be <= 65535");
+  if ((long long)sh->batch * sh->heads * nb > 0x7fffffffLL / 8)
+    return fail(USV_ERR_UNSUPPORTED, "batch * heads * blocks too large");
+  if (need_dtype) {
+    if (sh->head_dim != 64 && sh->head_dim != 128)
+      return fail(USV_ERR_UNSUPPORTED, "head_dim must be 64 or 128 (got %d)", sh->head_dim);
+    if (sh->dtype != USV_F32 && sh->dtype != USV_BF16)
+      return fail(USV_ERR_UNSUPPORTED, "dtype must be USV_F32 or USV_BF16 (got %d)", sh->dtype);
+  }
+  out->B = sh->batch;
+  out->Hh = sh->heads;
+  out->N = sh->seq_len;
+  out->Nv = sh->seq_valid;
+  out->d = sh->head_dim;
+  out->nb = nb;
+  out->nb_valid = (sh->seq_valid + sh->block - 1) / sh->block;
+  out->bf16 = sh->dtype == USV_BF16;
+  return USV_OK;
+}
+
+usv_status check_ptr(const void* p, const char* name) {
+  if (!p) return fail(USV_ERR_INVALID_ARG, "%s is NULL", name);
+  if (!aligned16(p)) return fail(USV_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+  return USV_OK;
+}
+
+usv_status hip_result(hipError_t e, const char* what) {
+  if (e == hipSuccess) {
+    g_err[0] = '\0';
+    return USV_OK;
+  }
+  return fail(USV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define USV_TRY(expr)                    \
+  do {                                   \
+    const usv_status st__ = (expr);      \
+    if (st__ != USV_OK) return st__;     \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t usv_workspace_bytes(const usv_shape* shape) {
+  usv::Dims s;
+  if (check_shape(shape, true, &s) != USV_OK) return 0;
+  return (size_t)2 * s.bh() * s.nb * s.d * sizeof(float);
+}
+
+usv_status usv_block_scores(const void* q, const void* k, const usv_shape* shape, float* scores, void* ws,
+                            size_t ws_bytes, void* stream) {
+  usv::Dims s;
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_ptr(q, "q"));
+  USV_TRY(check_ptr(k, "k"));
+  USV_TRY(check_ptr(scores, "scores"));
+  const size_t need = usv_workspace_bytes(shape);
+  if (!ws || !aligned16(ws) || ws_bytes < need)
+    return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
+  return hip_result(usv::launch_block_scores(q, k, s, scores, static_cast<float*>(ws), static_cast<hipStream_t>(stream)),
+                    "usv_block_scores launch");
+}
+
+usv_status usv_select_topk(const float* scores, const usv_shape* shape, int32_t k, const int32_t* budgets,
+                           int32_t kmax, int32_t* idx, int32_t* cnt, void* stream) {
+  usv::Dims s;
+  USV_TRY(check_shape(shape, false, &s));
+  USV_TRY(check_ptr(scores, "scores"));
+  USV_TRY(check_ptr(idx, "idx"));
+  USV_TRY(check_ptr(cnt, "cnt"));
+  if (kmax < 1 || kmax > s.nb) return fail(USV_ERR_INVALID_ARG, "kmax (%d) must be in [1, blocks = %d]", kmax, s.nb);
+  if (budgets) {
+    USV_TRY(check_ptr(budgets, "budgets"));
+  } else if (k < 1 || k > kmax) {
+    return fail(USV_ERR_INVALID_ARG, "k (%d) must be in [1, kmax = %d]", k, kmax);
+  }
+  return hip_result(usv::launch_select_topk(scores, s, k, budgets, kmax, idx, cnt, static_cast<hipStream_t>(stream)),
+                    "usv_select_topk launch");
+}
+
+usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v, const usv_shape* shape,
+                                 const int32_t* idx, const int32_t* cnt, int32_t kmax, float scale,
+                                 int32_t out_dtype, void* out, float* lse, void* stream) {
+  usv::Dims s;
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_ptr(q, "q"));
+  USV_TRY(check_ptr(k, "k"));
+  USV_TRY(check_ptr(v, "v"));
+  USV_TRY(check_ptr(idx, "idx"));
+  USV_TRY(check_ptr(cnt, "cnt"));
+  USV_TRY(check_ptr(out, "out"));
+  if (lse && !aligned16(lse)) return fail(USV_ERR_INVALID_ARG, "lse is not 16-byte aligned");
+  if (kmax < 1 || kmax > s.nb) return fail(USV_ERR_INVALID_ARG, "kmax (%d) must be in [1, blocks = %d]", kmax, s.nb);
+  if (out_dtype != shape->dtype && !(s.bf16 && out_dtype == USV_F32))
+    return fail(USV_ERR_UNSUPPORTED, "out_dtype must equal the input dtype, or be USV_F32 for bf16 inputs");
+  if (std::isnan(scale) || std::isinf(scale)) return fail(USV_ERR_INVALID_ARG, "scale must be finite");
+  if (scale <= 0.f) scale = 1.0f / std::sqrt((float)s.d);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const hipError_t e =
+      s.bf16 ? usv::launch_attn_bf16(q, k, v, s, idx, cnt, kmax, scale, out, out_dtype == USV_F32, lse, st)
+             : usv::launch_attn_f32(static_cast<const float*>(q), static_cast<const float*>(k),
+                                    static_cast<const float*>(v), s, idx, cnt, kmax, scale, static_cast<float*>(out),
+                                    lse, st);
+  return hip_result(e, "usv_block_sparse_attn launch");
+}
+
+const char* usv_status_string(int32_t status) {
+  switch (status) {
+    case USV_OK: return "USV_OK";
+    case USV_ERR_INVALID_ARG: return "USV_ERR_INVALID_ARG";
+    case USV_ERR_UNSUPPORTED: return "USV_ERR_UNSUPPORTED";
+    case USV_ERR_WORKSPACE: return "USV_ERR_WORKSPACE";
+    case USV_ERR_HIP: return "USV_ERR_HIP";
+    default: return "USV_ERR_UNKNOWN";
+  }
+}
+
+const char* usv_last_error(void) { return g_err; }
+
+}  // extern "C"

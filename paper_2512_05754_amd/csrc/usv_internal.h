@@ -1,0 +1,41 @@
+// Internal declarations shared by the HIP sources of libusv (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "usv.h"
+
+namespace usv {
+
+constexpr int kBlock = 64;        // tokens per cube
+constexpr int kNumXcd = 8;        // MI355X: 8 accelerator dies, each with its own L2
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct Dims {
+  int B, Hh, N, Nv, d, nb, nb_valid;
+  bool bf16;
+  long long bh() const { return (long long)B * Hh; }
+};
+
+// Workgroups are dealt round-robin to the 8 XCDs.  Map the hardware block id to a logical
+// work id so that each XCD walks one contiguous range of work items (consecutive heads and
+// query blocks share K/V in that XCD's L2).  `per_xcd` = ceil(total / 8); ids >= total idle.
+__device__ __forceinline__ int xcd_contiguous_id(int bid, int per_xcd) {
+  return (bid % kNumXcd) * per_xcd + bid / kNumXcd;
+}
+
+// launchers (each returns the hipError_t of its launches)
+hipError_t launch_block_scores(const void* q, const void* k, const Dims& s, float* scores, float* ws,
+                               hipStream_t st);
+hipError_t launch_select_topk(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax,
+                              int32_t* idx, int32_t* cnt, hipStream_t st);
+hipError_t launch_attn_f32(const float* q, const float* k, const float* v, const Dims& s, const int32_t* idx,
+                           const int32_t* cnt, int kmax, float scale, float* out, float* lse, hipStream_t st);
+hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
+                            const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
+                            hipStream_t st);
+
+}  // namespace usv

@@ -1,0 +1,116 @@
+// Stage 2: per-query-block top-k key-block selection ("top-k cube selection", paper Figure 2).
+//
+// One 64-lane wavefront owns one score row.  The row lives in registers (element e*64+lane in
+// slot e), mapped to order-preserving unsigned keys.  The k-th largest key is found by a
+// bit-by-bit search from the most significant bit (each step is a compare + wave-wide count),
+// which makes the result a pure function of the (key, index) total order: bit-exact and free of
+// atomics.  Ties at the threshold are broken towards the lower block index with ballot prefix
+// counts, and the survivors are written in ascending block index in one more pass.
+#include "usv_internal.h"
+
+namespace usv {
+namespace {
+
+constexpr int kRowsPerWg = 4;  // 4 wavefronts, one row each
+
+// Order-preserving key of a canonicalised fp32: -0 == +0, NaN below everything (also -inf).
+__device__ __forceinline__ uint32_t order_key(float x) {
+  uint32_t b = __float_as_uint(x);
+  if ((b & 0x7fffffffu) > 0x7f800000u) return 0u;  // NaN
+  if (b == 0x80000000u) b = 0u;                    // -0 -> +0
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__device__ __forceinline__ int wave_count(bool p) { return __popcll(__ballot(p)); }
+
+template <int EPL>  // elements per lane: row length <= 64 * EPL
+__global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __restrict__ scores,
+                                                               const int32_t* __restrict__ budgets, int k_uniform,
+                                                               int kmax, int nb, int nb_valid, long long rows,
+                                                               int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+  const int lane = threadIdx.x & 63;
+  const long long row = (long long)blockIdx.x * kRowsPerWg + (threadIdx.x >> 6);
+  if (row >= rows) return;  // whole wavefront leaves together; no barriers in this kernel
+  const int i = (int)(row % nb);
+  int32_t* out = idx + row * kmax;
+
+  int want = budgets ? budgets[row] : k_uniform;
+  want = max(0, min(want, min(kmax, nb_valid)));
+  if (i >= nb_valid) want = 0;
+
+  if (want > 0) {
+    const float* src = scores + row * nb;
+    uint32_t key[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const int j = e * 64 + lane;
+      // slots beyond the valid blocks get the lowest key; `want <= nb_valid` and the index
+      // tie-break keep them out of the result
+      key[e] = j < nb_valid ? order_key(src[j]) : 0u;
+    }
+    // threshold = the want-th largest key among the valid slots
+    uint32_t thr = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = thr | (1u << bit);
+      int c = 0;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) c += wave_count(e * 64 + lane < nb_valid && key[e] >= cand);
+      if (c >= want) thr = cand;
+    }
+    int greater = 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) greater += wave_count(e * 64 + lane < nb_valid && key[e] > thr);
+    const int need_eq = want - greater;  // >= 1 by construction
+
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    int out_base = 0, eq_base = 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const int j = e * 64 + lane;
+      const bool valid = j < nb_valid;
+      const bool gt = valid && key[e] > thr;
+      const bool eq = valid && key[e] == thr;
+      const unsigned long long eq_b = __ballot(eq);
+      const bool take = gt || (eq && eq_base + __popcll(eq_b & lt_mask) < need_eq);
+      const unsigned long long take_b = __ballot(take);
+      if (take) out[out_base + __popcll(take_b & lt_mask)] = j;
+      out_base += __popcll(take_b);
+      eq_base += __popcll(eq_b);
+    }
+  }
+  for (int s = want + lane; s < kmax; s += 64) out[s] = -1;
+  if (lane == 0) cnt[row] = want;
+}
+
+template <int EPL>
+hipError_t run(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax, int32_t* idx,
+               int32_t* cnt, hipStream_t st) {
+  const long long rows = s.bh() * s.nb;
+  const unsigned grid = (unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg);
+  select_topk<EPL><<<grid, 64 * kRowsPerWg, 0, st>>>(scores, budgets, k, kmax, s.nb, s.nb_valid, rows, idx, cnt);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_select_topk(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax,
+                              int32_t* idx, int32_t* cnt, hipStream_t st) {
+  const int epl = (s.nb + 63) / 64;
+#define USV_TOPK_CASE(E) \
+  if (epl <= E) return run<E>(scores, s, k, budgets, kmax, idx, cnt, st)
+  USV_TOPK_CASE(1);
+  USV_TOPK_CASE(2);
+  USV_TOPK_CASE(4);
+  USV_TOPK_CASE(8);
+  USV_TOPK_CASE(12);
+  USV_TOPK_CASE(16);
+  USV_TOPK_CASE(20);
+  USV_TOPK_CASE(24);
+  USV_TOPK_CASE(32);
+  USV_TOPK_CASE(48);
+  USV_TOPK_CASE(64);
+#undef USV_TOPK_CASE
+  return hipErrorInvalidValue;  // unreachable: the API rejects nb > USV_MAX_BLOCKS
+}
+
+}  // namespace usv

@@ -1,0 +1,236 @@
+"""GPU parity tests: every stage of the HIP path, through the C ABI binding, against the CPU oracle on the
+same seeded inputs.  Sizes here are ones the oracle finishes in seconds and that still span several
+tiles and a ragged tail; the full benchmark shapes are in test_gpu_fullsize.py."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as gu
+from oracle import usv_oracle as orc
+from paper_2512_05754_amd import synth
+from paper_2512_05754_amd.synth import Workload
+
+pytestmark = pytest.mark.gpu
+
+
+def small_workloads():
+    return [
+        synth.TINY,
+        Workload("f32_d128_ragged", 1, 2, 5 * 64 - 17, 128, "f32", 2.0, 2, seed=11),
+        Workload("bf16_d128_ragged", 2, 3, 9 * 64 - 9, 128, "bf16", 2.0, 4, seed=12),
+        Workload("bf16_d64", 1, 2, 6 * 64, 64, "bf16", 2.0, 3, seed=13),
+        Workload("bf16_d64_ragged", 1, 1, 6 * 64 - 40, 64, "bf16", 1.0, 5, seed=14),
+        Workload("bf16_d128_70blocks", 1, 1, 70 * 64 - 1, 128, "bf16", 2.0, 7, seed=15),
+    ]
+
+
+@pytest.mark.parametrize("w", small_workloads(), ids=lambda w: w.name)
+def test_block_scores(usv, w):
+    Q, K, _ = synth.gen_qkv(w)
+    S = usv.block_scores(gu.up(Q), gu.up(K), seq_valid=w.seq_valid)
+    ref = orc.block_scores(synth.as_f32(Q), synth.as_f32(K), w.seq_valid)
+    gu.assert_f32_close(gu.down(S), ref, w.name)
+
+
+def test_block_scores_fully_padded_blocks(usv):
+    w = Workload("pad2", 1, 1, 3 * 64 + 5, 64, "bf16", 2.0, 1, seed=3)
+    Q, K, _ = synth.gen_qkv(w)
+    # give the call two extra, fully padded blocks
+    pad = np.full((1, 1, 128, 64), synth.f32_to_bf16_bits(np.float32(synth.PAD_SENTINEL)), dtype=np.uint16)
+    Q, K = np.concatenate([Q, pad], axis=2), np.concatenate([K, pad], axis=2)
+    S = gu.down(usv.block_scores(gu.up(Q), gu.up(K), seq_valid=w.seq_valid))
+    ref = orc.block_scores(synth.as_f32(Q), synth.as_f32(K), w.seq_valid)
+    assert np.isneginf(S[0, 0, 4:, :]).all() and np.isneginf(S[0, 0, :, 4:]).all()
+    gu.assert_f32_close(S, ref)
+
+
+# --------------------------------------------------------------------------- #
+def check_topk(usv, S, k, seq_valid, budgets=None, kmax=None):
+    idx, cnt = usv.select_topk(gu.up(S), k=k, seq_valid=seq_valid,
+                               budgets=None if budgets is None else gu.up(budgets), kmax=kmax)
+    ridx, rcnt = orc.select_topk(S, k, seq_valid, budgets=budgets, kmax=kmax)
+    assert np.array_equal(gu.down(cnt), rcnt)
+    assert np.array_equal(gu.down(idx), ridx)  # bit-exact, including the -1 padding
+
+
+@pytest.mark.parametrize("nb,k", [(16, 4), (16, 1), (16, 16), (64, 7), (65, 64), (100, 37), (512, 51), (512, 512),
+                                  (512, 256), (1182, 59), (300, 1)])
+def test_topk_random(usv, nb, k):
+    rng = np.random.default_rng(nb * 1000 + k)
+    rows = 2 if nb > 600 else 3
+    S = rng.standard_normal((1, rows, nb, nb)).astype(np.float32) * 4
+    check_topk(usv, S, k, nb * 64)
+
+
+def test_topk_ties_and_special_values(usv):
+    nb = 128
+    rng = np.random.default_rng(5)
+    S = np.round(rng.standard_normal((1, 2, nb, nb)) * 2).astype(np.float32)  # heavy duplicates
+    S[0, 0, 0, :] = 0.0  # all equal
+    S[0, 0, 1, :] = np.where(rng.random(nb) < 0.5, -0.0, 0.0)  # signed zeros
+    S[0, 0, 2, ::3] = -np.inf
+    S[0, 0, 3, ::2] = np.nan
+    S[0, 0, 4, :] = np.nan
+    S[0, 0, 5, :] = -np.inf
+    S[0, 0, 6, :] = np.inf
+    S[0, 0, 7, :] = np.concatenate([np.full(nb - 3, np.nan), [-np.inf, 1.0, np.nan]])
+    S[0, 0, 8, :] = np.float32(1e-40) * rng.integers(-3, 4, nb)  # denormals around zero
+    for k in (1, 2, 40, 64, 127, 128):
+        check_topk(usv, S, k, nb * 64)
+    check_topk(usv, S, 40, nb * 64 - 64 * 3 - 5)  # only 125 candidate blocks, partial last one
+
+
+def test_topk_ragged_budgets(usv):
+    nb, kmax = 256, 64
+    rng = np.random.default_rng(9)
+    S = rng.standard_normal((2, 2, nb, nb)).astype(np.float32)
+    budgets = rng.integers(8, 65, size=(2, 2, nb), dtype=np.int32)
+    budgets[0, 0, :6] = [0, -3, 1, 64, 65, 1000]
+    check_topk(usv, S, 0, nb * 64, budgets=budgets, kmax=kmax)
+    check_topk(usv, S, 0, nb * 64 - 100, budgets=budgets, kmax=kmax)
+
+
+# --------------------------------------------------------------------------- #
+def run_pipeline(usv, w, out_dtype=None, budgets=None):
+    Q, K, V = synth.gen_qkv(w)
+    q, k, v = gu.up(Q), gu.up(K), gu.up(V)
+    S = usv.block_scores(q, k, seq_valid=w.seq_valid)
+    idx, cnt = usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, kmax=w.kmax,
+                               budgets=None if budgets is None else gu.up(budgets))
+    out, lse = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, return_lse=True, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    return (Q, K, V), gu.down(S), gu.down(idx), gu.down(cnt), out, gu.down(lse)
+
+
+@pytest.mark.parametrize("w", small_workloads(), ids=lambda w: w.name)
+def test_pipeline_against_oracle(usv, w):
+    """scores -> top-k -> attention; the oracle selects from the SAME fp32 scores the GPU produced."""
+    (Q, K, V), S, idx, cnt, out, lse = run_pipeline(usv, w, out_dtype=torch.float32)
+    ridx, rcnt = orc.select_topk(S, w.keep, w.seq_valid)
+    assert np.array_equal(idx, ridx) and np.array_equal(cnt, rcnt)
+    O, L = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), ridx, rcnt, w.seq_valid)
+    gu.assert_attn_close(gu.down(out), O, w.dtype, False, w.name)
+    live = np.isfinite(L)
+    assert np.array_equal(np.isneginf(lse), ~live)
+    assert np.abs(lse[live] - L[live]).max() <= (1e-4 if w.dtype == "f32" else 2e-2)
+    assert (gu.down(out)[..., w.seq_valid:, :] == 0).all()
+
+
+@pytest.mark.parametrize("w", [x for x in small_workloads() if x.dtype == "bf16"], ids=lambda w: w.name)
+def test_bf16_output_storage(usv, w):
+    (Q, K, V), S, idx, cnt, out, _ = run_pipeline(usv, w)
+    assert out.dtype == torch.bfloat16
+    O, _ = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), idx, cnt, w.seq_valid)
+    gu.assert_attn_close(gu.down(out), O, w.dtype, True, w.name)
+
+
+def arbitrary_lists(w, rng, kmax):
+    nbv = (w.seq_valid + 63) // 64
+    idx = np.full((w.batch, w.heads, w.nb, kmax), -1, dtype=np.int32)
+    cnt = np.zeros((w.batch, w.heads, w.nb), dtype=np.int32)
+    for b in range(w.batch):
+        for h in range(w.heads):
+            for i in range(w.nb):
+                c = int(rng.integers(0, min(kmax, nbv) + 1))
+                idx[b, h, i, :c] = rng.choice(nbv, size=c, replace=False)  # unsorted on purpose
+                cnt[b, h, i] = c
+    return idx, cnt
+
+
+@pytest.mark.parametrize("w", [small_workloads()[1], small_workloads()[2], small_workloads()[4]], ids=lambda w: w.name)
+def test_attention_with_arbitrary_lists(usv, w):
+    """Static / caller-made lists: unsorted, ragged, some empty, some holding only the partial block."""
+    rng = np.random.default_rng(21)
+    Q, K, V = synth.gen_qkv(w)
+    idx, cnt = arbitrary_lists(w, rng, 5)
+    nbv = (w.seq_valid + 63) // 64
+    idx[0, 0, 0, 0], cnt[0, 0, 0] = nbv - 1, 1  # only the partial block
+    cnt[0, 0, 1] = 0
+    out, lse = usv.block_sparse_attn(gu.up(Q), gu.up(K), gu.up(V), gu.up(idx), gu.up(cnt), seq_valid=w.seq_valid,
+                                     return_lse=True, out_dtype=torch.float32)
+    O, L = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), idx, cnt, w.seq_valid)
+    gu.assert_attn_close(gu.down(out), O, w.dtype, False, w.name)
+    assert (gu.down(out)[0, 0, 64:128] == 0).all() and np.isneginf(gu.down(lse)[0, 0, 64:128]).all()
+    # a custom softmax scale
+    out2 = usv.block_sparse_attn(gu.up(Q), gu.up(K), gu.up(V), gu.up(idx), gu.up(cnt), seq_valid=w.seq_valid,
+                                 scale=0.05, out_dtype=torch.float32)
+    O2, _ = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), idx, cnt, w.seq_valid, scale=0.05)
+    gu.assert_attn_close(gu.down(out2), O2, w.dtype, False, w.name + " scale")
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64)])
+def test_keep_all_equals_dense_attention(usv, dtype, d):
+    w = Workload("dense", 1, 2, 6 * 64 - 5, d, dtype, 1.0, 6, seed=31)
+    Q, K, V = synth.gen_qkv(w)
+    idx = np.tile(np.arange(6, dtype=np.int32), (1, 2, 6, 1))
+    cnt = np.full((1, 2, 6), 6, dtype=np.int32)
+    out = usv.block_sparse_attn(gu.up(Q), gu.up(K), gu.up(V), gu.up(idx), gu.up(cnt), seq_valid=w.seq_valid,
+                                out_dtype=torch.float32)
+    Nv = w.seq_valid
+    for h in range(2):
+        q, k, v = (synth.as_f32(x[0, h, :Nv]) for x in (Q, K, V))
+        O, _ = orc.dense_attn(q, k, v)
+        gu.assert_attn_close(gu.down(out)[0, h, :Nv], O, dtype, False, "dense")
+
+
+def test_online_softmax_survives_large_logit_offsets(usv):
+    """Keys shifted by a large common vector: every logit of a row moves by the same amount."""
+    w = Workload("shift", 1, 1, 8 * 64, 128, "bf16", 0.0, 8, seed=41)
+    Q, K, V = synth.gen_qkv(w)
+    Kf = synth.as_f32(K) + np.float32(6.0)  # logits shift by 6*sum(q)/sqrt(d): tens to hundreds
+    K = synth.f32_to_bf16_bits(Kf)
+    idx = np.tile(np.arange(8, dtype=np.int32)[::-1], (1, 1, 8, 1)).copy()
+    cnt = np.full((1, 1, 8), 8, dtype=np.int32)
+    out = usv.block_sparse_attn(gu.up(Q), gu.up(K), gu.up(V), gu.up(idx), gu.up(cnt), out_dtype=torch.float32)
+    O, _ = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), idx, cnt, w.seq_valid)
+    gu.assert_attn_close(gu.down(out), O, "bf16", False, "shift")
+
+
+def test_rows_sum_to_one_and_determinism(usv):
+    w = Workload("ones", 1, 2, 10 * 64 - 3, 128, "bf16", 2.0, 4, seed=51)
+    Q, K, V = synth.gen_qkv(w)
+    V1 = np.full_like(V, synth.f32_to_bf16_bits(np.float32(1.0)))
+    q, k = gu.up(Q), gu.up(K)
+    S = usv.block_scores(q, k, seq_valid=w.seq_valid)
+    idx, cnt = usv.select_topk(S, k=4, seq_valid=w.seq_valid)
+    out = gu.down(usv.block_sparse_attn(q, k, gu.up(V1), idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32))
+    np.testing.assert_allclose(out[..., : w.seq_valid, :], 1.0, rtol=0, atol=1e-5)
+    a = usv.block_sparse_attn(q, k, gu.up(V), idx, cnt, seq_valid=w.seq_valid)
+    b = usv.block_sparse_attn(q, k, gu.up(V), idx, cnt, seq_valid=w.seq_valid)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    S2 = usv.block_scores(q, k, seq_valid=w.seq_valid)
+    assert torch.equal(S, S2)
+
+
+def test_outputs_do_not_spill_past_their_buffers(usv):
+    """Canaries around scores, idx and out stay intact."""
+    w = Workload("canary", 1, 2, 5 * 64 - 1, 128, "bf16", 2.0, 3, seed=61)
+    Q, K, V = synth.gen_qkv(w)
+    q, k, v = gu.up(Q), gu.up(K), gu.up(V)
+    nb = w.nb
+
+    def guarded(numel, dtype, fill):
+        buf = torch.full((numel + 512,), fill, dtype=dtype, device=gu.DEV)
+        return buf, buf[256:256 + numel]
+
+    sbuf, s = guarded(2 * nb * nb, torch.float32, 777.0)
+    ibuf, ix = guarded(2 * nb * 3, torch.int32, 777)
+    cbuf, ct = guarded(2 * nb, torch.int32, 777)
+    obuf, o = guarded(q.numel(), torch.float32, 777.0)
+    S = usv.block_scores(q, k, seq_valid=w.seq_valid, out=s.view(1, 2, nb, nb))
+    idx, cnt = usv.select_topk(S, k=3, seq_valid=w.seq_valid, idx=ix.view(1, 2, nb, 3), cnt=ct.view(1, 2, nb))
+    usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=o.view(q.shape))
+    torch.cuda.synchronize()
+    for buf in (sbuf, ibuf, cbuf, obuf):
+        assert (buf[:256] == 777).all() and (buf[-256:] == 777).all()
+    assert not (o == 777).any()
+
+
+def test_errors_surface_as_exceptions(usv):
+    x = torch.zeros(1, 1, 128, 64, device=gu.DEV)
+    with pytest.raises(usv.UsvError, match="USV_ERR_INVALID_ARG"):
+        usv.select_topk(torch.zeros(1, 1, 2, 2, device=gu.DEV), k=3)
+    with pytest.raises(usv.UsvError, match="USV_ERR_UNSUPPORTED"):
+        usv.block_scores(torch.zeros(1, 1, 128, 96, device=gu.DEV), torch.zeros(1, 1, 128, 96, device=gu.DEV))
+    with pytest.raises(usv.UsvError, match="USV_ERR_WORKSPACE"):
+        usv.block_scores(x, x, workspace=torch.zeros(16, dtype=torch.uint8, device=gu.DEV))

@@ -1,0 +1,97 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header declares,
+and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_05754_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000  # aligned, non-null; never dereferenced because validation fails first
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "usv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(usv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTED_SYMBOLS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def shape(**kw):
+    base = dict(batch=1, heads=2, seq_len=1024, seq_valid=1024, head_dim=64, block=64, dtype=binding.USV_F32)
+    base.update(kw)
+    return binding.UsvShape(**base)
+
+
+def test_workspace_bytes():
+    L = binding.lib()
+    assert L.usv_workspace_bytes(ctypes.byref(shape())) == 2 * 2 * 16 * 64 * 4
+    assert L.usv_workspace_bytes(ctypes.byref(shape(block=32))) == 0
+    assert L.usv_workspace_bytes(None) == 0
+    assert binding.workspace_bytes(1, 12, 32768, 32760, 128, "bf16") == 2 * 12 * 512 * 128 * 4
+
+
+@pytest.mark.parametrize(
+    "kw,status",
+    [
+        (dict(block=32), "USV_ERR_UNSUPPORTED"),
+        (dict(head_dim=96), "USV_ERR_UNSUPPORTED"),
+        (dict(dtype=7), "USV_ERR_UNSUPPORTED"),
+        (dict(seq_len=1000), "USV_ERR_INVALID_ARG"),
+        (dict(seq_valid=0), "USV_ERR_INVALID_ARG"),
+        (dict(seq_valid=1025), "USV_ERR_INVALID_ARG"),
+        (dict(batch=0), "USV_ERR_INVALID_ARG"),
+        (dict(seq_len=64 * 4097, seq_valid=64), "USV_ERR_UNSUPPORTED"),
+    ],
+)
+def test_bad_shapes_are_rejected_before_launch(kw, status):
+    L = binding.lib()
+    sh = shape(**kw)
+    st = L.usv_block_scores(FAKE, FAKE, ctypes.byref(sh), FAKE, FAKE, 1 << 30, None)
+    assert L.usv_status_string(st).decode() == status
+    assert L.usv_last_error().decode() != ""
+    st = L.usv_block_sparse_attn(FAKE, FAKE, FAKE, ctypes.byref(sh), FAKE, FAKE, 4, 0.0, sh.dtype, FAKE, None, None)
+    assert L.usv_status_string(st).decode() == status
+
+
+def test_bad_pointers_workspace_and_budgets():
+    L = binding.lib()
+    sh = ctypes.byref(shape())
+    name = lambda st: L.usv_status_string(st).decode()
+    assert name(L.usv_block_scores(None, FAKE, sh, FAKE, FAKE, 1 << 20, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_block_scores(FAKE + 4, FAKE, sh, FAKE, FAKE, 1 << 20, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_block_scores(FAKE, FAKE, sh, FAKE, FAKE, 100, None)) == "USV_ERR_WORKSPACE"
+    assert name(L.usv_block_scores(FAKE, FAKE, sh, FAKE, None, 1 << 20, None)) == "USV_ERR_WORKSPACE"
+    assert "bytes" in L.usv_last_error().decode()
+    # top-k: k and kmax ranges
+    assert name(L.usv_select_topk(FAKE, sh, 0, None, 4, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_select_topk(FAKE, sh, 5, None, 4, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_select_topk(FAKE, sh, 4, None, 17, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_select_topk(FAKE, sh, 4, None, 0, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_select_topk(None, sh, 4, None, 4, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    # attention: kmax, scale, out_dtype
+    a = lambda kmax, scale, od: name(
+        L.usv_block_sparse_attn(FAKE, FAKE, FAKE, sh, FAKE, FAKE, kmax, scale, od, FAKE, None, None)
+    )
+    assert a(0, 0.0, 0) == "USV_ERR_INVALID_ARG"
+    assert a(17, 0.0, 0) == "USV_ERR_INVALID_ARG"
+    assert a(4, float("nan"), 0) == "USV_ERR_INVALID_ARG"
+    assert a(4, 0.0, binding.USV_BF16) == "USV_ERR_UNSUPPORTED"  # fp32 inputs cannot produce bf16 output
+    assert L.usv_status_string(99).decode() == "USV_ERR_UNKNOWN"
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    x = torch.zeros(1, 1, 64, 64)
+    with pytest.raises(TypeError, match="GPU tensor"):
+        binding.block_scores(x, x)
