@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-sparse video attention hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic Wan2.1-1.3B 480p attention layer
+(usv_block_scores -> usv_select_topk -> usv_block_sparse_attn, 10 % of the key blocks kept),
+with Q/K/V already resident in HBM.  Prints ONE JSON line:
+  value        effective TFLOP/s of a step, counting only the computed 64x64 tiles (4*64*64*d flop each)
+  ms_per_step  milliseconds per step (the three calls back to back)
+  roofline     the attention kernel against the bf16 MFMA peak, timed with events on the launch stream
+  cpu_baseline the fp64 CPU oracle on a bounded sample of the same workload (context, not the target)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "ms/call + effective TFLOP/s (computed tiles) of sparse attn, Wan-1.3B 480p, 10% keep"
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="wan13_480p",
+                    choices=["wan13_480p", "wan14_720p", "merged_ragged", "tiny",
+                             "sweep100", "sweep50", "sweep25", "sweep10", "sweep5"])
+    ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage type of the attention output (inputs are the workload's dtype)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-heads", type=int, default=12)
+    return ap.parse_args()
+
+
+def pick_workload(name):
+    from paper_2512_05754_amd import synth
+
+    table = {"wan13_480p": synth.WAN13_480P, "wan14_720p": synth.WAN14_720P,
+             "merged_ragged": synth.MERGED_RAGGED, "tiny": synth.TINY}
+    if name in table:
+        return table[name]
+    return synth.sweep(int(name[len("sweep"):]) / 100.0)
+
+
+def cpu_baseline(w, Q, K, V, n_heads):
+    """Times the oracle (all three stages) on the first n_heads heads of batch 0."""
+    import numpy as np
+
+    from oracle import usv_oracle as orc
+    from paper_2512_05754_amd import synth
+
+    try:
+        from threadpoolctl import threadpool_info
+
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    n_heads = min(n_heads, w.heads)
+    Qf, Kf, Vf = (synth.as_f32(x[:1, :n_heads]) for x in (Q, K, V))
+    budgets = synth.gen_budgets(w)[:1, :n_heads] if not w.keep else None
+    t0 = time.perf_counter()
+    S = orc.block_scores(Qf, Kf, w.seq_valid)
+    idx, cnt = orc.select_topk(S, w.keep, w.seq_valid, budgets=budgets, kmax=w.kmax)
+    orc.block_sparse_attn(Qf, Kf, Vf, idx, cnt, w.seq_valid)
+    dt = time.perf_counter() - t0
+    tiles = int(cnt.sum())
+    flop = tiles * 4.0 * 64 * 64 * w.head_dim
+    return {
+        "value": flop / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{n_heads} of {w.batch * w.heads} heads (all {w.nb} query blocks each, {tiles} tiles), "
+                  f"3 stages, numpy fp64, {dt:.2f} s; host has {len(os.sched_getaffinity(0))} usable cores",
+        "seconds": dt,
+        "ms_per_call_extrapolated": dt * 1e3 * (w.batch * w.heads) / n_heads,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2512_05754_amd as usv
+    from paper_2512_05754_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = pick_workload(args.workload)
+
+    Q, K, V = synth.gen_qkv(w)
+
+    def up(x):
+        if x.dtype == np.uint16:
+            return torch.from_numpy(x.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(x).to(dev)
+
+    q, k, v = up(Q), up(K), up(V)
+    budgets = None if w.keep else torch.from_numpy(synth.gen_budgets(w)).to(dev)
+    out_dtype = torch.float32 if (args.out_dtype == "f32" or w.dtype == "f32") else torch.bfloat16
+
+    # every buffer is allocated once, outside the timed region
+    B, Hh, N, d, nb, kmax = w.batch, w.heads, w.seq_len, w.head_dim, w.nb, w.kmax
+    S = torch.empty((B, Hh, nb, nb), dtype=torch.float32, device=dev)
+    ws = torch.empty(usv.workspace_bytes(B, Hh, N, w.seq_valid, d, w.dtype), dtype=torch.uint8, device=dev)
+    idx = torch.empty((B, Hh, nb, kmax), dtype=torch.int32, device=dev)
+    cnt = torch.empty((B, Hh, nb), dtype=torch.int32, device=dev)
+    out = torch.empty((B, Hh, N, d), dtype=out_dtype, device=dev)
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        usv.block_scores(q, k, seq_valid=w.seq_valid, out=S, workspace=ws)
+        if events is not None:
+            events[1].record()
+        usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, budgets=budgets, kmax=kmax, idx=idx, cnt=cnt)
+        if events is not None:
+            events[2].record()
+        usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=out)
+        if events is not None:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly --steps passes; per-stage events are recorded on the launch stream
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_step = wall * 1e3 / args.steps
+    st_ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in evs])  # [steps, 3]
+    avg = st_ms.mean(axis=0)
+    tiles = int(cnt.sum().item())
+    flop = tiles * 4.0 * 64 * 64 * d
+    esz = 2 if w.dtype == "bf16" else 4
+    bytes_scores = 2 * B * Hh * N * d * esz + B * Hh * nb * nb * 4
+    bytes_topk = B * Hh * nb * nb * 4 + B * Hh * nb * (kmax + 1) * 4
+
+    result = {
+        "metric": METRIC,
+        "value": flop / (ms_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "batch": B, "heads": Hh, "head_dim": d, "seq_len": N, "seq_valid": w.seq_valid,
+            "block": 64, "blocks": nb, "keep": w.keep if w.keep else f"U[{w.budget_lo},{w.budget_hi}]",
+            "computed_tiles": tiles, "flop_per_step": flop, "out_dtype": args.out_dtype if w.dtype == "bf16" else "f32",
+            "step": "usv_block_scores + usv_select_topk + usv_block_sparse_attn",
+        },
+        "stages_ms": {"block_scores": float(avg[0]), "select_topk": float(avg[1]), "block_sparse_attn": float(avg[2])},
+        "attn_ms_min": float(st_ms[:, 2].min()),
+        "attn_tflops": flop / (avg[2] * 1e-3) / 1e12,
+        "stage_hbm_gbs": {"block_scores": bytes_scores / (avg[0] * 1e-3) / 1e9,
+                          "select_topk": bytes_topk / (avg[1] * 1e-3) / 1e9},
+        "roofline": {
+            "kernel": "usv_block_sparse_attn (attn_bf16)" if w.dtype == "bf16" else "usv_block_sparse_attn (attn_f32)",
+            "bound": "mfma" if w.dtype == "bf16" else "alu",
+            "achieved": flop / (avg[2] * 1e-3) / 1e12,
+            "peak": PEAK_BF16_TFLOPS if w.dtype == "bf16" else 157.3,
+            "unit": "TFLOP/s",
+            "frac": flop / (avg[2] * 1e-3) / 1e12 / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else 157.3),
+            "traffic": None,
+            "avg_launch_ms": float(avg[2]),
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, Q, K, V, args.cpu_sample_heads)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
