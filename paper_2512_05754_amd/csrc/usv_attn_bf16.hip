@@ -16,8 +16,12 @@
 // order as long as both operands agree, so V^T is read in the order the accumulator holds keys).
 // V^T fragments come from the row-major V tile with the LDS transpose read ds_read_b64_tr_b16.
 //
-// LDS: double-buffered K and V tiles (2 x 2 x 64 x D bf16), 16-byte chunks XOR-swizzled so that
-// both the 16-byte K fragment reads and the transposing V reads spread over all banks.
+// Data movement: K/V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no
+// register staging), double-buffered; the 16-byte chunks of a row are XOR-permuted on the way in
+// (the permutation is applied to the global address, the LDS side of the DMA is lane-linear) so
+// that both the 16-byte K fragment reads and the transposing V reads are bank-conflict free.
+// Softmax: log2 domain, the running max is only raised when a row's tile max exceeds it by more
+// than kRescaleSlack (so P stays below 2^slack and the O rescale is skipped on most tiles).
 #include "usv_internal.h"
 
 namespace usv {
@@ -25,17 +29,21 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kThreads = 256;
+constexpr float kRescaleSlack = 8.0f;  // log2 units
 
 template <int D>
 struct Tile {
   static constexpr int kChunks = D / 8;           // 16-byte chunks per row
   static constexpr int kRowBytes = D * 2;
   static constexpr int kBytes = kBlock * D * 2;   // one K or V tile
-  static constexpr int kLoads = kBlock * kChunks / kThreads;  // 16-byte loads per thread per tile
+  static constexpr int kDmaPerWave = kBytes / 1024 / 4;  // 1 KiB DMA instructions per wave per tile
+  static constexpr int kRowsPerDma = 1024 / kRowBytes;
   // K: lanes 0..15 of a fragment read hit 16 consecutive rows at one chunk column.
   __device__ static int k_swz(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
   // V: a transposing read touches 8 consecutive rows x 4 consecutive chunks.
@@ -47,9 +55,26 @@ struct Tile {
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }  // lane ^ 32
 
-__device__ __forceinline__ float other_half(float x) {  // value held by lane ^ 32
-  return __shfl_xor(x, 32);
+// 16 bytes per lane, global -> LDS: lane reads gbase + voff (bytes) and the 64 lanes land at
+// lds_addr + 16 * lane.  Written as inline assembly so that the compiler does not pair the DMA with
+// a conservative "wait for all memory" before the next LDS read of the OTHER buffer; completion is
+// awaited explicitly (vmcnt) where the pipeline needs it.  M0 carries the LDS address and is
+// restored, since the compiler does not expect it to change.
+__device__ __forceinline__ void dma16(const void* gbase, unsigned voff, unsigned lds_addr) {
+  unsigned saved;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %1\n\t"
+      "global_load_lds_dwordx4 %2, %3\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved)
+      : "s"(lds_addr), "v"(voff), "s"(gbase)
+      : "memory");
+}
+__device__ __forceinline__ unsigned lds_address(const void* p) {  // LDS byte address of a __shared__ pointer
+  return (unsigned)(uintptr_t)p;
 }
 
 template <int D, bool OUT_F32>
@@ -64,7 +89,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
   using T = Tile<D>;
   constexpr int KSTEPS = D / 16;  // MFMA k-steps of the QK^T product
   constexpr int DSUB = D / 32;    // 32-wide d sub-tiles of the output
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * T::kBytes];
+  constexpr int XROWS = DSUB * 16 + 2;            // exchange rows per wave: O registers, m, l
+  constexpr int OSTRIDE = D + 4;                  // fp32 staging row stride (floats), bank-spread
+  constexpr int kXchBytes = 2 * XROWS * 64 * 4;
+  constexpr int kStageBytes = kBlock * OSTRIDE * 4;
+  constexpr int kSmem = (4 * T::kBytes > kXchBytes + kStageBytes) ? 4 * T::kBytes : kXchBytes + kStageBytes;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kSmem];
   unsigned char* const Kbuf = smem;                  // [2][kBytes]
   unsigned char* const Vbuf = smem + 2 * T::kBytes;  // [2][kBytes]
 
@@ -74,11 +104,38 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
   const long long head = work / nb;
   const long long head_off = head * (long long)nb * kBlock * D;
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction; keep it scalar
   const int qh = wave & 1, kh = wave >> 1;
   const int col = lane & 31, g = lane >> 5;
   const int n_list = cnt[work];
   const int32_t* list = idx + (long long)work * kmax;
+  const uint16_t* kbase = k + head_off;
+  const uint16_t* vbase = v + head_off;
+
+  // DMA plan of this wave: instruction `it` fills LDS bytes [a*1024, a*1024+1024) of a tile,
+  // a = wave*kDmaPerWave + it; lane -> (row, stored chunk position p); it fetches global chunk
+  // p ^ swz(row) of that row.  Byte offsets inside a tile are loop invariant.
+  int kofs[T::kDmaPerWave], vofs[T::kDmaPerWave];
+#pragma unroll
+  for (int it = 0; it < T::kDmaPerWave; ++it) {
+    const int a = wave * T::kDmaPerWave + it;
+    const int row = a * T::kRowsPerDma + lane / T::kChunks, p = lane % T::kChunks;
+    kofs[it] = (row * D + ((p ^ T::k_swz(row)) << 3)) * 2;  // bytes
+    vofs[it] = (row * D + ((p ^ T::v_swz(row)) << 3)) * 2;
+  }
+  auto prefetch = [&](int j, int buf) {
+    const uint16_t* kp = kbase + (long long)j * kBlock * D;
+    const uint16_t* vp = vbase + (long long)j * kBlock * D;
+#pragma unroll
+    for (int it = 0; it < T::kDmaPerWave; ++it) {
+      const int a = wave * T::kDmaPerWave + it;
+      dma16(kp, kofs[it], lds_address(Kbuf) + buf * T::kBytes + a * 1024);
+      dma16(vp, vofs[it], lds_address(Vbuf) + buf * T::kBytes + a * 1024);
+    }
+  };
+
+  if (n_list > 0) prefetch(list[0], 0);
 
   // Q fragments: lane holds query row 32*qh + col, channels 16 t + 8 g .. + 8 for every k-step t
   bf16x8 qf[KSTEPS];
@@ -93,42 +150,41 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
   for (int ds = 0; ds < DSUB; ++ds)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[ds][r] = 0.f;
-  float m = -INFINITY;  // running max of the scaled logits (log2 domain), shared by both lane halves
+  float m = -INFINITY;  // running reference max (log2 domain), identical in both lane halves
   float l = 0.f;        // this lane's partial row sum (its 16 keys per tile)
 
-  // global -> register staging of one K and one V tile (kLoads 16-byte pieces each per thread)
-  uint4 kst[T::kLoads], vst[T::kLoads];
-  auto fetch = [&](int j) {
-    const uint16_t* kp = k + head_off + (long long)j * kBlock * D;
-    const uint16_t* vp = v + head_off + (long long)j * kBlock * D;
+  // per-lane LDS byte offsets of the fragment reads (loop invariant)
+  int kfrag[KSTEPS];
 #pragma unroll
-    for (int it = 0; it < T::kLoads; ++it) {
-      const int id = it * kThreads + tid;
-      kst[it] = *reinterpret_cast<const uint4*>(kp + id * 8);
-      vst[it] = *reinterpret_cast<const uint4*>(vp + id * 8);
-    }
-  };
-  auto stash = [&](int buf) {
+  for (int t = 0; t < KSTEPS; ++t) kfrag[t] = T::k_off(kh * 32 + col, 2 * t + g);
+  int vfrag[DSUB][2][2];
+  {
+    const int l16 = lane & 15;
 #pragma unroll
-    for (int it = 0; it < T::kLoads; ++it) {
-      const int id = it * kThreads + tid;
-      const int row = id / T::kChunks, c = id % T::kChunks;
-      *reinterpret_cast<uint4*>(Kbuf + buf * T::kBytes + T::k_off(row, c)) = kst[it];
-      *reinterpret_cast<uint4*>(Vbuf + buf * T::kBytes + T::v_off(row, c)) = vst[it];
+    for (int ds = 0; ds < DSUB; ++ds) {
+      const int dcol = 32 * ds + 16 * ((lane >> 4) & 1) + 4 * (l16 & 3);  // 4 channels = half a chunk
+      const int chunk = dcol >> 3, half = (dcol >> 2) & 1;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        // slots 0..3: keys 16 t + 4 g + (0..3); slots 4..7: keys 16 t + 8 + 4 g + (0..3) of this wave's half
+        const int key0 = kh * 32 + 16 * t + 4 * g + (l16 >> 2);
+        vfrag[ds][t][0] = T::v_off(key0, chunk) + half * 8;
+        vfrag[ds][t][1] = T::v_off(key0 + 8, chunk) + half * 8;
+      }
     }
-  };
-
-  if (n_list > 0) {
-    fetch(list[0]);
-    stash(0);
   }
+
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): tile 0 (and Q) have landed
+  // pin the Q fragments here: otherwise the compiler sinks their loads into the loop and then waits
+  // for "all outstanding loads" there, which would also wait for the tile prefetch it cannot see
+#pragma unroll
+  for (int t = 0; t < KSTEPS; ++t) asm volatile("" ::"v"(qf[t]));
   __syncthreads();
 
   for (int n = 0; n < n_list; ++n) {
     const int j = list[n];
     const int buf = n & 1;
-    const bool more = n + 1 < n_list;
-    if (more) fetch(list[n + 1]);
+    if (n + 1 < n_list) prefetch(list[n + 1], buf ^ 1);
 
     // ---- S^T = K Q^T over this wave's 32 keys --------------------------------------------
     f32x16 s;
@@ -136,68 +192,63 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
     {
       const unsigned char* kb = Kbuf + buf * T::kBytes;
-      const int krow = kh * 32 + col;
 #pragma unroll
       for (int t = 0; t < KSTEPS; ++t) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb + T::k_off(krow, 2 * t + g));
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb + kfrag[t]);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s, 0, 0, 0);
       }
     }
     // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
     const int nkeys = Nv - j * kBlock;  // valid keys in this tile (>= 64 except in the last block)
     if (nkeys < kBlock) {
+      const int lim = nkeys - (kh * 32 + 4 * g);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = kh * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (key >= nkeys) s[r] = -INFINITY;
-      }
+      for (int r = 0; r < 16; ++r) s[r] = (8 * (r >> 2) + (r & 3)) < lim ? s[r] : -INFINITY;
     }
 
-    // ---- online softmax (log2 domain) -----------------------------------------------------
-    float mx = s[0];
+    // ---- online softmax (log2 domain, lazily raised reference max) -------------------------
+    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-    mx = fmaxf(mx, other_half(mx));
-    const float m_new = fmaxf(m, mx * scale_log2e);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;  // all keys masked so far
-    const float alpha = fast_exp2(m - m_use);
-    m = m_new;
-    float psum = 0.f;
+    for (int r = 4; r < 16; r += 4) mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
+    mx = fmaxf(mx, other_half(mx)) * scale_log2e;
+    if (__any(mx > m + kRescaleSlack)) {  // wave-uniform; always taken on the first live tile
+      const float m_new = fmaxf(m, mx);
+      const float alpha = fast_exp2(m - (m_new == -INFINITY ? 0.f : m_new));  // m = -inf -> 0
+      m = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int ds = 0; ds < DSUB; ++ds)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[ds][r] *= alpha;
+    }
+    const float neg_m = m == -INFINITY ? 0.f : -m;  // every key of this half masked so far
     bf16x8 pf[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const __bf16 p = (__bf16)fast_exp2(fmaf(s[r], scale_log2e, -m_use));
-      // the row sum is taken over the ROUNDED probabilities, the ones P V actually uses, so
-      // that the final division cancels the rounding of a dominant key instead of keeping it
-      psum += (float)p;
-      pf[r >> 3][r & 7] = p;
+    for (int r = 0; r < 16; r += 2) {
+      bf16x2 pp;
+      pp[0] = (__bf16)fast_exp2(fmaf(s[r], scale_log2e, neg_m));
+      pp[1] = (__bf16)fast_exp2(fmaf(s[r + 1], scale_log2e, neg_m));
+      // the row sum is taken over the ROUNDED probabilities, the ones P V actually uses, so that
+      // the final division cancels the rounding of a dominant key instead of keeping it
+      bf16x2 ones;
+      ones[0] = (__bf16)1.0f;
+      ones[1] = (__bf16)1.0f;
+      l = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l, false);
+      pf[r >> 3][r & 7] = pp[0];
+      pf[r >> 3][(r & 7) + 1] = pp[1];
     }
-    l = fmaf(l, alpha, psum);
-#pragma unroll
-    for (int ds = 0; ds < DSUB; ++ds)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[ds][r] *= alpha;
 
     // ---- O^T += V^T P^T ---------------------------------------------------------------------
     {
       const unsigned char* vb = Vbuf + buf * T::kBytes;
-      const int l16 = lane & 15;
 #pragma unroll
       for (int ds = 0; ds < DSUB; ++ds) {
-        // this lane's 16-lane group covers channels dbase .. dbase + 16
-        const int dbase = 32 * ds + 16 * ((lane >> 4) & 1);
-        const int dcol = dbase + 4 * (l16 & 3);       // 4 channels = half a 16-byte chunk
-        const int chunk = dcol >> 3, half = (dcol >> 2) & 1;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          // keys 16 t + 4 g + (0..3) and 16 t + 8 + 4 g + (0..3) of this wave's half
-          const int key0 = kh * 32 + 16 * t + 4 * g + (l16 >> 2);
-          const int key1 = key0 + 8;
           const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (short4v __attribute__((address_space(3)))*)(vb + T::v_off(key0, chunk) + half * 8));
+              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][0]));
           const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (short4v __attribute__((address_space(3)))*)(vb + T::v_off(key1, chunk) + half * 8));
-          typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
+              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][1]));
           const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           bf16x8 vf;
           __builtin_memcpy(&vf, &both, sizeof(vf));
@@ -206,15 +257,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
       }
     }
 
-    if (more) stash(buf ^ 1);
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's share of tile n+1 is in LDS
+    __syncthreads();                      // everyone's share is, and tile n is no longer read
   }
 
-  // ---- merge the two key halves and write out --------------------------------------------
-  // (the last loop iteration ended with a barrier, so the tile buffers are free to reuse)
+  // ---- merge the two key halves, stage the block row-major in LDS, store coalesced ----------
+  // (the loop ended with a barrier, so the tile buffers are free)
   const float l_row = l + other_half(l);
-  float* xch = reinterpret_cast<float*>(smem);  // [2 qh][DSUB*16 + 2][64 lanes]
-  constexpr int XROWS = DSUB * 16 + 2;
+  float* xch = reinterpret_cast<float*>(smem);                 // [2 qh][XROWS][64 lanes]
+  float* stage = reinterpret_cast<float*>(smem + kXchBytes);   // [64 rows][OSTRIDE]
   if (kh == 1) {
     float* dst = xch + (qh * XROWS) * 64 + lane;
 #pragma unroll
@@ -229,40 +280,48 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
     const float* src = xch + (qh * XROWS) * 64 + lane;
     const float m1 = src[(DSUB * 16) * 64], l1 = src[(DSUB * 16 + 1) * 64];
     const float mm = fmaxf(m, m1);
-    const float m_use = mm == -INFINITY ? 0.f : mm;
-    const float a0 = fast_exp2(m - m_use), a1 = fast_exp2(m1 - m_use);
+    const float m_ref = mm == -INFINITY ? 0.f : mm;
+    const float a0 = fast_exp2(m - m_ref), a1 = fast_exp2(m1 - m_ref);
     const float lt = l_row * a0 + l1 * a1;
-    const int token = i * kBlock + qh * 32 + col;
+    const int row = qh * 32 + col;
+    const int token = i * kBlock + row;
     const bool live = token < Nv && n_list > 0;
     const float inv = live ? 1.f / lt : 0.f;
-    const float w0 = a0 * inv, w1 = a1 * inv;
-    const long long row_off = head_off + (long long)token * D;
+    const float w0 = live ? a0 * inv : 0.f, w1 = live ? a1 * inv : 0.f;
 #pragma unroll
     for (int ds = 0; ds < DSUB; ++ds)
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
-        float val[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = rq * 4 + e;
-          val[e] = live ? o[ds][r] * w0 + src[(ds * 16 + r) * 64] * w1 : 0.f;
-        }
+        float4 val;
         // register r = 4 rq + e is channel 32 ds + 8 rq + 4 g + e
-        const int ch = 32 * ds + 8 * rq + 4 * g;
-        if (OUT_F32) {
-          *reinterpret_cast<float4*>(static_cast<float*>(out) + row_off + ch) =
-              make_float4(val[0], val[1], val[2], val[3]);
-        } else {
-          bf16x4 pk;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) pk[e] = (__bf16)val[e];
-          *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(out) + row_off + ch) = pk;
-        }
+        val.x = o[ds][rq * 4 + 0] * w0 + src[(ds * 16 + rq * 4 + 0) * 64] * w1;
+        val.y = o[ds][rq * 4 + 1] * w0 + src[(ds * 16 + rq * 4 + 1) * 64] * w1;
+        val.z = o[ds][rq * 4 + 2] * w0 + src[(ds * 16 + rq * 4 + 2) * 64] * w1;
+        val.w = o[ds][rq * 4 + 3] * w0 + src[(ds * 16 + rq * 4 + 3) * 64] * w1;
+        *reinterpret_cast<float4*>(stage + row * OSTRIDE + 32 * ds + 8 * rq + 4 * g) = live ? val : make_float4(0.f, 0.f, 0.f, 0.f);
       }
     if (lse && g == 0) lse[head * (long long)nb * kBlock + token] = live ? (mm + __log2f(lt)) * kLn2 : -INFINITY;
   }
+  __syncthreads();
+  {
+    // 64 rows x D channels, 4 channels per thread per pass, consecutive threads -> consecutive addresses
+    constexpr int PIECES = kBlock * D / 4;
+    const long long blk_off = head_off + (long long)i * kBlock * D;
+#pragma unroll
+    for (int it = 0; it < PIECES / kThreads; ++it) {
+      const int id = it * kThreads + tid;
+      const int row = id / (D / 4), c4 = (id % (D / 4)) * 4;
+      const float4 val = *reinterpret_cast<const float4*>(stage + row * OSTRIDE + c4);
+      if (OUT_F32) {
+        *reinterpret_cast<float4*>(static_cast<float*>(out) + blk_off + row * D + c4) = val;
+      } else {
+        bf16x4 pk;
+        pk[0] = (__bf16)val.x; pk[1] = (__bf16)val.y; pk[2] = (__bf16)val.z; pk[3] = (__bf16)val.w;
+        *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(out) + blk_off + row * D + c4) = pk;
+      }
+    }
+  }
 }
-
 
 template <int D, bool OUT_F32>
 hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx, const int32_t* cnt,
