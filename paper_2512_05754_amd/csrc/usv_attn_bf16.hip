@@ -17,11 +17,17 @@
 // V^T fragments come from the row-major V tile with the LDS transpose read ds_read_b64_tr_b16.
 //
 // Data movement: K/V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no
-// register staging), double-buffered; the 16-byte chunks of a row are XOR-permuted on the way in
-// (the permutation is applied to the global address, the LDS side of the DMA is lane-linear) so
-// that both the 16-byte K fragment reads and the transposing V reads are bank-conflict free.
+// register staging) through a ring of five tile slots that holds K(n), V(n), K(n+1), V(n+1), ...
+// in consumption order.  A slot is refilled as soon as the barrier after its last reader has
+// passed, so every tile is requested about two iterations before it is needed and the CU's
+// 64 B/clk vector-memory path (the second roofline of this kernel: 32 KiB per 64x64 tile) never
+// idles.  The 16-byte chunks of a row are XOR-permuted on the way in (the permutation is applied
+// to the global address, the LDS side of the DMA is lane-linear) so that both the 16-byte K
+// fragment reads and the transposing V reads are bank-conflict free.
 // Softmax: log2 domain, the running max is only raised when a row's tile max exceeds it by more
 // than kRescaleSlack (so P stays below 2^slack and the O rescale is skipped on most tiles).
+#include <type_traits>
+
 #include "usv_internal.h"
 
 namespace usv {
@@ -55,7 +61,20 @@ struct Tile {
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }  // lane ^ 32
+// Lanes l and l ^ 32 hold the two key halves of one query.  v_permlane32_swap on two copies of x
+// leaves (x of the low lane, x of the high lane) in both lanes: one VALU op, no LDS round trip.
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  lo = __uint_as_float(r[0]);
+  hi = __uint_as_float(r[1]);
+}
+// max of three without the NaN-quieting moves the compiler adds around fmaxf (inputs are never NaN)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
 
 // 16 bytes per lane, global -> LDS: lane reads gbase + voff (bytes) and the 64 lanes land at
 // lds_addr + 16 * lane.  Written as inline assembly so that the compiler does not pair the DMA with
@@ -93,10 +112,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
   constexpr int OSTRIDE = D + 4;                  // fp32 staging row stride (floats), bank-spread
   constexpr int kXchBytes = 2 * XROWS * 64 * 4;
   constexpr int kStageBytes = kBlock * OSTRIDE * 4;
-  constexpr int kSmem = (4 * T::kBytes > kXchBytes + kStageBytes) ? 4 * T::kBytes : kXchBytes + kStageBytes;
+  constexpr int kSlots = 5;                       // ring of K/V tile slots
+  constexpr int kDma = T::kDmaPerWave;
+  constexpr int kSmem = (kSlots * T::kBytes > kXchBytes + kStageBytes) ? kSlots * T::kBytes : kXchBytes + kStageBytes;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kSmem];
-  unsigned char* const Kbuf = smem;                  // [2][kBytes]
-  unsigned char* const Vbuf = smem + 2 * T::kBytes;  // [2][kBytes]
 
   const int work = xcd_contiguous_id(blockIdx.x, per_xcd);
   if (work >= total) return;  // whole workgroup leaves before any barrier
@@ -124,18 +143,36 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
     kofs[it] = (row * D + ((p ^ T::k_swz(row)) << 3)) * 2;  // bytes
     vofs[it] = (row * D + ((p ^ T::v_swz(row)) << 3)) * 2;
   }
-  auto prefetch = [&](int j, int buf) {
+  // this wave's quarter of one tile -> ring slot (kDma instructions, counted by vmcnt in issue order)
+  auto issue_k = [&](int j, int slot) {
     const uint16_t* kp = kbase + (long long)j * kBlock * D;
+#pragma unroll
+    for (int it = 0; it < kDma; ++it)
+      dma16(kp, kofs[it], lds_address(smem) + slot * T::kBytes + (wave * kDma + it) * 1024);
+  };
+  auto issue_v = [&](int j, int slot) {
     const uint16_t* vp = vbase + (long long)j * kBlock * D;
 #pragma unroll
-    for (int it = 0; it < T::kDmaPerWave; ++it) {
-      const int a = wave * T::kDmaPerWave + it;
-      dma16(kp, kofs[it], lds_address(Kbuf) + buf * T::kBytes + a * 1024);
-      dma16(vp, vofs[it], lds_address(Vbuf) + buf * T::kBytes + a * 1024);
-    }
+    for (int it = 0; it < kDma; ++it)
+      dma16(vp, vofs[it], lds_address(smem) + slot * T::kBytes + (wave * kDma + it) * 1024);
   };
 
-  if (n_list > 0) prefetch(list[0], 0);
+  // one DMA instruction of a tile at a time, so that the requests can be spread between the MFMAs:
+  // a wave that issues them in a burst sits blocked on the (64 B/clk) vector-memory queue instead
+  // of feeding the matrix cores
+  auto issue_one = [&](const uint16_t* tile, int ofs, int slot, int it) {
+    dma16(tile, ofs, lds_address(smem) + slot * T::kBytes + (wave * kDma + it) * 1024);
+  };
+
+  // ring item 2n = K(list[n]) -> slot (2n) % 5, item 2n+1 = V(list[n]) -> slot (2n+1) % 5
+  if (n_list > 0) {
+    issue_k(list[0], 0);
+    issue_v(list[0], 1);
+  }
+  if (n_list > 1) {
+    issue_k(list[1], 2);
+    issue_v(list[1], 3);
+  }
 
   // Q fragments: lane holds query row 32*qh + col, channels 16 t + 8 g .. + 8 for every k-step t
   bf16x8 qf[KSTEPS];
@@ -174,30 +211,75 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
     }
   }
 
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): tile 0 (and Q) have landed
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles and Q have landed
   // pin the Q fragments here: otherwise the compiler sinks their loads into the loop and then waits
   // for "all outstanding loads" there, which would also wait for the tile prefetch it cannot see
 #pragma unroll
   for (int t = 0; t < KSTEPS; ++t) asm volatile("" ::"v"(qf[t]));
   __syncthreads();
 
-  for (int n = 0; n < n_list; ++n) {
-    const int j = list[n];
-    const int buf = n & 1;
-    if (n + 1 < n_list) prefetch(list[n + 1], buf ^ 1);
+  // Waits until at most `younger` of this wave's most recent DMA instructions are outstanding
+  // (they complete in issue order).  Near the end of the list fewer tiles are in flight than the
+  // steady-state count assumes, so the last two iterations simply wait for everything.
+  auto wait_dma = [&](bool steady) {
+    if (steady)
+      __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * kDma));
+    else
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+  };
 
-    // ---- S^T = K Q^T over this wave's 32 keys --------------------------------------------
+  // One tile.  PHASE = n % 5 is a compile-time constant so that every LDS offset of the ring
+  // folds into the instruction.
+  auto tile_step = [&](auto phase_c, int n) {
+    constexpr int phase = decltype(phase_c)::value;
+    constexpr int kslot = (2 * phase) % kSlots, vslot = (2 * phase + 1) % kSlots;
+    constexpr int k2slot = (2 * phase + 4) % kSlots;  // item 2n+4 = K(n+2): the slot V(n-1) just left
+    const int j = list[n];
+    const bool steady = n + 2 < n_list;
+    const int j2 = steady ? list[n + 2] : 0;
+    const uint16_t* k2 = kbase + (long long)j2 * kBlock * D;
+    const uint16_t* v2 = vbase + (long long)j2 * kBlock * D;
+
+    // ---- S^T = K Q^T over this wave's 32 keys, K(n+2) requested between the MFMAs ----------
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
     {
-      const unsigned char* kb = Kbuf + buf * T::kBytes;
+      // all K fragments are requested up front: their LDS latency (long while the DMA engine and
+      // the other waves use the LDS) is then paid once, not once per MFMA pair
+      const unsigned char* kb = smem + kslot * T::kBytes;
+      bf16x8 kf[KSTEPS];
+#pragma unroll
+      for (int t = 0; t < KSTEPS; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kb + kfrag[t]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < KSTEPS; ++t) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb + kfrag[t]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s, 0, 0, 0);
+        constexpr int kEvery = KSTEPS / kDma;
+        if (t % kEvery == kEvery - 1 && steady) issue_one(k2, kofs[t / kEvery], k2slot, t / kEvery);
       }
     }
+    wait_dma(steady);  // V(n) has landed: younger are K(n+1), V(n+1), K(n+2)
+    __syncthreads();   // ... for every wave; and nobody reads K(n) any more
+
+    // all V^T fragments are requested now and arrive while the softmax runs on the VALU
+    bf16x8 vf[DSUB][2];
+    {
+      const unsigned char* vb = smem + vslot * T::kBytes;
+#pragma unroll
+      for (int ds = 0; ds < DSUB; ++ds)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][0]));
+          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][1]));
+          const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          __builtin_memcpy(&vf[ds][t], &both, sizeof(bf16x8));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
     // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
     const int nkeys = Nv - j * kBlock;  // valid keys in this tile (>= 64 except in the last block)
     if (nkeys < kBlock) {
@@ -207,10 +289,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
     }
 
     // ---- online softmax (log2 domain, lazily raised reference max) -------------------------
-    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+    float mx = max3(s[0], s[1], s[2]);
 #pragma unroll
-    for (int r = 4; r < 16; r += 4) mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
-    mx = fmaxf(mx, other_half(mx)) * scale_log2e;
+    for (int r = 3; r < 15; r += 2) mx = max3(mx, s[r], s[r + 1]);
+    {
+      float lo, hi;
+      both_halves(max3(mx, s[15], s[15]), lo, hi);
+      mx = max3(lo, hi, hi) * scale_log2e;
+    }
     if (__any(mx > m + kRescaleSlack)) {  // wave-uniform; always taken on the first live tile
       const float m_new = fmaxf(m, mx);
       const float alpha = fast_exp2(m - (m_new == -INFINITY ? 0.f : m_new));  // m = -inf -> 0
@@ -238,32 +324,31 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
       pf[r >> 3][(r & 7) + 1] = pp[1];
     }
 
-    // ---- O^T += V^T P^T ---------------------------------------------------------------------
-    {
-      const unsigned char* vb = Vbuf + buf * T::kBytes;
+    // ---- O^T += V^T P^T, V(n+2) requested between the MFMAs ----------------------------------
 #pragma unroll
-      for (int ds = 0; ds < DSUB; ++ds) {
+    for (int ds = 0; ds < DSUB; ++ds) {
+      // item 2n+5 = V(n+2) takes K(n)'s slot (free since the barrier above), one request per d sub-tile
+      if (ds % (DSUB / kDma) == 0 && steady) issue_one(v2, vofs[ds / (DSUB / kDma)], kslot, ds / (DSUB / kDma));
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][0]));
-          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][1]));
-          const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          bf16x8 vf;
-          __builtin_memcpy(&vf, &both, sizeof(vf));
-          o[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t], o[ds], 0, 0, 0);
-        }
-      }
+      for (int t = 0; t < 2; ++t) o[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ds][t], pf[t], o[ds], 0, 0, 0);
     }
 
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's share of tile n+1 is in LDS
-    __syncthreads();                      // everyone's share is, and tile n is no longer read
+    wait_dma(steady);  // K(n+1) has landed: younger are V(n+1), K(n+2), V(n+2)
+    __syncthreads();   // ... for every wave; and nobody reads V(n) any more
+  };
+  for (int n = 0; n < n_list; n += 5) {
+    tile_step(std::integral_constant<int, 0>{}, n);
+    if (n + 1 < n_list) tile_step(std::integral_constant<int, 1>{}, n + 1);
+    if (n + 2 < n_list) tile_step(std::integral_constant<int, 2>{}, n + 2);
+    if (n + 3 < n_list) tile_step(std::integral_constant<int, 3>{}, n + 3);
+    if (n + 4 < n_list) tile_step(std::integral_constant<int, 4>{}, n + 4);
   }
 
   // ---- merge the two key halves, stage the block row-major in LDS, store coalesced ----------
   // (the loop ended with a barrier, so the tile buffers are free)
-  const float l_row = l + other_half(l);
+  float l_lo, l_hi;
+  both_halves(l, l_lo, l_hi);
+  const float l_row = l_lo + l_hi;
   float* xch = reinterpret_cast<float*>(smem);                 // [2 qh][XROWS][64 lanes]
   float* stage = reinterpret_cast<float*>(smem + kXchBytes);   // [64 rows][OSTRIDE]
   if (kh == 1) {
