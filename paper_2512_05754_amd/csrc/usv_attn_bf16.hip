@@ -16,16 +16,20 @@
 // order as long as both operands agree, so V^T is read in the order the accumulator holds keys).
 // V^T fragments come from the row-major V tile with the LDS transpose read ds_read_b64_tr_b16.
 //
-// Data movement: K/V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no
-// register staging) through a ring of five tile slots that holds K(n), V(n), K(n+1), V(n+1), ...
-// in consumption order.  A slot is refilled as soon as the barrier after its last reader has
-// passed, so every tile is requested about two iterations before it is needed and the CU's
-// 64 B/clk vector-memory path (the second roofline of this kernel: 32 KiB per 64x64 tile) never
-// idles.  The 16-byte chunks of a row are XOR-permuted on the way in (the permutation is applied
-// to the global address, the LDS side of the DMA is lane-linear) so that both the 16-byte K
-// fragment reads and the transposing V reads are bank-conflict free.
-// Softmax: log2 domain, the running max is only raised when a row's tile max exceeds it by more
-// than kRescaleSlack (so P stays below 2^slack and the O rescale is skipped on most tiles).
+// What bounds the kernel, measured on MI355X: a wavefront issues at most one instruction (of any
+// kind) every ~8 clocks, a 32x32x16 MFMA occupies the matrix pipe for 32 clocks, and the CU's
+// vector-memory path moves 64 B/clk (a 64x64 tile needs 32 KiB of K and V: 512 clocks, the same
+// as its 16 MFMAs per SIMD).  So the design goal is few instructions per tile and three
+// workgroups per CU (three waves per SIMD) to cover each other's issue gaps and waits:
+//   - <= 168 VGPRs and 48 KiB of LDS per workgroup;
+//   - K/V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no register
+//     staging, M0 set once per tile) through a ring of three tile slots K(n), V(n), K(n+1), ...;
+//     a slot is refilled as soon as the barrier after its last reader has passed;
+//   - the 16-byte chunks of a row are XOR-permuted on the way in (applied to the global address;
+//     the LDS side of the DMA is lane-linear) so that both the 16-byte K fragment reads and the
+//     transposing V reads are bank-conflict free;
+//   - softmax in the log2 domain; the running max is only raised when a row's tile max exceeds it
+//     by more than kRescaleSlack, so the O rescale is skipped on almost every tile.
 #include <type_traits>
 
 #include "usv_internal.h"
@@ -41,7 +45,9 @@ typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kThreads = 256;
+constexpr int kWgPerCu = 3;
 constexpr float kRescaleSlack = 8.0f;  // log2 units
+constexpr int kSlots = 3;              // ring of K/V tile slots
 
 template <int D>
 struct Tile {
@@ -61,6 +67,7 @@ struct Tile {
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // Lanes l and l ^ 32 hold the two key halves of one query.  v_permlane32_swap on two copies of x
 // leaves (x of the low lane, x of the high lane) in both lanes: one VALU op, no LDS round trip.
 __device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
@@ -69,52 +76,78 @@ __device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
   lo = __uint_as_float(r[0]);
   hi = __uint_as_float(r[1]);
 }
-// max of three without the NaN-quieting moves the compiler adds around fmaxf (inputs are never NaN)
-__device__ __forceinline__ float max3(float a, float b, float c) {
-  float d;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-  return d;
+
+// Max of the 16 accumulator registers in 8 instructions.  One assembly block: v_max3 without the
+// NaN-quieting moves the compiler adds around fmaxf (the inputs are never NaN).
+__device__ __forceinline__ float max16(const f32x16& s) {
+  float a, b;
+  asm("v_max3_f32 %0, %2, %3, %4\n\t"
+      "v_max3_f32 %1, %5, %6, %7\n\t"
+      "v_max3_f32 %0, %0, %8, %9\n\t"
+      "v_max3_f32 %1, %1, %10, %11\n\t"
+      "v_max3_f32 %0, %0, %12, %13\n\t"
+      "v_max3_f32 %1, %1, %14, %15\n\t"
+      "v_max3_f32 %0, %0, %16, %17\n\t"
+      "v_max3_f32 %0, %0, %1, %1"
+      : "=&v"(a), "=&v"(b)
+      : "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]), "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]), "v"(s[8]),
+        "v"(s[9]), "v"(s[10]), "v"(s[11]), "v"(s[12]), "v"(s[13]), "v"(s[14]), "v"(s[15]));
+  return a;
 }
 
-// 16 bytes per lane, global -> LDS: lane reads gbase + voff (bytes) and the 64 lanes land at
-// lds_addr + 16 * lane.  Written as inline assembly so that the compiler does not pair the DMA with
-// a conservative "wait for all memory" before the next LDS read of the OTHER buffer; completion is
-// awaited explicitly (vmcnt) where the pipeline needs it.  M0 carries the LDS address and is
-// restored, since the compiler does not expect it to change.
-__device__ __forceinline__ void dma16(const void* gbase, unsigned voff, unsigned lds_addr) {
-  unsigned saved;
-  asm volatile(
-      "s_mov_b32 %0, m0\n\t"
-      "s_mov_b32 m0, %1\n\t"
-      "global_load_lds_dwordx4 %2, %3\n\t"
-      "s_mov_b32 m0, %0"
-      : "=&s"(saved)
-      : "s"(lds_addr), "v"(voff), "s"(gbase)
-      : "memory");
-}
 __device__ __forceinline__ unsigned lds_address(const void* p) {  // LDS byte address of a __shared__ pointer
   return (unsigned)(uintptr_t)p;
 }
 
+// One wave's share of a tile, global -> LDS: N instructions of 16 bytes per lane.  Instruction `it`
+// reads gbase + voff[it] + 1024*it per lane and lands at lds_addr + 1024*it + 16*lane (the
+// instruction offset applies to both addresses).  Inline assembly so that the compiler does not
+// pair the DMA with a conservative "wait for all memory" before the next LDS read of ANOTHER slot;
+// completion is awaited explicitly (vmcnt) where the pipeline needs it.  M0 carries the LDS
+// address; nothing else in this kernel uses M0.
+template <int N>
+__device__ __forceinline__ void dma_tile(const void* gbase, const int (&voff)[N], unsigned lds_addr);
+template <>
+__device__ __forceinline__ void dma_tile<4>(const void* gbase, const int (&voff)[4], unsigned lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "global_load_lds_dwordx4 %1, %5\n\t"
+      "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+      "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+      "global_load_lds_dwordx4 %4, %5 offset:3072"
+      :
+      : "s"(lds_addr), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(gbase)
+      : "memory");
+}
+template <>
+__device__ __forceinline__ void dma_tile<2>(const void* gbase, const int (&voff)[2], unsigned lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "global_load_lds_dwordx4 %1, %3\n\t"
+      "global_load_lds_dwordx4 %2, %3 offset:1024"
+      :
+      : "s"(lds_addr), "v"(voff[0]), "v"(voff[1]), "s"(gbase)
+      : "memory");
+}
+
 template <int D, bool OUT_F32>
-__global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restrict__ q,
-                                                         const uint16_t* __restrict__ k,
-                                                         const uint16_t* __restrict__ v,
-                                                         const int32_t* __restrict__ idx,
-                                                         const int32_t* __restrict__ cnt,
-                                                         void* __restrict__ out, float* __restrict__ lse,
-                                                         int nb, int Nv, int kmax, float scale_log2e,
-                                                         int total, int per_xcd) {
+__global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* __restrict__ q,
+                                                                const uint16_t* __restrict__ k,
+                                                                const uint16_t* __restrict__ v,
+                                                                const int32_t* __restrict__ idx,
+                                                                const int32_t* __restrict__ cnt,
+                                                                void* __restrict__ out, float* __restrict__ lse,
+                                                                int nb, int Nv, int kmax, float scale_log2e,
+                                                                int total, int per_xcd) {
   using T = Tile<D>;
   constexpr int KSTEPS = D / 16;  // MFMA k-steps of the QK^T product
   constexpr int DSUB = D / 32;    // 32-wide d sub-tiles of the output
-  constexpr int XROWS = DSUB * 16 + 2;            // exchange rows per wave: O registers, m, l
-  constexpr int OSTRIDE = D + 4;                  // fp32 staging row stride (floats), bank-spread
-  constexpr int kXchBytes = 2 * XROWS * 64 * 4;
-  constexpr int kStageBytes = kBlock * OSTRIDE * 4;
-  constexpr int kSlots = 5;                       // ring of K/V tile slots
   constexpr int kDma = T::kDmaPerWave;
-  constexpr int kSmem = (kSlots * T::kBytes > kXchBytes + kStageBytes) ? kSlots * T::kBytes : kXchBytes + kStageBytes;
+  constexpr int XROWS = DSUB * 16 + 2;  // exchange rows per wave: O registers, m, l
+  constexpr int OSTRIDE = D + 4;        // fp32 staging row stride (floats), bank-spread
+  static_assert(XROWS * 64 == 32 * OSTRIDE, "the staging rows of a query half overlay its exchange area");
+  constexpr int kEpilogueBytes = 2 * XROWS * 64 * 4;
+  constexpr int kSmem = kSlots * T::kBytes > kEpilogueBytes ? kSlots * T::kBytes : kEpilogueBytes;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kSmem];
 
   const int work = xcd_contiguous_id(blockIdx.x, per_xcd);
@@ -132,46 +165,34 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
   const uint16_t* kbase = k + head_off;
   const uint16_t* vbase = v + head_off;
 
-  // DMA plan of this wave: instruction `it` fills LDS bytes [a*1024, a*1024+1024) of a tile,
-  // a = wave*kDmaPerWave + it; lane -> (row, stored chunk position p); it fetches global chunk
-  // p ^ swz(row) of that row.  Byte offsets inside a tile are loop invariant.
-  int kofs[T::kDmaPerWave], vofs[T::kDmaPerWave];
+  // DMA plan of this wave: instruction `it` fills LDS bytes [a*1024, a*1024+1024) of a tile slot,
+  // a = wave*kDma + it; lane -> (row, stored chunk position p); it fetches global chunk
+  // p ^ swz(row) of that row.  The byte offsets are loop invariant; the 1024*it that the
+  // instruction offset adds on both sides is taken out of the global one here.
+  int kofs[kDma], vofs[kDma];
 #pragma unroll
-  for (int it = 0; it < T::kDmaPerWave; ++it) {
-    const int a = wave * T::kDmaPerWave + it;
-    const int row = a * T::kRowsPerDma + lane / T::kChunks, p = lane % T::kChunks;
-    kofs[it] = (row * D + ((p ^ T::k_swz(row)) << 3)) * 2;  // bytes
-    vofs[it] = (row * D + ((p ^ T::v_swz(row)) << 3)) * 2;
+  for (int it = 0; it < kDma; ++it) {
+    const int row = (wave * kDma + it) * T::kRowsPerDma + lane / T::kChunks, p = lane % T::kChunks;
+    kofs[it] = (row * D + ((p ^ T::k_swz(row)) << 3)) * 2 - 1024 * it;
+    vofs[it] = (row * D + ((p ^ T::v_swz(row)) << 3)) * 2 - 1024 * it;
   }
-  // this wave's quarter of one tile -> ring slot (kDma instructions, counted by vmcnt in issue order)
+  const unsigned wave_lds = lds_address(smem) + wave * kDma * 1024;
   auto issue_k = [&](int j, int slot) {
-    const uint16_t* kp = kbase + (long long)j * kBlock * D;
-#pragma unroll
-    for (int it = 0; it < kDma; ++it)
-      dma16(kp, kofs[it], lds_address(smem) + slot * T::kBytes + (wave * kDma + it) * 1024);
+    dma_tile<kDma>(kbase + (long long)j * kBlock * D, kofs, wave_lds + slot * T::kBytes);
   };
   auto issue_v = [&](int j, int slot) {
-    const uint16_t* vp = vbase + (long long)j * kBlock * D;
-#pragma unroll
-    for (int it = 0; it < kDma; ++it)
-      dma16(vp, vofs[it], lds_address(smem) + slot * T::kBytes + (wave * kDma + it) * 1024);
+    dma_tile<kDma>(vbase + (long long)j * kBlock * D, vofs, wave_lds + slot * T::kBytes);
   };
 
-  // one DMA instruction of a tile at a time, so that the requests can be spread between the MFMAs:
-  // a wave that issues them in a burst sits blocked on the (64 B/clk) vector-memory queue instead
-  // of feeding the matrix cores
-  auto issue_one = [&](const uint16_t* tile, int ofs, int slot, int it) {
-    dma16(tile, ofs, lds_address(smem) + slot * T::kBytes + (wave * kDma + it) * 1024);
-  };
+  // Block ids are fetched (scalar loads) one tile before they are used: a wait for a scalar load
+  // is also a wait for every LDS read in flight.
+  int j_cur = n_list > 0 ? list[0] : 0;  // tile n
+  int j_nxt = n_list > 1 ? list[1] : 0;  // tile n+1
 
-  // ring item 2n = K(list[n]) -> slot (2n) % 5, item 2n+1 = V(list[n]) -> slot (2n+1) % 5
+  // ring item 2n = K(list[n]) -> slot (2n) % 3, item 2n+1 = V(list[n]) -> slot (2n+1) % 3
   if (n_list > 0) {
-    issue_k(list[0], 0);
-    issue_v(list[0], 1);
-  }
-  if (n_list > 1) {
-    issue_k(list[1], 2);
-    issue_v(list[1], 3);
+    issue_k(j_cur, 0);
+    issue_v(j_cur, 1);
   }
 
   // Q fragments: lane holds query row 32*qh + col, channels 16 t + 8 g .. + 8 for every k-step t
@@ -211,74 +232,45 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
     }
   }
 
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles and Q have landed
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): tile 0 and Q have landed
   // pin the Q fragments here: otherwise the compiler sinks their loads into the loop and then waits
   // for "all outstanding loads" there, which would also wait for the tile prefetch it cannot see
 #pragma unroll
   for (int t = 0; t < KSTEPS; ++t) asm volatile("" ::"v"(qf[t]));
   __syncthreads();
 
-  // Waits until at most `younger` of this wave's most recent DMA instructions are outstanding
-  // (they complete in issue order).  Near the end of the list fewer tiles are in flight than the
-  // steady-state count assumes, so the last two iterations simply wait for everything.
-  auto wait_dma = [&](bool steady) {
-    if (steady)
-      __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * kDma));
-    else
-      __builtin_amdgcn_s_waitcnt(0x0f70);
-  };
-
-  // One tile.  PHASE = n % 5 is a compile-time constant so that every LDS offset of the ring
-  // folds into the instruction.
+  // One tile.  PHASE = n % 3 is a compile-time constant so that every LDS offset of the ring folds
+  // into the instruction.  On entry K(n) is in LDS and visible to every wave, V(n) is in flight
+  // (or landed), and the slot of V(n-1) is free.
   auto tile_step = [&](auto phase_c, int n) {
     constexpr int phase = decltype(phase_c)::value;
     constexpr int kslot = (2 * phase) % kSlots, vslot = (2 * phase + 1) % kSlots;
-    constexpr int k2slot = (2 * phase + 4) % kSlots;  // item 2n+4 = K(n+2): the slot V(n-1) just left
-    const int j = list[n];
-    const bool steady = n + 2 < n_list;
-    const int j2 = steady ? list[n + 2] : 0;
-    const uint16_t* k2 = kbase + (long long)j2 * kBlock * D;
-    const uint16_t* v2 = vbase + (long long)j2 * kBlock * D;
+    constexpr int k1slot = (2 * phase + 2) % kSlots;  // item 2n+2 = K(n+1): the slot V(n-1) just left
+    const int j = j_cur;
+    const bool more = n + 1 < n_list;
+    if (more) issue_k(j_nxt, k1slot);
 
-    // ---- S^T = K Q^T over this wave's 32 keys, K(n+2) requested between the MFMAs ----------
+    // ---- S^T = K Q^T over this wave's 32 keys --------------------------------------------
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
     {
-      // all K fragments are requested up front: their LDS latency (long while the DMA engine and
-      // the other waves use the LDS) is then paid once, not once per MFMA pair
       const unsigned char* kb = smem + kslot * T::kBytes;
-      bf16x8 kf[KSTEPS];
-#pragma unroll
-      for (int t = 0; t < KSTEPS; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kb + kfrag[t]);
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < KSTEPS; ++t) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], s, 0, 0, 0);
-        constexpr int kEvery = KSTEPS / kDma;
-        if (t % kEvery == kEvery - 1 && steady) issue_one(k2, kofs[t / kEvery], k2slot, t / kEvery);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb + kfrag[t]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s, 0, 0, 0);
       }
     }
-    wait_dma(steady);  // V(n) has landed: younger are K(n+1), V(n+1), K(n+2)
-    __syncthreads();   // ... for every wave; and nobody reads K(n) any more
-
-    // all V^T fragments are requested now and arrive while the softmax runs on the VALU
-    bf16x8 vf[DSUB][2];
-    {
-      const unsigned char* vb = smem + vslot * T::kBytes;
-#pragma unroll
-      for (int ds = 0; ds < DSUB; ++ds)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][0]));
-          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][1]));
-          const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          __builtin_memcpy(&vf[ds][t], &both, sizeof(bf16x8));
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
+    // V(n) has landed; only K(n+1), requested after it, may still be in flight
+    if (more)
+      __builtin_amdgcn_s_waitcnt(0x0f70 | kDma);
+    else
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();  // ... for every wave; and nobody reads K(n) any more
+    if (more) issue_v(j_nxt, kslot);  // item 2n+3 = V(n+1) takes K(n)'s slot
+    j_cur = j_nxt;
+    j_nxt = n + 2 < n_list ? list[n + 2] : 0;
 
     // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
     const int nkeys = Nv - j * kBlock;  // valid keys in this tile (>= 64 except in the last block)
@@ -289,13 +281,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
     }
 
     // ---- online softmax (log2 domain, lazily raised reference max) -------------------------
-    float mx = max3(s[0], s[1], s[2]);
-#pragma unroll
-    for (int r = 3; r < 15; r += 2) mx = max3(mx, s[r], s[r + 1]);
+    float mx;
     {
       float lo, hi;
-      both_halves(max3(mx, s[15], s[15]), lo, hi);
-      mx = max3(lo, hi, hi) * scale_log2e;
+      both_halves(max16(s), lo, hi);
+      mx = fmaxf(lo, hi) * scale_log2e;
     }
     if (__any(mx > m + kRescaleSlack)) {  // wave-uniform; always taken on the first live tile
       const float m_new = fmaxf(m, mx);
@@ -324,35 +314,47 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
       pf[r >> 3][(r & 7) + 1] = pp[1];
     }
 
-    // ---- O^T += V^T P^T, V(n+2) requested between the MFMAs ----------------------------------
+    // ---- O^T += V^T P^T ---------------------------------------------------------------------
+    {
+      const unsigned char* vb = smem + vslot * T::kBytes;
 #pragma unroll
-    for (int ds = 0; ds < DSUB; ++ds) {
-      // item 2n+5 = V(n+2) takes K(n)'s slot (free since the barrier above), one request per d sub-tile
-      if (ds % (DSUB / kDma) == 0 && steady) issue_one(v2, vofs[ds / (DSUB / kDma)], kslot, ds / (DSUB / kDma));
+      for (int ds = 0; ds < DSUB; ++ds) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) o[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ds][t], pf[t], o[ds], 0, 0, 0);
+        for (int t = 0; t < 2; ++t) {
+          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][0]));
+          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][1]));
+          const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          bf16x8 vf;
+          __builtin_memcpy(&vf, &both, sizeof(vf));
+          o[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t], o[ds], 0, 0, 0);
+        }
+      }
     }
 
-    wait_dma(steady);  // K(n+1) has landed: younger are V(n+1), K(n+2), V(n+2)
-    __syncthreads();   // ... for every wave; and nobody reads V(n) any more
+    // K(n+1) has landed; only V(n+1), requested after it, may still be in flight
+    if (more)
+      __builtin_amdgcn_s_waitcnt(0x0f70 | kDma);
+    else
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();  // ... for every wave; and nobody reads V(n) any more
   };
-  for (int n = 0; n < n_list; n += 5) {
+  for (int n = 0; n < n_list; n += 3) {
     tile_step(std::integral_constant<int, 0>{}, n);
     if (n + 1 < n_list) tile_step(std::integral_constant<int, 1>{}, n + 1);
     if (n + 2 < n_list) tile_step(std::integral_constant<int, 2>{}, n + 2);
-    if (n + 3 < n_list) tile_step(std::integral_constant<int, 3>{}, n + 3);
-    if (n + 4 < n_list) tile_step(std::integral_constant<int, 4>{}, n + 4);
   }
 
   // ---- merge the two key halves, stage the block row-major in LDS, store coalesced ----------
-  // (the loop ended with a barrier, so the tile buffers are free)
+  // (the loop ended with a barrier, so the tile slots are free).  The staging rows of a query half
+  // overlay the exchange area that the SAME wave has just read into registers.
   float l_lo, l_hi;
   both_halves(l, l_lo, l_hi);
   const float l_row = l_lo + l_hi;
-  float* xch = reinterpret_cast<float*>(smem);                 // [2 qh][XROWS][64 lanes]
-  float* stage = reinterpret_cast<float*>(smem + kXchBytes);   // [64 rows][OSTRIDE]
+  float* xch = reinterpret_cast<float*>(smem) + qh * XROWS * 64;  // [XROWS][64 lanes] of this query half
   if (kh == 1) {
-    float* dst = xch + (qh * XROWS) * 64 + lane;
+    float* dst = xch + lane;
 #pragma unroll
     for (int ds = 0; ds < DSUB; ++ds)
 #pragma unroll
@@ -362,34 +364,38 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bf16(const uint16_t* __restr
   }
   __syncthreads();
   if (kh == 0) {
-    const float* src = xch + (qh * XROWS) * 64 + lane;
+    const float* src = xch + lane;
     const float m1 = src[(DSUB * 16) * 64], l1 = src[(DSUB * 16 + 1) * 64];
     const float mm = fmaxf(m, m1);
     const float m_ref = mm == -INFINITY ? 0.f : mm;
     const float a0 = fast_exp2(m - m_ref), a1 = fast_exp2(m1 - m_ref);
     const float lt = l_row * a0 + l1 * a1;
-    const int row = qh * 32 + col;
-    const int token = i * kBlock + row;
+    const int token = i * kBlock + qh * 32 + col;
     const bool live = token < Nv && n_list > 0;
     const float inv = live ? 1.f / lt : 0.f;
     const float w0 = live ? a0 * inv : 0.f, w1 = live ? a1 * inv : 0.f;
 #pragma unroll
     for (int ds = 0; ds < DSUB; ++ds)
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        float4 val;
-        // register r = 4 rq + e is channel 32 ds + 8 rq + 4 g + e
-        val.x = o[ds][rq * 4 + 0] * w0 + src[(ds * 16 + rq * 4 + 0) * 64] * w1;
-        val.y = o[ds][rq * 4 + 1] * w0 + src[(ds * 16 + rq * 4 + 1) * 64] * w1;
-        val.z = o[ds][rq * 4 + 2] * w0 + src[(ds * 16 + rq * 4 + 2) * 64] * w1;
-        val.w = o[ds][rq * 4 + 3] * w0 + src[(ds * 16 + rq * 4 + 3) * 64] * w1;
-        *reinterpret_cast<float4*>(stage + row * OSTRIDE + 32 * ds + 8 * rq + 4 * g) = live ? val : make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int r = 0; r < 16; ++r) {
+        const float val = o[ds][r] * w0 + src[(ds * 16 + r) * 64] * w1;
+        o[ds][r] = live ? val : 0.f;
       }
     if (lse && g == 0) lse[head * (long long)nb * kBlock + token] = live ? (mm + __log2f(lt)) * kLn2 : -INFINITY;
+    // every exchange value of this wave must be in registers before its area is overwritten
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    float* stage = xch + col * OSTRIDE;  // row (32 qh + col) of the block
+#pragma unroll
+    for (int ds = 0; ds < DSUB; ++ds)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq)  // register r = 4 rq + e is channel 32 ds + 8 rq + 4 g + e
+        *reinterpret_cast<float4*>(stage + 32 * ds + 8 * rq + 4 * g) =
+            make_float4(o[ds][rq * 4], o[ds][rq * 4 + 1], o[ds][rq * 4 + 2], o[ds][rq * 4 + 3]);
   }
   __syncthreads();
   {
     // 64 rows x D channels, 4 channels per thread per pass, consecutive threads -> consecutive addresses
+    const float* stage = reinterpret_cast<const float*>(smem);  // row r at r * OSTRIDE
     constexpr int PIECES = kBlock * D / 4;
     const long long blk_off = head_off + (long long)i * kBlock * D;
 #pragma unroll
