@@ -58,10 +58,10 @@ struct Tile {
   static constexpr int kRowsPerDma = 1024 / kRowBytes;
   // K: lanes 0..15 of a fragment read hit 16 consecutive rows at one chunk column.
   __device__ static int k_swz(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
-  // V: a transposing read touches 8 consecutive rows x 4 consecutive chunks.
-  __device__ static int v_swz(int row) {
-    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : (((row & 1) << 2) | ((row >> 1) & 3));
-  }
+  // V: one LDS cycle of a transposing read covers 4 consecutive rows x 4 consecutive chunks (one
+  // 64-byte group); XOR-ing the group index with the row spreads the 4 rows over all banks.  Rows
+  // r, r+8, r+16 share the permutation, so the fragment addresses differ by constants.
+  __device__ static int v_swz(int row) { return D == 128 ? ((row & 3) << 2) : ((row & 1) << 2); }
   __device__ static int k_off(int row, int chunk) { return row * kRowBytes + ((chunk ^ k_swz(row)) << 4); }
   __device__ static int v_off(int row, int chunk) { return row * kRowBytes + ((chunk ^ v_swz(row)) << 4); }
 };
@@ -184,10 +184,13 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
     dma_tile<kDma>(vbase + (long long)j * kBlock * D, vofs, wave_lds + slot * T::kBytes);
   };
 
-  // Block ids are fetched (scalar loads) one tile before they are used: a wait for a scalar load
-  // is also a wait for every LDS read in flight.
-  int j_cur = n_list > 0 ? list[0] : 0;  // tile n
-  int j_nxt = n_list > 1 ? list[1] : 0;  // tile n+1
+  // The index list lives in a VGPR, 64 entries at a time (lane t holds entry 64*chunk + t), and is
+  // read with v_readlane: one instruction per tile and no scalar-memory wait, which would also be
+  // a wait for every LDS read in flight.
+  int list_v = lane < n_list ? list[lane] : 0;
+  auto list_at = [&](int n) { return __builtin_amdgcn_readlane(list_v, n & 63); };
+  int j_cur = list_at(0);  // tile n
+  int j_nxt = list_at(1);  // tile n+1
 
   // ring item 2n = K(list[n]) -> slot (2n) % 3, item 2n+1 = V(list[n]) -> slot (2n+1) % 3
   if (n_list > 0) {
@@ -215,20 +218,16 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
   int kfrag[KSTEPS];
 #pragma unroll
   for (int t = 0; t < KSTEPS; ++t) kfrag[t] = T::k_off(kh * 32 + col, 2 * t + g);
-  int vfrag[DSUB][2][2];
+  // V^T fragment of d sub-tile ds, k-step t: slots 0..3 are keys 16 t + 4 g + (0..3), slots 4..7
+  // keys 16 t + 8 + 4 g + (0..3) of this wave's half; +8 and +16 rows are constant byte offsets
+  int vfrag[DSUB];
   {
     const int l16 = lane & 15;
+    const int key0 = kh * 32 + 4 * g + (l16 >> 2);
 #pragma unroll
     for (int ds = 0; ds < DSUB; ++ds) {
       const int dcol = 32 * ds + 16 * ((lane >> 4) & 1) + 4 * (l16 & 3);  // 4 channels = half a chunk
-      const int chunk = dcol >> 3, half = (dcol >> 2) & 1;
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        // slots 0..3: keys 16 t + 4 g + (0..3); slots 4..7: keys 16 t + 8 + 4 g + (0..3) of this wave's half
-        const int key0 = kh * 32 + 16 * t + 4 * g + (l16 >> 2);
-        vfrag[ds][t][0] = T::v_off(key0, chunk) + half * 8;
-        vfrag[ds][t][1] = T::v_off(key0 + 8, chunk) + half * 8;
-      }
+      vfrag[ds] = T::v_off(key0, dcol >> 3) + ((dcol >> 2) & 1) * 8;
     }
   }
 
@@ -255,11 +254,21 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
     {
+      // fragments are read four at a time and awaited once per batch: every s_waitcnt costs the
+      // wave an issue slot, and the other waves of the SIMD cover the LDS latency
       const unsigned char* kb = smem + kslot * T::kBytes;
 #pragma unroll
-      for (int t = 0; t < KSTEPS; ++t) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb + kfrag[t]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s, 0, 0, 0);
+      for (int t0 = 0; t0 < KSTEPS; t0 += 4) {
+        bf16x8 kf[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kb + kfrag[t0 + t]);
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+        // s_setprio also fences the compiler's scheduler, which keeps each batch together:
+        // four reads, one wait, four back-to-back MFMAs that go first on the matrix pipe
+        __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t0 + t], s, 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
       }
     }
     // V(n) has landed; only K(n+1), requested after it, may still be in flight
@@ -270,7 +279,12 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
     __syncthreads();  // ... for every wave; and nobody reads K(n) any more
     if (more) issue_v(j_nxt, kslot);  // item 2n+3 = V(n+1) takes K(n)'s slot
     j_cur = j_nxt;
-    j_nxt = n + 2 < n_list ? list[n + 2] : 0;
+    if (((n + 2) & 63) == 0) {  // next 64 entries; awaited right here (once per 64 tiles) so that the
+      list_v = n + 2 + lane < n_list ? list[n + 2 + lane] : 0;  // hot path carries no vector-memory wait
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+      asm volatile("" ::"v"(list_v));
+    }
+    j_nxt = list_at(n + 2);
 
     // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
     const int nkeys = Nv - j * kBlock;  // valid keys in this tile (>= 64 except in the last block)
@@ -298,38 +312,57 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
         for (int r = 0; r < 16; ++r) o[ds][r] *= alpha;
     }
     const float neg_m = m == -INFINITY ? 0.f : -m;  // every key of this half masked so far
-    bf16x8 pf[2];
+    // P^T of this wave's 32 keys, rounded to bf16 and packed two per register: the same registers
+    // feed the row sum (v_dot2 with ones) and, as they stand, the B operand of the second product
+    typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned uint4v;
+    bf16x2 pk[8];
 #pragma unroll
     for (int r = 0; r < 16; r += 2) {
-      bf16x2 pp;
-      pp[0] = (__bf16)fast_exp2(fmaf(s[r], scale_log2e, neg_m));
-      pp[1] = (__bf16)fast_exp2(fmaf(s[r + 1], scale_log2e, neg_m));
+      pk[r >> 1][0] = (__bf16)fast_exp2(fmaf(s[r], scale_log2e, neg_m));
+      pk[r >> 1][1] = (__bf16)fast_exp2(fmaf(s[r + 1], scale_log2e, neg_m));
+    }
+    {
       // the row sum is taken over the ROUNDED probabilities, the ones P V actually uses, so that
       // the final division cancels the rounding of a dominant key instead of keeping it
       bf16x2 ones;
       ones[0] = (__bf16)1.0f;
       ones[1] = (__bf16)1.0f;
-      l = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l, false);
-      pf[r >> 3][r & 7] = pp[0];
-      pf[r >> 3][(r & 7) + 1] = pp[1];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) l = __builtin_amdgcn_fdot2_f32_bf16(pk[r], ones, l, false);
+    }
+    bf16x8 pf[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const uint4v w = {__builtin_bit_cast(unsigned, pk[4 * t]), __builtin_bit_cast(unsigned, pk[4 * t + 1]),
+                        __builtin_bit_cast(unsigned, pk[4 * t + 2]), __builtin_bit_cast(unsigned, pk[4 * t + 3])};
+      pf[t] = __builtin_bit_cast(bf16x8, w);
     }
 
     // ---- O^T += V^T P^T ---------------------------------------------------------------------
     {
       const unsigned char* vb = smem + vslot * T::kBytes;
 #pragma unroll
-      for (int ds = 0; ds < DSUB; ++ds) {
+      for (int ds0 = 0; ds0 < DSUB; ds0 += 2) {
+        bf16x8 vf[2][2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][0]));
-          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (short4v __attribute__((address_space(3)))*)(vb + vfrag[ds][t][1]));
-          const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          bf16x8 vf;
-          __builtin_memcpy(&vf, &both, sizeof(vf));
-          o[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t], o[ds], 0, 0, 0);
-        }
+        for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const unsigned char* p = vb + vfrag[ds0 + dd] + t * 16 * T::kRowBytes;
+            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
+            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (short4v __attribute__((address_space(3)))*)(p + 8 * T::kRowBytes));
+            const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            __builtin_memcpy(&vf[dd][t], &both, sizeof(bf16x8));
+          }
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+        __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+        for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+            o[ds0 + dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dd][t], pf[t], o[ds0 + dd], 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
       }
     }
 
