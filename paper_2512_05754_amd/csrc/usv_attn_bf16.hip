@@ -19,11 +19,11 @@
 // What bounds the kernel, measured on MI355X: a wavefront issues at most one instruction (of any
 // kind) every ~8 clocks, a 32x32x16 MFMA occupies the matrix pipe for 32 clocks, and the CU's
 // vector-memory path moves 64 B/clk (a 64x64 tile needs 32 KiB of K and V: 512 clocks, the same
-// as its 16 MFMAs per SIMD).  So the design goal is few instructions per tile and three
-// workgroups per CU (three waves per SIMD) to cover each other's issue gaps and waits:
-//   - <= 168 VGPRs and 48 KiB of LDS per workgroup;
+// as its 16 MFMAs per SIMD).  So the design goal is few instructions per tile and two or three
+// workgroups per CU (waves per SIMD) that cover each other's issue gaps and waits:
+//   - <= 168 VGPRs, so that three workgroups fit where the LDS ring allows it;
 //   - K/V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no register
-//     staging, M0 set once per tile) through a ring of three tile slots K(n), V(n), K(n+1), ...;
+//     staging, M0 set once per tile) through a ring of 3 or 5 tile slots K(n), V(n), K(n+1), ...;
 //     a slot is refilled as soon as the barrier after its last reader has passed;
 //   - the 16-byte chunks of a row are XOR-permuted on the way in (applied to the global address;
 //     the LDS side of the DMA is lane-linear) so that both the 16-byte K fragment reads and the
@@ -45,9 +45,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kThreads = 256;
-constexpr int kWgPerCu = 3;
 constexpr float kRescaleSlack = 8.0f;  // log2 units
-constexpr int kSlots = 3;              // ring of K/V tile slots
 
 template <int D>
 struct Tile {
@@ -130,8 +128,10 @@ __device__ __forceinline__ void dma_tile<2>(const void* gbase, const int (&voff)
       : "memory");
 }
 
-template <int D, bool OUT_F32>
-__global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* __restrict__ q,
+// SLOTS (odd) = tile slots of the LDS ring; a tile is requested LEAD = (SLOTS-1)/2 tiles before it
+// is used.  WGS = workgroups (= waves per SIMD) the register and LDS budget is sized for.
+template <int D, bool OUT_F32, int SLOTS, int WGS>
+__global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __restrict__ q,
                                                                 const uint16_t* __restrict__ k,
                                                                 const uint16_t* __restrict__ v,
                                                                 const int32_t* __restrict__ idx,
@@ -143,6 +143,9 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
   constexpr int KSTEPS = D / 16;  // MFMA k-steps of the QK^T product
   constexpr int DSUB = D / 32;    // 32-wide d sub-tiles of the output
   constexpr int kDma = T::kDmaPerWave;
+  constexpr int kSlots = SLOTS;
+  constexpr int LEAD = (SLOTS - 1) / 2;
+  static_assert(SLOTS % 2 == 1 && SLOTS >= 3, "odd ring: K items land on the slots V items left and vice versa");
   constexpr int XROWS = DSUB * 16 + 2;  // exchange rows per wave: O registers, m, l
   constexpr int OSTRIDE = D + 4;        // fp32 staging row stride (floats), bank-spread
   static_assert(XROWS * 64 == 32 * OSTRIDE, "the staging rows of a query half overlay its exchange area");
@@ -189,14 +192,19 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
   // a wait for every LDS read in flight.
   int list_v = lane < n_list ? list[lane] : 0;
   auto list_at = [&](int n) { return __builtin_amdgcn_readlane(list_v, n & 63); };
-  int j_cur = list_at(0);  // tile n
-  int j_nxt = list_at(1);  // tile n+1
 
-  // ring item 2n = K(list[n]) -> slot (2n) % 3, item 2n+1 = V(list[n]) -> slot (2n+1) % 3
-  if (n_list > 0) {
-    issue_k(j_cur, 0);
-    issue_v(j_cur, 1);
-  }
+  // ring item 2n = K(list[n]) -> slot (2n) % SLOTS, item 2n+1 = V(list[n]) -> slot (2n+1) % SLOTS;
+  // the first LEAD tiles are requested here
+#pragma unroll
+  for (int t = 0; t < LEAD; ++t)
+    if (t < n_list) {
+      const int j = list_at(t);
+      issue_k(j, (2 * t) % kSlots);
+      issue_v(j, (2 * t + 1) % kSlots);
+    }
+  int jq[LEAD + 1];  // block ids of tiles n .. n+LEAD (entries beyond the list read as block 0, unused)
+#pragma unroll
+  for (int t = 0; t <= LEAD; ++t) jq[t] = list_at(t);
 
   // Q fragments: lane holds query row 32*qh + col, channels 16 t + 8 g .. + 8 for every k-step t
   bf16x8 qf[KSTEPS];
@@ -231,23 +239,24 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
     }
   }
 
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): tile 0 and Q have landed
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles and Q have landed
   // pin the Q fragments here: otherwise the compiler sinks their loads into the loop and then waits
   // for "all outstanding loads" there, which would also wait for the tile prefetch it cannot see
 #pragma unroll
   for (int t = 0; t < KSTEPS; ++t) asm volatile("" ::"v"(qf[t]));
   __syncthreads();
 
-  // One tile.  PHASE = n % 3 is a compile-time constant so that every LDS offset of the ring folds
-  // into the instruction.  On entry K(n) is in LDS and visible to every wave, V(n) is in flight
-  // (or landed), and the slot of V(n-1) is free.
+  // One tile.  PHASE = n % SLOTS is a compile-time constant so that every LDS offset of the ring
+  // folds into the instruction.  On entry K(n) is in LDS and visible to every wave and the slot of
+  // V(n-1) is free.  A freed slot of item e is refilled with item e + SLOTS.
   auto tile_step = [&](auto phase_c, int n) {
     constexpr int phase = decltype(phase_c)::value;
     constexpr int kslot = (2 * phase) % kSlots, vslot = (2 * phase + 1) % kSlots;
-    constexpr int k1slot = (2 * phase + 2) % kSlots;  // item 2n+2 = K(n+1): the slot V(n-1) just left
-    const int j = j_cur;
-    const bool more = n + 1 < n_list;
-    if (more) issue_k(j_nxt, k1slot);
+    constexpr int freed_v = (2 * phase + kSlots - 1) % kSlots;  // slot of item 2n-1 = V(n-1)
+    const int j = jq[0];
+    const int j_pre = jq[LEAD];
+    const bool steady = n + LEAD < n_list;
+    if (steady) issue_k(j_pre, freed_v);  // item 2n-1+SLOTS = K(n+LEAD)
 
     // ---- S^T = K Q^T over this wave's 32 keys --------------------------------------------
     f32x16 s;
@@ -257,34 +266,38 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
       // fragments are read four at a time and awaited once per batch: every s_waitcnt costs the
       // wave an issue slot, and the other waves of the SIMD cover the LDS latency
       const unsigned char* kb = smem + kslot * T::kBytes;
+      constexpr int KB = WGS <= 2 ? (KSTEPS < 8 ? KSTEPS : 8) : 4;  // fragments per batch (register budget)
 #pragma unroll
-      for (int t0 = 0; t0 < KSTEPS; t0 += 4) {
-        bf16x8 kf[4];
+      for (int t0 = 0; t0 < KSTEPS; t0 += KB) {
+        bf16x8 kf[KB];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kb + kfrag[t0 + t]);
+        for (int t = 0; t < KB; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kb + kfrag[t0 + t]);
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
         // s_setprio also fences the compiler's scheduler, which keeps each batch together:
         // four reads, one wait, four back-to-back MFMAs that go first on the matrix pipe
         __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t0 + t], s, 0, 0, 0);
+        for (int t = 0; t < KB; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t0 + t], s, 0, 0, 0);
         __builtin_amdgcn_s_setprio(0);
       }
     }
-    // V(n) has landed; only K(n+1), requested after it, may still be in flight
-    if (more)
-      __builtin_amdgcn_s_waitcnt(0x0f70 | kDma);
+    // V(n) has landed; only the SLOTS-2 items requested after it may still be in flight (near the
+    // end of the list fewer are, so the last LEAD tiles simply wait for everything)
+    if (steady)
+      __builtin_amdgcn_s_waitcnt(0x0f70 | ((kSlots - 2) * kDma));
     else
       __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();  // ... for every wave; and nobody reads K(n) any more
-    if (more) issue_v(j_nxt, kslot);  // item 2n+3 = V(n+1) takes K(n)'s slot
-    j_cur = j_nxt;
-    if (((n + 2) & 63) == 0) {  // next 64 entries; awaited right here (once per 64 tiles) so that the
-      list_v = n + 2 + lane < n_list ? list[n + 2 + lane] : 0;  // hot path carries no vector-memory wait
-      __builtin_amdgcn_s_waitcnt(0x0f70);
+    if (steady) issue_v(j_pre, kslot);  // item 2n+SLOTS = V(n+LEAD) takes K(n)'s slot
+    // block ids for the next iteration: shift the queue and append tile n+1+LEAD
+#pragma unroll
+    for (int t = 0; t < LEAD; ++t) jq[t] = jq[t + 1];
+    if (((n + 1 + LEAD) & 63) == 0) {  // next 64 entries; awaited right here (once per 64 tiles) so that
+      list_v = n + 1 + LEAD + lane < n_list ? list[n + 1 + LEAD + lane] : 0;  // the hot path carries no
+      __builtin_amdgcn_s_waitcnt(0x0f70);                                      // vector-memory wait
       asm volatile("" ::"v"(list_v));
     }
-    j_nxt = list_at(n + 2);
+    jq[LEAD] = list_at(n + 1 + LEAD);
 
     // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
     const int nkeys = Nv - j * kBlock;  // valid keys in this tile (>= 64 except in the last block)
@@ -341,11 +354,12 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
     // ---- O^T += V^T P^T ---------------------------------------------------------------------
     {
       const unsigned char* vb = smem + vslot * T::kBytes;
+      constexpr int VB = WGS <= 2 ? DSUB : 2;  // d sub-tiles per batch
 #pragma unroll
-      for (int ds0 = 0; ds0 < DSUB; ds0 += 2) {
-        bf16x8 vf[2][2];
+      for (int ds0 = 0; ds0 < DSUB; ds0 += VB) {
+        bf16x8 vf[VB][2];
 #pragma unroll
-        for (int dd = 0; dd < 2; ++dd)
+        for (int dd = 0; dd < VB; ++dd)
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
             const unsigned char* p = vb + vfrag[ds0 + dd] + t * 16 * T::kRowBytes;
@@ -358,7 +372,7 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
         __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-        for (int dd = 0; dd < 2; ++dd)
+        for (int dd = 0; dd < VB; ++dd)
 #pragma unroll
           for (int t = 0; t < 2; ++t)
             o[ds0 + dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dd][t], pf[t], o[ds0 + dd], 0, 0, 0);
@@ -366,17 +380,21 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
       }
     }
 
-    // K(n+1) has landed; only V(n+1), requested after it, may still be in flight
-    if (more)
-      __builtin_amdgcn_s_waitcnt(0x0f70 | kDma);
+    // K(n+1) has landed; again at most SLOTS-2 younger items are in flight
+    if (steady)
+      __builtin_amdgcn_s_waitcnt(0x0f70 | ((kSlots - 2) * kDma));
     else
       __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();  // ... for every wave; and nobody reads V(n) any more
   };
-  for (int n = 0; n < n_list; n += 3) {
+  for (int n = 0; n < n_list; n += kSlots) {
     tile_step(std::integral_constant<int, 0>{}, n);
     if (n + 1 < n_list) tile_step(std::integral_constant<int, 1>{}, n + 1);
     if (n + 2 < n_list) tile_step(std::integral_constant<int, 2>{}, n + 2);
+    if constexpr (kSlots >= 5) {
+      if (n + 3 < n_list) tile_step(std::integral_constant<int, 3>{}, n + 3);
+      if (n + 4 < n_list) tile_step(std::integral_constant<int, 4>{}, n + 4);
+    }
   }
 
   // ---- merge the two key halves, stage the block row-major in LDS, store coalesced ----------
@@ -447,7 +465,7 @@ __global__ __launch_bounds__(kThreads, kWgPerCu) void attn_bf16(const uint16_t* 
   }
 }
 
-template <int D, bool OUT_F32>
+template <int D, bool OUT_F32, int SLOTS, int WGS>
 hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx, const int32_t* cnt,
                int kmax, float scale, void* out, float* lse, hipStream_t st) {
   const long long total = s.bh() * s.nb;
@@ -457,7 +475,7 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
   auto Q = static_cast<const uint16_t*>(q);
   auto K = static_cast<const uint16_t*>(k);
   auto V = static_cast<const uint16_t*>(v);
-  attn_bf16<D, OUT_F32><<<grid, kThreads, 0, st>>>(Q, K, V, idx, cnt, out, lse, s.nb, s.Nv, kmax, sl2, (int)total,
+  attn_bf16<D, OUT_F32, SLOTS, WGS><<<grid, kThreads, 0, st>>>(Q, K, V, idx, cnt, out, lse, s.nb, s.Nv, kmax, sl2, (int)total,
                                                     per_xcd);
   return hipGetLastError();
 }
@@ -467,11 +485,22 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
                             hipStream_t st) {
-  if (s.d == 128)
-    return out_f32 ? run<128, true>(q, k, v, s, idx, cnt, kmax, scale, out, lse, st)
-                   : run<128, false>(q, k, v, s, idx, cnt, kmax, scale, out, lse, st);
-  return out_f32 ? run<64, true>(q, k, v, s, idx, cnt, kmax, scale, out, lse, st)
-                 : run<64, false>(q, k, v, s, idx, cnt, kmax, scale, out, lse, st);
+  // Two launch shapes (measured at the 480p shape, 51 of 512 blocks kept):
+  //   sparse lists: 5-slot ring, 2 workgroups per CU.  Independent lists miss the 4 MiB L2 about half
+  //     the time, and what then limits the tile feed is the number of bytes in flight per CU;
+  //   dense-like lists (at least half of the blocks kept, so neighbouring query blocks share most
+  //     tiles and L2 serves them): 3-slot ring, 3 workgroups per CU, for the extra wave per SIMD.
+  const bool dense_like = 2 * (long long)kmax >= s.nb;
+#define USV_ATTN_CASE(DD, F32)                                                                         \
+  return dense_like ? run<DD, F32, 3, 3>(q, k, v, s, idx, cnt, kmax, scale, out, lse, st)              \
+                    : run<DD, F32, 5, 2>(q, k, v, s, idx, cnt, kmax, scale, out, lse, st)
+  if (s.d == 128) {
+    if (out_f32) USV_ATTN_CASE(128, true);
+    USV_ATTN_CASE(128, false);
+  }
+  if (out_f32) USV_ATTN_CASE(64, true);
+  USV_ATTN_CASE(64, false);
+#undef USV_ATTN_CASE
 }
 
 }  // namespace usv
