@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of the attention output (inputs are the workload's dtype)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (untimed) so that a rocprofv3 --pmc run of this "
+                         "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
     return ap.parse_args()
 
@@ -81,6 +84,16 @@ def cpu_baseline(w, Q, K, V, n_heads):
         "seconds": dt,
         "ms_per_call_extrapolated": dt * 1e3 * (w.batch * w.heads) / n_heads,
     }
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per attention launch from the rocprofv3 --pmc runs summarised under profiles/ (null if none)."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload_name, {}).get("attn_hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
 
 
 def main():
@@ -133,6 +146,13 @@ def main():
         usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=out)
         if events is not None:
             events[3].record()
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -187,7 +207,7 @@ def main():
             "peak": PEAK_BF16_TFLOPS if w.dtype == "bf16" else 157.3,
             "unit": "TFLOP/s",
             "frac": flop / (avg[2] * 1e-3) / 1e12 / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else 157.3),
-            "traffic": None,
+            "traffic": measured_traffic(w.name),
             "avg_launch_ms": float(avg[2]),
         },
     }
