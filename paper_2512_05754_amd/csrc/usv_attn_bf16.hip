@@ -248,14 +248,16 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
 
   // One tile.  PHASE = n % SLOTS is a compile-time constant so that every LDS offset of the ring
   // folds into the instruction.  On entry K(n) is in LDS and visible to every wave and the slot of
-  // V(n-1) is free.  A freed slot of item e is refilled with item e + SLOTS.
-  auto tile_step = [&](auto phase_c, int n) {
+  // V(n-1) is free.  A freed slot of item e is refilled with item e + SLOTS.  STEADY (compile time)
+  // says that tile n+LEAD exists, which spares the main loop every end-of-list check.
+  const int partial_j = (Nv % kBlock) ? (Nv / kBlock) : -1;  // the only block with padded keys, if any
+  auto tile_step = [&](auto phase_c, auto steady_c, int n) {
     constexpr int phase = decltype(phase_c)::value;
     constexpr int kslot = (2 * phase) % kSlots, vslot = (2 * phase + 1) % kSlots;
     constexpr int freed_v = (2 * phase + kSlots - 1) % kSlots;  // slot of item 2n-1 = V(n-1)
     const int j = jq[0];
     const int j_pre = jq[LEAD];
-    const bool steady = n + LEAD < n_list;
+    const bool steady = decltype(steady_c)::value || n + LEAD < n_list;
     if (steady) issue_k(j_pre, freed_v);  // item 2n-1+SLOTS = K(n+LEAD)
 
     // ---- S^T = K Q^T over this wave's 32 keys --------------------------------------------
@@ -273,12 +275,11 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
 #pragma unroll
         for (int t = 0; t < KB; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kb + kfrag[t0 + t]);
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
-        // s_setprio also fences the compiler's scheduler, which keeps each batch together:
-        // four reads, one wait, four back-to-back MFMAs that go first on the matrix pipe
-        __builtin_amdgcn_s_setprio(2);
+        // the fences keep each batch together: reads, one wait, back-to-back MFMAs
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < KB; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t0 + t], s, 0, 0, 0);
-        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     // V(n) has landed; only the SLOTS-2 items requested after it may still be in flight (near the
@@ -300,9 +301,8 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     jq[LEAD] = list_at(n + 1 + LEAD);
 
     // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
-    const int nkeys = Nv - j * kBlock;  // valid keys in this tile (>= 64 except in the last block)
-    if (nkeys < kBlock) {
-      const int lim = nkeys - (kh * 32 + 4 * g);
+    if (j == partial_j) {
+      const int lim = (Nv % kBlock) - (kh * 32 + 4 * g);  // valid keys of the tile ahead of this lane's first
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = (8 * (r >> 2) + (r & 3)) < lim ? s[r] : -INFINITY;
     }
@@ -370,13 +370,13 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
             __builtin_memcpy(&vf[dd][t], &both, sizeof(bf16x8));
           }
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
-        __builtin_amdgcn_s_setprio(2);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int dd = 0; dd < VB; ++dd)
 #pragma unroll
           for (int t = 0; t < 2; ++t)
             o[ds0 + dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dd][t], pf[t], o[ds0 + dd], 0, 0, 0);
-        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 
@@ -387,13 +387,34 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
       __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();  // ... for every wave; and nobody reads V(n) any more
   };
-  for (int n = 0; n < n_list; n += kSlots) {
-    tile_step(std::integral_constant<int, 0>{}, n);
-    if (n + 1 < n_list) tile_step(std::integral_constant<int, 1>{}, n + 1);
-    if (n + 2 < n_list) tile_step(std::integral_constant<int, 2>{}, n + 2);
+  {
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    using P3 = std::integral_constant<int, 3>;
+    using P4 = std::integral_constant<int, 4>;
+    int n = 0;
+    for (; n + kSlots + LEAD <= n_list; n += kSlots) {  // whole rounds of the ring, no end-of-list checks
+      tile_step(P0{}, std::true_type{}, n);
+      tile_step(P1{}, std::true_type{}, n + 1);
+      tile_step(P2{}, std::true_type{}, n + 2);
+      if constexpr (kSlots >= 5) {
+        tile_step(P3{}, std::true_type{}, n + 3);
+        tile_step(P4{}, std::true_type{}, n + 4);
+      }
+    }
+    // the last, partial round (n is a multiple of SLOTS here, so the phases line up)
+    if (n < n_list) tile_step(P0{}, std::false_type{}, n);
+    if (n + 1 < n_list) tile_step(P1{}, std::false_type{}, n + 1);
+    if (n + 2 < n_list) tile_step(P2{}, std::false_type{}, n + 2);
     if constexpr (kSlots >= 5) {
-      if (n + 3 < n_list) tile_step(std::integral_constant<int, 3>{}, n + 3);
-      if (n + 4 < n_list) tile_step(std::integral_constant<int, 4>{}, n + 4);
+      if (n + 3 < n_list) tile_step(P3{}, std::false_type{}, n + 3);
+      if (n + 4 < n_list) tile_step(P4{}, std::false_type{}, n + 4);
+    }
+    // up to SLOTS + LEAD - 1 tiles can remain: LEAD - 1 more
+    static_assert(LEAD <= 2, "one extra tile after the partial round");
+    if constexpr (LEAD == 2) {
+      if (n + kSlots < n_list) tile_step(P0{}, std::false_type{}, n + kSlots);
     }
   }
 
