@@ -221,6 +221,9 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     for (int r = 0; r < 16; ++r) o[ds][r] = 0.f;
   float m = -INFINITY;  // running reference max (log2 domain), identical in both lane halves
   float l = 0.f;        // this lane's partial row sum (its 16 keys per tile)
+  // derived from m, refreshed only when m moves (rare): the exponent offset and the raise threshold
+  float neg_m = 0.f;            // -m, or 0 while every key seen so far was masked (m = -inf)
+  float m_raise = -INFINITY;    // m + kRescaleSlack
 
   // per-lane LDS byte offsets of the fragment reads (loop invariant)
   int kfrag[KSTEPS];
@@ -312,19 +315,21 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     {
       float lo, hi;
       both_halves(max16(s), lo, hi);
-      mx = fmaxf(lo, hi) * scale_log2e;
+      asm("v_max_f32 %0, %1, %2" : "=v"(mx) : "v"(lo), "v"(hi));  // no NaN-quieting moves: never NaN
+      mx *= scale_log2e;
     }
-    if (__any(mx > m + kRescaleSlack)) {  // wave-uniform; always taken on the first live tile
+    if (__any(mx > m_raise)) {  // wave-uniform; always taken on the first live tile
       const float m_new = fmaxf(m, mx);
       const float alpha = fast_exp2(m - (m_new == -INFINITY ? 0.f : m_new));  // m = -inf -> 0
       m = m_new;
+      neg_m = m == -INFINITY ? 0.f : -m;
+      m_raise = m + kRescaleSlack;
       l *= alpha;
 #pragma unroll
       for (int ds = 0; ds < DSUB; ++ds)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[ds][r] *= alpha;
     }
-    const float neg_m = m == -INFINITY ? 0.f : -m;  // every key of this half masked so far
     // P^T of this wave's 32 keys, rounded to bf16 and packed two per register: the same registers
     // feed the row sum (v_dot2 with ones) and, as they stand, the B operand of the second product
     typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned uint4v;
