@@ -173,6 +173,20 @@ def test_keep_all_equals_dense_attention(usv, dtype, d):
         gu.assert_attn_close(gu.down(out)[0, h, :Nv], O, dtype, False, "dense")
 
 
+@pytest.mark.parametrize("nb,k", [(200, 70), (200, 67), (140, 100), (130, 129), (330, 64), (330, 65)])
+def test_long_lists_cross_the_index_reload_boundary(usv, nb, k):
+    """Lists longer than 64 entries (the kernel keeps 64 block ids in a register and reloads), in both
+    launch shapes (k < nb/2: deep ring; k >= nb/2: three workgroups per CU), with a padded last block."""
+    w = Workload(f"long_{nb}_{k}", 1, 1, nb * 64 - 11, 128, "bf16", 2.0, k, seed=71 + nb + k)
+    (Q, K, V), S, idx, cnt, out, lse = run_pipeline(usv, w, out_dtype=torch.float32)
+    ridx, rcnt = orc.select_topk(S, w.keep, w.seq_valid)
+    assert np.array_equal(idx, ridx) and np.array_equal(cnt, rcnt)
+    blocks = [0, 1, nb // 2, nb - 2, nb - 1]
+    ref = gu.oracle_attn_blocks(Q[0, 0], K[0, 0], V[0, 0], ridx[0, 0], rcnt[0, 0], w.seq_valid, blocks)
+    got = np.stack([gu.down(out[0, 0, i * 64:(i + 1) * 64]) for i in blocks])
+    gu.assert_attn_close(got, np.stack([ref[i][0] for i in blocks]), "bf16", False, w.name)
+
+
 def test_online_softmax_survives_large_logit_offsets(usv):
     """Keys shifted by a large common vector: every logit of a row moves by the same amount."""
     w = Workload("shift", 1, 1, 8 * 64, 128, "bf16", 0.0, 8, seed=41)
