@@ -2,9 +2,8 @@
 // paper Sections 2.2 and 3.2).  Two kernels:
 //   pool_means   HBM-bound: reads Q and K once with 16-byte coalesced loads, reduces each
 //                64-token cube to its fp32 mean over the valid tokens.
-//   score_gemm   S = Qm Km^T / sqrt(d) per head in fp32 (LDS-tiled FMA; the contraction is
-//                tiny next to the read of Q and K, so it stays off the bf16 matrix cores to
-//                keep the scores at fp32 accuracy).
+//   score_gemm   S = Qm Km^T / sqrt(d) per head on the fp32 matrix cores (fp32 operands and
+//                accumulation: the scores keep fp32 accuracy; bf16 MFMA would not).
 #include "usv_internal.h"
 
 namespace usv {
@@ -80,70 +79,64 @@ __global__ __launch_bounds__(kPoolThreads) void pool_means(const T* __restrict__
   }
 }
 
-// S[bh, i, j] = sum_c Qm[bh,i,c] Km[bh,j,c] * rsqrt_d.  64x64 output tile per workgroup of 256
-// threads; thread (ty, tx) owns the 4x4 patch rows ty+16a, cols tx+16b (interleaved so that LDS
-// reads of consecutive lanes hit consecutive rows with an odd-ish padded stride).
+// S[bh, i, j] = sum_c Qm[bh,i,c] Km[bh,j,c] * rsqrt_d on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32: fp32 operands and accumulation, so the scores keep fp32 accuracy).
+// 64x64 output tile per workgroup, one 32x32 quadrant per wave; the pooled means are staged in LDS
+// 64 channels at a time.  An MFMA step contracts 2 channels, one per 32-lane half; which channels a
+// step takes is free as long as both operands agree, so half g takes channels 32 g + t at step t
+// and every lane reads its operands as contiguous 16-byte pieces.
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
 template <int D>
 __global__ __launch_bounds__(256) void score_gemm(const float* __restrict__ qm, const float* __restrict__ km,
                                                   float* __restrict__ scores, int nb, int nb_valid,
                                                   float rsqrt_d) {
   constexpr int KC = 64;        // channels staged per pass
-  constexpr int LD = KC + 4;
-  __shared__ float As[64 * LD];
-  __shared__ float Bs[64 * LD];
+  constexpr int LD = KC + 4;    // row stride in floats: 16-byte reads of 32 consecutive rows spread over the banks
+  __shared__ __attribute__((aligned(16))) float As[64 * LD];
+  __shared__ __attribute__((aligned(16))) float Bs[64 * LD];
   const int bh = blockIdx.z;
   const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
   const float* qbase = qm + (long long)bh * nb * D;
   const float* kbase = km + (long long)bh * nb * D;
   const int tid = threadIdx.x;
-  const int ty = tid / 16, tx = tid % 16;
-  float acc[4][4];
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;  // this wave's quadrant
+  const int r = lane & 31, g = lane >> 5;
+  f32x16 acc;
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
-#pragma unroll
-    for (int b = 0; b < 4; ++b) acc[a][b] = 0.f;
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   for (int kc = 0; kc < D; kc += KC) {
     if (kc) __syncthreads();
     // stage both 64 x KC tiles (zero rows beyond nb)
     for (int e = tid; e < 64 * (KC / 4); e += 256) {
-      const int r = e / (KC / 4), c = (e % (KC / 4)) * 4;
+      const int row = e / (KC / 4), c = (e % (KC / 4)) * 4;
       float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
-      if (i0 + r < nb) a = *reinterpret_cast<const float4*>(qbase + (long long)(i0 + r) * D + kc + c);
-      if (j0 + r < nb) b = *reinterpret_cast<const float4*>(kbase + (long long)(j0 + r) * D + kc + c);
-      *reinterpret_cast<float4*>(As + r * LD + c) = a;
-      *reinterpret_cast<float4*>(Bs + r * LD + c) = b;
+      if (i0 + row < nb) a = *reinterpret_cast<const float4*>(qbase + (long long)(i0 + row) * D + kc + c);
+      if (j0 + row < nb) b = *reinterpret_cast<const float4*>(kbase + (long long)(j0 + row) * D + kc + c);
+      *reinterpret_cast<float4*>(As + row * LD + c) = a;
+      *reinterpret_cast<float4*>(Bs + row * LD + c) = b;
     }
     __syncthreads();
-#pragma unroll 4
-    for (int c = 0; c < KC; c += 4) {
-      float4 av[4], bv[4];
+    const float* ap = As + (wi + r) * LD + 32 * g;
+    const float* bp = Bs + (wj + r) * LD + 32 * g;
 #pragma unroll
-      for (int a = 0; a < 4; ++a) av[a] = *reinterpret_cast<const float4*>(As + (ty + 16 * a) * LD + c);
-#pragma unroll
-      for (int b = 0; b < 4; ++b) bv[b] = *reinterpret_cast<const float4*>(Bs + (tx + 16 * b) * LD + c);
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          acc[a][b] = fmaf(av[a].x, bv[b].x, acc[a][b]);
-          acc[a][b] = fmaf(av[a].y, bv[b].y, acc[a][b]);
-          acc[a][b] = fmaf(av[a].z, bv[b].z, acc[a][b]);
-          acc[a][b] = fmaf(av[a].w, bv[b].w, acc[a][b]);
-        }
+    for (int t = 0; t < 32; t += 4) {
+      const float4 a = *reinterpret_cast<const float4*>(ap + t);
+      const float4 b = *reinterpret_cast<const float4*>(bp + t);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
     }
   }
+  // accumulator register e of lane (r, g): row wi + 8 (e/4) + 4 g + (e%4), column wj + r
   float* out = scores + (long long)bh * nb * nb;
+  const int j = j0 + wj + r;
 #pragma unroll
-  for (int a = 0; a < 4; ++a) {
-    const int i = i0 + ty + 16 * a;
-    if (i >= nb) continue;
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int j = j0 + tx + 16 * b;
-      if (j >= nb) continue;
-      const bool live = i < nb_valid && j < nb_valid;
-      out[(long long)i * nb + j] = live ? acc[a][b] * rsqrt_d : -INFINITY;
-    }
+  for (int e = 0; e < 16; ++e) {
+    const int i = i0 + wi + 8 * (e >> 2) + 4 * g + (e & 3);
+    if (i < nb && j < nb) out[(long long)i * nb + j] = (i < nb_valid && j < nb_valid) ? acc[e] * rsqrt_d : -INFINITY;
   }
 }
 
