@@ -41,6 +41,8 @@ def parse():
                     help="also run one plain 256 MiB device copy (untimed) so that a rocprofv3 --pmc run of this "
                          "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
+    ap.add_argument("--no-mfma-peak", action="store_true",
+                    help="skip the MFMA-only peak probe (paper_2512_05754_amd/tools/mfma_peak, ~1 s)")
     return ap.parse_args()
 
 
@@ -96,11 +98,27 @@ def measured_traffic(workload_name):
         return None
 
 
+def mfma_only_peak():
+    """Runs the MFMA-only probe (a child process, before this process touches the GPU); None if it is not built."""
+    import subprocess
+
+    tool = os.path.join(ROOT, "paper_2512_05754_amd", "tools", "mfma_peak")
+    if not os.path.exists(tool):
+        return None
+    try:
+        res = subprocess.run([tool], capture_output=True, text=True, timeout=60)
+        return json.loads(res.stdout.strip().splitlines()[-1]) if res.returncode == 0 else None
+    except (OSError, ValueError, IndexError, subprocess.TimeoutExpired):
+        return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    peak_probe = None if args.no_mfma_peak else mfma_only_peak()
 
     import numpy as np
     import torch
@@ -211,6 +229,9 @@ def main():
             "avg_launch_ms": float(avg[2]),
         },
     }
+    if peak_probe is not None:
+        # context for `frac`: what an MFMA-only loop sustains on this GPU (the clock drops with operand activity)
+        result["roofline"]["measured_mfma_only_tflops"] = peak_probe
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, Q, K, V, args.cpu_sample_heads)
     print(json.dumps(result))

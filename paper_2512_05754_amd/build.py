@@ -44,5 +44,23 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
     return LIB_PATH
 
 
+TOOLS_DIR = os.path.join(PKG_DIR, "tools")
+PEAK_TOOL = os.path.join(TOOLS_DIR, "mfma_peak")
+
+
+def build_tools(verbose: bool = True) -> str:
+    """Compiles the stand-alone MFMA-only peak probe (measurement aid; not part of libusv.so)."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument", "-Wno-unused-result", os.path.join(TOOLS_DIR, "mfma_peak.hip"),
+           "-o", PEAK_TOOL]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return PEAK_TOOL
+
+
 if __name__ == "__main__":
     print(build_library(extra_flags=tuple(sys.argv[1:])))
+    print(build_tools())
