@@ -22,6 +22,12 @@ description; Figure 2's "top-k cube selection"):
                     small N (pins the gathered form above).
   dense_attn        softmax(Q K^T / sqrt(d_k)) V, the keep-all limit.
 
+  cube_token_order / cube_gather / cube_scatter
+                    the step either side of the path (Figure 2, right: tokens are
+                    "partitioned into local 3D cubes" on the way in and "broadcast
+                    back to the full token grid" on the way out): the permutation
+                    between raster (t, h, w) token order and cube-major order.
+
 Every function is pinned by tests/test_oracle_pins.py against something other
 than itself (closed forms, torch's scaled_dot_product_attention in fp64,
 pure-Python brute force, invariants).  No function here is "parity unpinned".
@@ -35,6 +41,12 @@ Readings taken where the paper is silent (also listed in the design notes):
     ascending cube index, unused slots hold -1.
   * log M is added to the scaled logit (it is 0 or -inf, so where the division
     by sqrt(d_k) is drawn makes no difference).
+  * cube-major order of a T x H x W grid tiled by ct x ch x cw cubes: cubes that
+    lie wholly inside the grid come first, in raster order of their cube
+    coordinates, one per 64-token block; the cubes cut by the grid boundary
+    follow in the same raster order, packed without gaps (so only the tail of
+    the sequence is padding, which is what seq_valid expresses); inside a cube,
+    tokens are in raster order of their local coordinates.
   * padded keys (token >= seq_valid) are masked; padded query rows output 0 and
     lse = -inf; a query cube with an empty list outputs 0.
 """
@@ -201,3 +213,44 @@ def block_sparse_attn(Q, K, V, idx, cnt, seq_valid, scale=None, block=BLOCK):
                 Q[b, h], K[b, h], V[b, h], idx[b, h], cnt[b, h], seq_valid, scale, None, block
             )
     return O, lse
+
+
+# --------------------------------------------------------------------------- #
+# either side of the path: raster <-> cube-major token order (Figure 2, right)
+# --------------------------------------------------------------------------- #
+def cube_token_order(grid, cube):
+    """order[p] = raster index t*H*W + h*W + w of the token at cube-major position p.
+
+    grid = (T, H, W), cube = (ct, ch, cw).  Built by walking the cubes one by one: first every
+    cube that fits wholly inside the grid, then the ones the boundary cuts, both in raster order
+    of the cube coordinates; a cube's tokens in raster order of their local coordinates."""
+    T, H, W = grid
+    ct, ch, cw = cube
+    cubes = [(a, b, c) for a in range(0, T, ct) for b in range(0, H, ch) for c in range(0, W, cw)]
+    whole = [q for q in cubes if q[0] + ct <= T and q[1] + ch <= H and q[2] + cw <= W]
+    cut = [q for q in cubes if q not in set(whole)]
+    order = []
+    for (a, b, c) in whole + cut:
+        for t in range(a, min(a + ct, T)):
+            for h in range(b, min(b + ch, H)):
+                for w in range(c, min(c + cw, W)):
+                    order.append((t * H + h) * W + w)
+    return np.asarray(order, dtype=np.int64)
+
+
+def cube_gather(X, grid, cube, seq_len):
+    """Raster-ordered X [..., T*H*W, d] -> cube-major [..., seq_len, d]; rows past T*H*W are zero."""
+    X = np.asarray(X)
+    order = cube_token_order(grid, cube)
+    out = np.zeros(X.shape[:-2] + (seq_len, X.shape[-1]), dtype=X.dtype)
+    out[..., : len(order), :] = X[..., order, :]
+    return out
+
+
+def cube_scatter(Y, grid, cube):
+    """Cube-major Y [..., seq_len, d] -> raster order [..., T*H*W, d] (the padding rows are dropped)."""
+    Y = np.asarray(Y)
+    order = cube_token_order(grid, cube)
+    out = np.empty(Y.shape[:-2] + (len(order), Y.shape[-1]), dtype=Y.dtype)
+    out[..., order, :] = Y[..., : len(order), :]
+    return out

@@ -315,3 +315,81 @@ def test_generator_is_deterministic_and_shaped():
     assert [synth.sweep(r).keep for r in synth.SWEEP_RATIOS] == [512, 256, 128, 51, 25]
     assert (synth.WAN14_720P.seq_len, synth.WAN14_720P.nb) == (75648, 1182)
     assert synth.keep_count(0.05, 1182) == 59
+
+
+# --------------------------------------------------------------------------- #
+# raster <-> cube-major token order (Figure 2, right)
+# --------------------------------------------------------------------------- #
+GOLDEN = __import__("os").path.join(__import__("os").path.dirname(__file__), "golden")
+
+
+def _golden_order(name):
+    with open(f"{GOLDEN}/{name}") as f:
+        rows = [ln for ln in f if ln.strip() and not ln.startswith("#")]
+    return np.array(rows[0].split(), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name,grid,cube", [
+    ("cube_order_1x3x3_cube_1x2x2.txt", (1, 3, 3), (1, 2, 2)),
+    ("cube_order_3x2x5_cube_2x2x2.txt", (3, 2, 5), (2, 2, 2)),
+])
+def test_cube_order_hand_enumerated(name, grid, cube):
+    """Two small grids written out by hand.  Catches swapped axes, cut cubes placed before whole
+    ones, a cut cube's rows taken with the full cube's width."""
+    np.testing.assert_array_equal(orc.cube_token_order(grid, cube), _golden_order(name))
+
+
+@pytest.mark.parametrize("grid,cube", [((8, 8, 8), (4, 4, 4)), ((4, 12, 8), (2, 4, 8)), ((3, 16, 24), (1, 8, 8))])
+def test_cube_order_divisible_grid_is_a_reshape_transpose(grid, cube):
+    """With no cut cubes the order is NumPy's reshape + transpose of the raster index grid.
+    Catches a wrong nesting of the cube loops or of the loops inside a cube."""
+    T, H, W = grid
+    ct, ch, cw = cube
+    raster = np.arange(T * H * W).reshape(T // ct, ct, H // ch, ch, W // cw, cw)
+    expect = raster.transpose(0, 2, 4, 1, 3, 5).reshape(-1)
+    np.testing.assert_array_equal(orc.cube_token_order(grid, cube), expect)
+
+
+@pytest.mark.parametrize("grid", [(21, 30, 52), (5, 6, 7), (1, 9, 9), (7, 4, 4), (4, 4, 3)])
+def test_cube_order_structure_on_cut_grids(grid):
+    """Bijection; every whole cube is one aligned 64-block holding exactly a 4x4x4 box; the cut
+    cubes follow, each one's tokens consecutive, in raster order of their corner."""
+    T, H, W = grid
+    cube = (4, 4, 4)
+    order = orc.cube_token_order(grid, cube)
+    assert sorted(order.tolist()) == list(range(T * H * W))
+    t, h, w = order // (H * W), (order // W) % H, order % W
+    n_whole = (T // 4) * (H // 4) * (W // 4)
+    for b in range(n_whole):
+        sl = slice(64 * b, 64 * b + 64)
+        assert t[sl].max() - t[sl].min() == 3 and h[sl].max() - h[sl].min() == 3 and w[sl].max() - w[sl].min() == 3
+        assert t[sl].min() % 4 == 0 and h[sl].min() % 4 == 0 and w[sl].min() % 4 == 0
+    corners = np.stack([t // 4, h // 4, w // 4], axis=1)
+    tail = corners[64 * n_whole:]
+    if len(tail):
+        change = np.any(tail[1:] != tail[:-1], axis=1)
+        runs = tail[np.concatenate([[True], change])]
+        keys = [tuple(r) for r in runs]
+        assert len(set(keys)) == len(keys), "a cut cube's tokens are not consecutive"
+        assert keys == sorted(keys), "cut cubes are not in raster order"
+        # whole cubes never appear in the tail
+        assert all(not (a < T // 4 and b < H // 4 and c < W // 4) for a, b, c in keys)
+
+
+def test_cube_gather_scatter_roundtrip_and_padding():
+    """gather then scatter is the identity; padding rows are zero; a divisible grid matches the
+    reshape/transpose of the tensor itself.  Catches gather/scatter using the same direction."""
+    grid, cube = (5, 6, 7), (4, 4, 4)
+    n = 5 * 6 * 7
+    X = randn(2, 3, n, 8)
+    Y = orc.cube_gather(X, grid, cube, 256)
+    assert Y.shape == (2, 3, 256, 8) and np.all(Y[..., n:, :] == 0)
+    order = orc.cube_token_order(grid, cube)
+    np.testing.assert_array_equal(Y[1, 2, 17], X[1, 2, order[17]])
+    np.testing.assert_array_equal(orc.cube_scatter(Y, grid, cube), X)
+    X2 = randn(1, 1, 512, 4)
+    Y2 = orc.cube_gather(X2, (8, 8, 8), cube, 512)
+    expect = X2.reshape(2, 4, 2, 4, 2, 4, 4).transpose(0, 2, 4, 1, 3, 5, 6).reshape(1, 1, 512, 4)
+    np.testing.assert_array_equal(Y2, expect)
+    # a non-symmetric permutation: scatter must be the inverse, not the same map applied again
+    assert not np.array_equal(orc.cube_gather(Y2, (8, 8, 8), cube, 512), X2)
