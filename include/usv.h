@@ -8,9 +8,10 @@
  *   usv_select_topk       per query cube, the k best key cubes -> compact index list
  *   usv_block_sparse_attn softmax attention over only the listed key/value cubes
  *
- * Tokens are the flattened 3-D video latent, already ordered cube-major: the 64
- * tokens of one 4x4x4 spatio-temporal cube are consecutive, so "block i" is
- * tokens [64 i, 64 i + 64).
+ * Tokens are the flattened 3-D video latent, ordered cube-major: the 64 tokens
+ * of one 4x4x4 spatio-temporal cube are consecutive, so "block i" is tokens
+ * [64 i, 64 i + 64).  usv_cube_gather / usv_cube_scatter convert from and to the
+ * raster order a model holds its tokens in.
  *
  * Common conventions
  *   - Every pointer except the usv_shape is a DEVICE pointer to caller-owned
@@ -134,6 +135,60 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v,
                                  const usv_shape* shape, const int32_t* idx, const int32_t* cnt,
                                  int32_t kmax, float scale, int32_t out_dtype, void* out, float* lse,
                                  void* stream);
+
+/*
+ * Either side of the three stages: the token order (Figure 2, right: queries, keys
+ * and values are "partitioned into local 3D cubes"; the outputs are "broadcast back
+ * to the full token grid").  A model holds tokens in raster order of the latent
+ * grid, index (t*H + h)*W + w; the stages above want cube-major order.
+ *
+ * Cube-major order of a T x H x W grid tiled by ct x ch x cw cubes (ct*ch*cw = 64):
+ *   1. the cubes that lie wholly inside the grid, in raster order of their cube
+ *      coordinates (t/ct, h/ch, w/cw): whole cube number n is block n, tokens
+ *      [64 n, 64 n + 64);
+ *   2. then the cubes the grid boundary cuts, in the same raster order, packed
+ *      without gaps, so that the only padding is the tail [T*H*W, seq_len);
+ *   3. inside a cube, tokens in raster order of their local coordinates.
+ * The paper does not say how a grid that the cube does not divide is tiled; this
+ * reading keeps every whole cube one aligned block and leaves the padding where
+ * seq_valid expects it.
+ */
+
+/* Token grid and cube (host struct). */
+typedef struct {
+  int32_t T, H, W;    /* latent grid, T*H*W == shape->seq_valid */
+  int32_t ct, ch, cw; /* cube, ct*ch*cw == shape->block */
+} usv_grid;
+
+/* Element strides of a raster-ordered tensor whose channel index is contiguous
+ * (host struct): element (b, head, token, c) is at b*batch + head*head + token*token + c.
+ * Each stride times the element size must be a multiple of 16 bytes and rows must not
+ * overlap.  [B, Hh, Nv, d] is {Hh*Nv*d, Nv*d, d}; a projection output [B, Nv, Hh*d]
+ * is {Nv*Hh*d, d, Hh*d}. */
+typedef struct {
+  int64_t batch, head, token;
+} usv_strides;
+
+/* HOST helper: order[p] = raster index of the token at cube-major position p, for
+ * p in [0, T*H*W).  `order` is a host array of T*H*W int32.  Launches nothing. */
+usv_status usv_cube_token_order(const usv_grid* grid, int32_t* order);
+
+/*
+ * Raster -> cube-major (with padding).  cube[b,h,p,:] = raster[b,h,order[p],:] for
+ * p < T*H*W; rows T*H*W <= p < seq_len are written as zero.
+ * raster  : device, read only, laid out by `strides` (NULL = contiguous [B,Hh,Nv,d])
+ * shape   : seq_valid = T*H*W; dtype = element type of THIS tensor (an fp32
+ *           attention output is moved with dtype = USV_F32)
+ * cube    : [B, Hh, seq_len, d] contiguous (device, written); must not overlap raster
+ */
+usv_status usv_cube_gather(const void* raster, const usv_strides* strides, const usv_shape* shape,
+                           const usv_grid* grid, void* cube, void* stream);
+
+/* Cube-major -> raster, the inverse: raster[b,h,order[p],:] = cube[b,h,p,:] for
+ * p < T*H*W; the padding rows of `cube` are not read.  Arguments as above, with
+ * `raster` written and `cube` read only. */
+usv_status usv_cube_scatter(const void* cube, const usv_shape* shape, const usv_grid* grid,
+                            void* raster, const usv_strides* strides, void* stream);
 
 /* Static string for a status code. */
 const char* usv_status_string(int32_t status);

@@ -8,6 +8,9 @@ _BINDING_NAMES = (
     "block_scores",
     "select_topk",
     "block_sparse_attn",
+    "cube_token_order",
+    "cube_gather",
+    "cube_scatter",
     "workspace_bytes",
     "lib",
     "lib_path",

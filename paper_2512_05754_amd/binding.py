@@ -20,6 +20,9 @@ EXPORTED_SYMBOLS = (
     "usv_block_scores",
     "usv_select_topk",
     "usv_block_sparse_attn",
+    "usv_cube_token_order",
+    "usv_cube_gather",
+    "usv_cube_scatter",
     "usv_status_string",
     "usv_last_error",
 )
@@ -42,6 +45,14 @@ class UsvShape(ctypes.Structure):
         ("block", ctypes.c_int32),
         ("dtype", ctypes.c_int32),
     ]
+
+
+class UsvGrid(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "H", "W", "ct", "ch", "cw")]
+
+
+class UsvStrides(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("batch", "head", "token")]
 
 
 def lib_path() -> str:
@@ -69,6 +80,10 @@ def lib() -> ctypes.CDLL:
     L.usv_select_topk.restype, L.usv_select_topk.argtypes = i32, [vp, sp, i32, vp, i32, vp, vp, vp]
     L.usv_block_sparse_attn.restype = i32
     L.usv_block_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, i32, f32, i32, vp, vp, vp]
+    gp, stp = ctypes.POINTER(UsvGrid), ctypes.POINTER(UsvStrides)
+    L.usv_cube_token_order.restype, L.usv_cube_token_order.argtypes = i32, [gp, vp]
+    L.usv_cube_gather.restype, L.usv_cube_gather.argtypes = i32, [vp, stp, sp, gp, vp, vp]
+    L.usv_cube_scatter.restype, L.usv_cube_scatter.argtypes = i32, [vp, sp, gp, vp, stp, vp]
     L.usv_status_string.restype, L.usv_status_string.argtypes = ctypes.c_char_p, [i32]
     L.usv_last_error.restype, L.usv_last_error.argtypes = ctypes.c_char_p, []
     _lib = L
@@ -189,3 +204,57 @@ def block_sparse_attn(q, k, v, idx, cnt, seq_valid=None, scale=0.0, out=None, ls
         )
     )
     return (out, lse) if return_lse else out
+
+
+def _grid(grid, cube) -> UsvGrid:
+    return UsvGrid(*(int(x) for x in grid), *(int(x) for x in cube))
+
+
+def cube_token_order(grid, cube=(4, 4, 4)):
+    """usv_cube_token_order (host): int32 array, order[p] = raster index of the token at cube-major position p."""
+    import numpy as np
+
+    g = _grid(grid, cube)
+    order = np.full(max(int(grid[0]) * int(grid[1]) * int(grid[2]), 1), -1, dtype=np.int32)
+    _check(lib().usv_cube_token_order(ctypes.byref(g), order.ctypes.data_as(ctypes.c_void_p)))
+    return order
+
+
+def _raster(t: torch.Tensor, name: str):
+    """Pointer and element strides of a raster tensor [B, Hh, Nv, d] (any strides with the channel index contiguous)."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor (there is no CPU path)")
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError(f"{name} must be [B, Hh, Nv, d] with contiguous channels")
+    return t.data_ptr(), UsvStrides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def cube_gather(raster, grid, cube=(4, 4, 4), seq_len=None, out=None):
+    """usv_cube_gather: raster-ordered [B, Hh, T*H*W, d] (a strided view is fine) -> cube-major [B, Hh, seq_len, d]."""
+    B, Hh, Nv, d = raster.shape
+    if seq_len is None:
+        seq_len = -(-Nv // BLOCK) * BLOCK
+    if out is None:
+        out = torch.empty((B, Hh, seq_len, d), dtype=raster.dtype, device=raster.device)
+    if tuple(out.shape) != (B, Hh, seq_len, d) or out.dtype != raster.dtype:
+        raise ValueError("out must be [B, Hh, seq_len, d] of the input dtype")
+    sh = _shape_of(out, Nv)
+    ptr, st = _raster(raster, "raster")
+    g = _grid(grid, cube)
+    _check(lib().usv_cube_gather(ptr, ctypes.byref(st), ctypes.byref(sh), ctypes.byref(g), _dev(out, "cube"), _stream()))
+    return out
+
+
+def cube_scatter(cube_major, grid, cube=(4, 4, 4), out=None):
+    """usv_cube_scatter: cube-major [B, Hh, seq_len, d] -> raster order [B, Hh, T*H*W, d] (out may be a strided view)."""
+    B, Hh, N, d = cube_major.shape
+    Nv = int(grid[0]) * int(grid[1]) * int(grid[2])
+    if out is None:
+        out = torch.empty((B, Hh, Nv, d), dtype=cube_major.dtype, device=cube_major.device)
+    if tuple(out.shape) != (B, Hh, Nv, d) or out.dtype != cube_major.dtype:
+        raise ValueError("out must be [B, Hh, T*H*W, d] of the input dtype")
+    sh = _shape_of(cube_major, Nv)
+    ptr, st = _raster(out, "raster")
+    g = _grid(grid, cube)
+    _check(lib().usv_cube_scatter(_dev(cube_major, "cube"), ctypes.byref(sh), ctypes.byref(g), ptr, ctypes.byref(st), _stream()))
+    return out

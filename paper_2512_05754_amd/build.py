@@ -10,7 +10,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libusv.so")
-SOURCES = ("usv_api.hip", "usv_scores.hip", "usv_topk.hip", "usv_attn_f32.hip", "usv_attn_bf16.hip")
+SOURCES = ("usv_api.hip", "usv_scores.hip", "usv_topk.hip", "usv_attn_f32.hip", "usv_attn_bf16.hip",
+           "usv_reorder.hip")
 
 
 def hipcc() -> str:

@@ -65,6 +65,42 @@ usv_status hip_result(hipError_t e, const char* what) {
   return fail(USV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// Checks the grid against the shape and fills CubeGrid.
+usv_status check_grid(const usv_grid* g, const usv_shape* sh, usv::CubeGrid* out) {
+  if (!g) return fail(USV_ERR_INVALID_ARG, "grid is NULL");
+  if (g->T < 1 || g->H < 1 || g->W < 1) return fail(USV_ERR_INVALID_ARG, "grid extents must be >= 1");
+  if (g->ct < 1 || g->ch < 1 || g->cw < 1) return fail(USV_ERR_INVALID_ARG, "cube extents must be >= 1");
+  if ((long long)g->ct * g->ch * g->cw != usv::kBlock)
+    return fail(USV_ERR_UNSUPPORTED, "cube must hold 64 tokens (got %d x %d x %d)", g->ct, g->ch, g->cw);
+  const long long tokens = (long long)g->T * g->H * g->W;
+  if (tokens > (long long)USV_MAX_BLOCKS * usv::kBlock)
+    return fail(USV_ERR_UNSUPPORTED, "grid holds more than %d tokens", USV_MAX_BLOCKS * usv::kBlock);
+  if (sh && tokens != sh->seq_valid)
+    return fail(USV_ERR_INVALID_ARG, "grid holds %lld tokens but seq_valid is %d", tokens, sh->seq_valid);
+  *out = usv::CubeGrid{g->T, g->H, g->W, g->ct, g->ch, g->cw, g->T / g->ct, g->H / g->ch, g->W / g->cw};
+  return USV_OK;
+}
+
+// Raster strides in bytes (contiguous [B, Hh, Nv, d] when `st` is NULL), checked for 16-byte rows that do not overlap.
+usv_status check_strides(const usv_strides* st, const usv::Dims& s, long long out_bytes[3]) {
+  const long long esz = s.bf16 ? 2 : 4;
+  long long e[3] = {(long long)s.Hh * s.Nv * s.d, (long long)s.Nv * s.d, (long long)s.d};
+  if (st) {
+    e[0] = st->batch;
+    e[1] = st->head;
+    e[2] = st->token;
+  }
+  for (int i = 0; i < 3; ++i) {
+    if (e[i] < 0 || e[i] > (1LL << 40)) return fail(USV_ERR_INVALID_ARG, "raster strides must be in [0, 2^40] elements");
+    if ((e[i] * esz) % 16 != 0) return fail(USV_ERR_INVALID_ARG, "raster strides must be multiples of 16 bytes");
+    out_bytes[i] = e[i] * esz;
+  }
+  if (e[2] < s.d) return fail(USV_ERR_INVALID_ARG, "token stride (%lld) is smaller than head_dim: rows overlap", e[2]);
+  if (s.Hh > 1 && e[1] < s.d) return fail(USV_ERR_INVALID_ARG, "head stride (%lld) is smaller than head_dim: rows overlap", e[1]);
+  if (s.B > 1 && e[0] < s.d) return fail(USV_ERR_INVALID_ARG, "batch stride (%lld) is smaller than head_dim: rows overlap", e[0]);
+  return USV_OK;
+}
+
 #define USV_TRY(expr)                    \
   do {                                   \
     const usv_status st__ = (expr);      \
@@ -136,6 +172,45 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v, co
                                     static_cast<const float*>(v), s, idx, cnt, kmax, scale, static_cast<float*>(out),
                                     lse, st);
   return hip_result(e, "usv_block_sparse_attn launch");
+}
+
+usv_status usv_cube_token_order(const usv_grid* grid, int32_t* order) {
+  usv::CubeGrid g;
+  USV_TRY(check_grid(grid, nullptr, &g));
+  if (!order) return fail(USV_ERR_INVALID_ARG, "order is NULL");
+  for (int t = 0; t < g.T; ++t)
+    for (int h = 0; h < g.H; ++h)
+      for (int w = 0; w < g.W; ++w) order[usv::cube_position(g, t, h, w)] = (t * g.H + h) * g.W + w;
+  g_err[0] = '\0';
+  return USV_OK;
+}
+
+usv_status usv_cube_gather(const void* raster, const usv_strides* strides, const usv_shape* shape,
+                           const usv_grid* grid, void* cube, void* stream) {
+  usv::Dims s;
+  usv::CubeGrid g;
+  long long sb[3];
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_grid(grid, shape, &g));
+  USV_TRY(check_strides(strides, s, sb));
+  USV_TRY(check_ptr(raster, "raster"));
+  USV_TRY(check_ptr(cube, "cube"));
+  return hip_result(usv::launch_cube_move(true, raster, cube, g, s, sb[0], sb[1], sb[2], static_cast<hipStream_t>(stream)),
+                    "usv_cube_gather launch");
+}
+
+usv_status usv_cube_scatter(const void* cube, const usv_shape* shape, const usv_grid* grid, void* raster,
+                            const usv_strides* strides, void* stream) {
+  usv::Dims s;
+  usv::CubeGrid g;
+  long long sb[3];
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_grid(grid, shape, &g));
+  USV_TRY(check_strides(strides, s, sb));
+  USV_TRY(check_ptr(cube, "cube"));
+  USV_TRY(check_ptr(raster, "raster"));
+  return hip_result(usv::launch_cube_move(false, cube, raster, g, s, sb[0], sb[1], sb[2], static_cast<hipStream_t>(stream)),
+                    "usv_cube_scatter launch");
 }
 
 const char* usv_status_string(int32_t status) {

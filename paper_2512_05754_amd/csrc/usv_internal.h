@@ -20,6 +20,13 @@ struct Dims {
   long long bh() const { return (long long)B * Hh; }
 };
 
+// Token grid T x H x W tiled by ct x ch x cw cubes; Tf, Hf, Wf = whole cubes along each axis.
+struct CubeGrid {
+  int T, H, W, ct, ch, cw, Tf, Hf, Wf;
+};
+// Cube-major position of raster token (t, h, w): the one definition the kernel and the host helper share.
+__host__ __device__ long long cube_position(const CubeGrid& g, int t, int h, int w);
+
 // Workgroups are dealt round-robin to the 8 XCDs.  Map the hardware block id to a logical
 // work id so that each XCD walks one contiguous range of work items (consecutive heads and
 // query blocks share K/V in that XCD's L2).  `per_xcd` = ceil(total / 8); ids >= total idle.
@@ -37,5 +44,9 @@ hipError_t launch_attn_f32(const float* q, const float* k, const float* v, const
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
                             hipStream_t st);
+
+// gather: raster -> cube-major (+ zeroed padding); else cube-major -> raster.  Strides of the raster tensor in BYTES.
+hipError_t launch_cube_move(bool gather, const void* src, void* dst, const CubeGrid& g, const Dims& s, long long sb,
+                            long long sh, long long st, hipStream_t stream);
 
 }  // namespace usv

@@ -95,3 +95,54 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 1, 64, 64)
     with pytest.raises(TypeError, match="GPU tensor"):
         binding.block_scores(x, x)
+
+
+# --------------------------------------------------------------------------- #
+# raster <-> cube-major order: the closed form the kernel uses, checked on the host
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("grid,cube", [
+    ((21, 30, 52), (4, 4, 4)), ((21, 45, 80), (4, 4, 4)), ((8, 8, 8), (4, 4, 4)), ((5, 6, 7), (4, 4, 4)),
+    ((1, 9, 9), (4, 4, 4)), ((3, 3, 3), (4, 4, 4)), ((7, 4, 4), (4, 4, 4)), ((4, 4, 3), (4, 4, 4)),
+    ((3, 17, 19), (1, 8, 8)), ((5, 9, 20), (2, 4, 8)), ((2, 2, 130), (1, 1, 64)), ((9, 5, 6), (16, 2, 2)),
+])
+def test_cube_token_order_closed_form_equals_oracle_enumeration(grid, cube):
+    """usv_cube_token_order evaluates the same closed-form position function as the kernel; the
+    oracle walks the cubes one by one."""
+    import numpy as np
+
+    from oracle import usv_oracle as orc
+
+    got = binding.cube_token_order(grid, cube)
+    np.testing.assert_array_equal(got.astype(np.int64), orc.cube_token_order(grid, cube))
+
+
+@pytest.mark.parametrize(
+    "grid,shape_kw,strides,status",
+    [
+        ((4, 4, 4, 4, 4, 2), {}, None, "USV_ERR_UNSUPPORTED"),            # cube of 32 tokens
+        ((4, 4, 4, 0, 4, 4), {}, None, "USV_ERR_INVALID_ARG"),            # zero cube extent
+        ((0, 4, 4, 4, 4, 4), {}, None, "USV_ERR_INVALID_ARG"),            # empty grid
+        ((4, 4, 5, 4, 4, 4), {}, None, "USV_ERR_INVALID_ARG"),            # 80 tokens but seq_valid = 64
+        ((4, 4, 4, 4, 4, 4), {}, (64 * 64, 64, 32), "USV_ERR_INVALID_ARG"),   # token stride < head_dim
+        ((4, 4, 4, 4, 4, 4), {}, (64 * 64, 64 * 64, 66), "USV_ERR_INVALID_ARG"),  # rows not 16-byte aligned
+        ((4, 4, 4, 4, 4, 4), dict(head_dim=96), None, "USV_ERR_UNSUPPORTED"),
+    ],
+)
+def test_cube_move_rejects_bad_arguments_before_launch(grid, shape_kw, strides, status):
+    L = binding.lib()
+    sh = shape(seq_len=64, seq_valid=64, **shape_kw)
+    g = binding.UsvGrid(*grid)
+    st = None if strides is None else ctypes.byref(binding.UsvStrides(*strides))
+    for rc in (L.usv_cube_gather(FAKE, st, ctypes.byref(sh), ctypes.byref(g), FAKE, None),
+               L.usv_cube_scatter(FAKE, ctypes.byref(sh), ctypes.byref(g), FAKE, st, None)):
+        assert L.usv_status_string(rc).decode() == status
+    assert L.usv_last_error()
+
+
+def test_cube_move_rejects_null_and_misaligned_pointers():
+    L = binding.lib()
+    sh, g = shape(seq_len=64, seq_valid=64), binding.UsvGrid(4, 4, 4, 4, 4, 4)
+    assert L.usv_cube_gather(None, None, ctypes.byref(sh), ctypes.byref(g), FAKE, None) == 1
+    assert L.usv_cube_gather(FAKE, None, ctypes.byref(sh), ctypes.byref(g), FAKE + 4, None) == 1
+    assert L.usv_cube_scatter(FAKE, ctypes.byref(sh), None, FAKE, None, None) == 1
+    assert L.usv_cube_token_order(ctypes.byref(g), None) == 1
