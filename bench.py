@@ -41,6 +41,9 @@ def parse():
                     help="also run one plain 256 MiB device copy (untimed) so that a rocprofv3 --pmc run of this "
                          "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
+    ap.add_argument("--path", default="attention", choices=["attention", "reorder"],
+                    help="attention: the three-stage hot path (the headline metric); reorder: the raster <-> "
+                         "cube-major token reorder either side of it (gather Q, K, V + scatter O)")
     ap.add_argument("--no-mfma-peak", action="store_true",
                     help="skip the MFMA-only peak probe (paper_2512_05754_amd/tools/mfma_peak, ~1 s)")
     return ap.parse_args()
@@ -112,11 +115,97 @@ def mfma_only_peak():
         return None
 
 
+GRIDS = {"wan1.3b_480p_keep10": (21, 30, 52), "wan14b_720p_keep5": (21, 45, 80)}
+
+
+def reorder_main(args):
+    """Times usv_cube_gather (Q, K, V) + usv_cube_scatter (O) at the workload's latent grid; HBM roofline."""
+    import numpy as np
+    import torch
+
+    import paper_2512_05754_amd as usv
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = pick_workload(args.workload)
+    if w.name not in GRIDS:
+        print(f"bench.py: --path reorder needs a workload with a latent grid ({sorted(GRIDS)})", file=sys.stderr)
+        sys.exit(2)
+    grid, cube = GRIDS[w.name], (4, 4, 4)
+    B, Hh, Nv, N, d = w.batch, w.heads, w.seq_valid, w.seq_len, w.head_dim
+    gen = torch.Generator(device=dev).manual_seed(w.seed)
+    raster = [torch.randn((B, Hh, Nv, d), device=dev, generator=gen).to(torch.bfloat16) for _ in range(3)]
+    cubes = [torch.empty((B, Hh, N, d), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+    o_cube = torch.randn((B, Hh, N, d), device=dev, generator=gen)  # the attention output, fp32 as in --path attention
+    o_raster = torch.empty((B, Hh, Nv, d), dtype=torch.float32, device=dev)
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        for x, y in zip(raster, cubes):
+            usv.cube_gather(x, grid, cube, seq_len=N, out=y)
+        if events is not None:
+            events[1].record()
+        usv.cube_scatter(o_cube, grid, cube, out=o_raster)
+        if events is not None:
+            events[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    st_ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(2)] for e in evs]).mean(axis=0)
+    rows = B * Hh
+    gather_bytes = rows * (Nv + N) * d * 2           # one gather launch: read Nv rows, write N rows (bf16)
+    scatter_bytes = rows * 2 * Nv * d * 4            # the scatter launch: read and write Nv rows (fp32)
+    total = 3 * gather_bytes + scatter_bytes
+    gather_ms = float(st_ms[0]) / 3
+    result = {
+        "metric": "GB/s of raster <-> cube-major reorder (gather Q, K, V + scatter O), algorithmic bytes",
+        "value": total / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": w.name, "path": "reorder", "grid": list(grid), "cube": list(cube), "batch": B, "heads": Hh,
+                   "head_dim": d, "seq_valid": Nv, "seq_len": N, "bytes_per_step": total,
+                   "step": "3 x usv_cube_gather (bf16) + usv_cube_scatter (fp32)"},
+        "stages_ms": {"cube_gather_x3": float(st_ms[0]), "cube_scatter": float(st_ms[1])},
+        "roofline": {"kernel": "usv_cube_gather (cube_move<true, 16>)", "bound": "hbm",
+                     "achieved": gather_bytes / (gather_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gather_bytes / (gather_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "avg_launch_ms": gather_ms},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import usv_oracle as orc
+
+        xs = [x[0, :2].view(torch.int16).cpu().numpy() for x in raster]
+        oc = o_cube[0, :2].cpu().numpy()
+        t0 = time.perf_counter()
+        for x in xs:
+            orc.cube_gather(x, grid, cube, N)
+        orc.cube_scatter(oc, grid, cube)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": total * 2 / rows / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"2 of {rows} heads, 3 gathers + 1 scatter, numpy indexing (incl. building the order), {dt:.2f} s"}
+    print(json.dumps(result))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.path == "reorder":
+        return reorder_main(args)
 
     peak_probe = None if args.no_mfma_peak else mfma_only_peak()
 

@@ -4,8 +4,12 @@
 // Pure data movement, HBM bound: every token row (d channels) is read once and written once.
 // One workgroup moves 64 consecutive RASTER tokens of one (batch, head): the first 64 lanes turn
 // their raster index into its cube-major position (closed form, a handful of integer divisions),
-// then all 256 lanes copy the rows 16 bytes at a time.  Consecutive raster tokens run along w, so
+// then all lanes copy the rows 16 bytes at a time.  Consecutive raster tokens run along w, so
 // the raster side is contiguous and the cube side comes in runs of cw rows (>= 256 bytes each).
+// Measured on MI355X (working set cycled beyond the Infinity Cache): at most four 16-byte pieces
+// per lane (8 per lane: 3.7 instead of 5.5 TB/s), source read with non-temporal loads (it is dead
+// afterwards; +3 %); the destination is stored normally because the next kernel reads it (streaming
+// stores make this kernel 8 % faster but its consumer slower by as much).
 #include "usv_internal.h"
 
 namespace usv {
@@ -36,15 +40,15 @@ __host__ __device__ long long cube_position(const CubeGrid& g, int t, int h, int
 
 namespace {
 
-constexpr int kThreads = 256;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned chunk_t;  // 16 bytes
 
 // GATHER: raster -> cube (and zero the padding rows); otherwise cube -> raster.
 // CHUNKS = 16-byte pieces per token row.
 template <bool GATHER, int CHUNKS>
-__global__ __launch_bounds__(kThreads) void cube_move(const unsigned char* __restrict__ src,
+__global__ __launch_bounds__(CHUNKS >= 32 ? 512 : 256) void cube_move(const unsigned char* __restrict__ src,
                                                       unsigned char* __restrict__ dst, CubeGrid g, int N, int Nv,
                                                       int Hh, long long sb, long long sh, long long st) {
+  constexpr int kThreads = CHUNKS >= 32 ? 512 : 256;  // <= 4 pieces per lane
   __shared__ int pos[kBlock];
   const int tid = threadIdx.x;
   const int r0 = blockIdx.x * kBlock;
@@ -76,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void cube_move(const unsigned char* __res
     if (r < Nv) {
       const unsigned char* p = GATHER ? raster_c + raster_base + (long long)r * st + ch * 16
                                       : src + cube_base + (long long)pos[row] * kRowBytes + ch * 16;
-      val[it] = *reinterpret_cast<const chunk_t*>(p);
+      val[it] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(p));
     }
   }
 #pragma unroll
@@ -94,7 +98,7 @@ template <bool GATHER, int CHUNKS>
 hipError_t run(const void* src, void* dst, const CubeGrid& g, const Dims& s, long long sb, long long sh, long long st,
                hipStream_t stream) {
   const dim3 grid((unsigned)(s.N / kBlock), (unsigned)s.bh());
-  cube_move<GATHER, CHUNKS><<<grid, kThreads, 0, stream>>>(static_cast<const unsigned char*>(src),
+  cube_move<GATHER, CHUNKS><<<grid, CHUNKS >= 32 ? 512 : 256, 0, stream>>>(static_cast<const unsigned char*>(src),
                                                            static_cast<unsigned char*>(dst), g, s.N, s.Nv, s.Hh, sb, sh, st);
   return hipGetLastError();
 }

@@ -98,3 +98,25 @@ def test_pipeline_from_raster_tokens(usv):
     np.testing.assert_array_equal(cnt.cpu().numpy(), rcnt)
     ref = orc.cube_scatter(orc.block_sparse_attn(Qo, Ko, Vo, ridx, rcnt, w.seq_valid)[0], grid, cube)
     gu.assert_attn_close(o_raster, ref, "bf16", False, "raster pipeline")
+
+
+@pytest.mark.parametrize("grid,Hh,dtype", [((21, 30, 52), 12, "bf16"), ((21, 30, 52), 12, "f32"), ((21, 45, 80), 40, "bf16")],
+                         ids=["480p_bf16", "480p_f32_output", "720p_bf16"])
+def test_full_size_grids_bit_exact(usv, grid, Hh, dtype):
+    """The benchmark grids with all heads, in the launch configuration bench.py times (contiguous
+    [1, Hh, Nv, 128]); the oracle redoes a sample of heads in full, the rest is covered by the round trip."""
+    cube, d = (4, 4, 4), 128
+    Nv = grid[0] * grid[1] * grid[2]
+    N = -(-Nv // 64) * 64
+    rng = np.random.default_rng([3, *grid])
+    X = bits(rng, (1, Hh, Nv, d), dtype)
+    x = to_dev(X)
+    y = usv.cube_gather(x, grid, cube, seq_len=N)
+    back = usv.cube_scatter(y, grid, cube)
+    assert torch.equal(back.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       x.view(torch.int16 if dtype == "bf16" else torch.int32))
+    order = orc.cube_token_order(grid, cube)
+    for h in sorted(set(rng.choice(Hh, size=3, replace=False).tolist()) | {0, Hh - 1}):
+        got = to_bits(y[0, h])
+        np.testing.assert_array_equal(got[:Nv], X[0, h][order])
+        assert not got[Nv:].any()
