@@ -91,12 +91,12 @@ def cpu_baseline(w, Q, K, V, n_heads):
     }
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per attention launch from the rocprofv3 --pmc runs summarised under profiles/ (null if none)."""
+def measured_traffic(workload_name, key="attn_hbm_bytes_per_launch"):
+    """HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc runs summarised under profiles/ (null if none)."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload_name, {}).get("attn_hbm_bytes_per_launch")
+            return json.load(f).get(workload_name, {}).get(key)
     except (OSError, ValueError):
         return None
 
@@ -181,7 +181,8 @@ def reorder_main(args):
         "stages_ms": {"cube_gather_x3": float(st_ms[0]), "cube_scatter": float(st_ms[1])},
         "roofline": {"kernel": "usv_cube_gather (cube_move<true, 16>)", "bound": "hbm",
                      "achieved": gather_bytes / (gather_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": gather_bytes / (gather_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                     "frac": gather_bytes / (gather_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": measured_traffic("reorder:" + w.name, "gather_hbm_bytes_per_launch"),
                      "avg_launch_ms": gather_ms},
     }
     if not args.no_cpu_baseline:
