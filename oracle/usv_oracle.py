@@ -28,6 +28,10 @@ description; Figure 2's "top-k cube selection"):
                     back to the full token grid" on the way out): the permutation
                     between raster (t, h, w) token order and cube-major order.
 
+  coarse_attn / fuse_outputs
+                    the cube-level branch and the fusion of Figure 2 (right), for which the
+                    paper prints no formula: the readings below.
+
 Every function is pinned by tests/test_oracle_pins.py against something other
 than itself (closed forms, torch's scaled_dot_product_attention in fp64,
 pure-Python brute force, invariants).  No function here is "parity unpinned".
@@ -47,6 +51,12 @@ Readings taken where the paper is silent (also listed in the design notes):
     follow in the same raster order, packed without gaps (so only the tail of
     the sequence is padding, which is what seq_valid expresses); inside a cube,
     tokens are in raster order of their local coordinates.
+  * coarse branch (the cube level of the coarse-to-fine scheme, Section 2.2): attention
+    among the pooled cubes, C_i = sum_j softmax_j(S_ij) mean(V_j) over the cubes that hold
+    a valid token, with S the stage-1 scores (they already carry the 1/sqrt(d)).
+  * fusion ("broadcast back to the full token grid, and fused"): every token r of cube i
+    receives C_i; out_r = g_fine[r] * O_fine[r] + g_coarse[r] * C_cube(r), elementwise, with
+    per-token, per-channel gates supplied by the model (absent gate = 1).
   * padded keys (token >= seq_valid) are masked; padded query rows output 0 and
     lse = -inf; a query cube with an empty list outputs 0.
 """
@@ -111,11 +121,13 @@ def select_topk_row(scores_row, k, nb_valid):
     return np.sort(keep).astype(np.int32)
 
 
-def select_topk(S, k, seq_valid, budgets=None, kmax=None, block=BLOCK):
+def select_topk(S, k, seq_valid, budgets=None, kmax=None, block=BLOCK, force_local=False):
     """S: fp32 [B, Hh, nb, nb].  Returns idx int32 [B,Hh,nb,kmax] (-1 padded) and cnt int32 [B,Hh,nb].
 
     A row keeps min(budget, kmax, nb_valid) blocks where budget = budgets[b,h,i] if given else k.
-    Query blocks with no valid token keep nothing."""
+    Query blocks with no valid token keep nothing.
+    force_local (Figure 2, right: part of the budget goes to "local cube attention"): a row that
+    keeps anything keeps its own cube i, and fills the rest of its budget with the best OTHER cubes."""
     B, Hh, nb, _ = S.shape
     nb_valid = (seq_valid + block - 1) // block
     if kmax is None:
@@ -127,7 +139,12 @@ def select_topk(S, k, seq_valid, budgets=None, kmax=None, block=BLOCK):
             for i in range(nb_valid):
                 want = int(budgets[b, h, i]) if budgets is not None else int(k)
                 want = max(0, min(want, kmax))
-                sel = select_topk_row(S[b, h, i], want, nb_valid)
+                if force_local and want >= 1:
+                    others = np.array([j for j in range(nb_valid) if j != i], dtype=np.int64)
+                    best = select_topk_row(S[b, h, i][others], want - 1, len(others))
+                    sel = np.sort(np.concatenate([others[best], [i]])).astype(np.int32)
+                else:
+                    sel = select_topk_row(S[b, h, i], want, nb_valid)
                 idx[b, h, i, : len(sel)] = sel
                 cnt[b, h, i] = len(sel)
     return idx, cnt
@@ -253,4 +270,40 @@ def cube_scatter(Y, grid, cube):
     order = cube_token_order(grid, cube)
     out = np.empty(Y.shape[:-2] + (len(order), Y.shape[-1]), dtype=Y.dtype)
     out[..., order, :] = Y[..., : len(order), :]
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# cube-level branch and output fusion (Figure 2, right; Section 2.2's coarse level)
+# --------------------------------------------------------------------------- #
+def coarse_attn(S, V, seq_valid, block=BLOCK):
+    """C[b,h,i,:] = sum_j softmax_j(S[b,h,i,:])_j * mean(V_j) over the cubes holding a valid token.
+
+    S: fp32 scores [B,Hh,nb,nb] (already scaled); V: [B,Hh,N,d].  Returns fp64 [B,Hh,nb,d];
+    rows of cubes without a valid token are 0."""
+    S = _f64(S)
+    nb = S.shape[-1]
+    nbv = (seq_valid + block - 1) // block
+    Vm = block_means(V, seq_valid, block)[..., :nbv, :]
+    L = S[..., :nbv, :nbv]
+    P = np.exp(L - L.max(axis=-1, keepdims=True))
+    P = P / P.sum(axis=-1, keepdims=True)
+    C = np.zeros(S.shape[:-1] + (Vm.shape[-1],))
+    C[..., :nbv, :] = P @ Vm
+    assert C.shape[-2] == nb
+    return C
+
+
+def fuse_outputs(fine, coarse, seq_valid, gate_fine=None, gate_coarse=None, block=BLOCK):
+    """out[r] = gate_fine[r] * fine[r] + gate_coarse[r] * coarse[cube(r)] for r < seq_valid, else 0.
+
+    fine, gates: [B,Hh,N,d]; coarse: [B,Hh,nb,d].  A missing gate is 1."""
+    fine, coarse = _f64(fine), _f64(coarse)
+    N = fine.shape[-2]
+    spread = np.repeat(coarse, block, axis=-2)  # every token of cube i receives row i
+    gf = 1.0 if gate_fine is None else _f64(gate_fine)
+    gc = 1.0 if gate_coarse is None else _f64(gate_coarse)
+    out = gf * fine + gc * spread
+    out[..., seq_valid:, :] = 0.0
+    assert out.shape[-2] == N
     return out

@@ -393,3 +393,83 @@ def test_cube_gather_scatter_roundtrip_and_padding():
     np.testing.assert_array_equal(Y2, expect)
     # a non-symmetric permutation: scatter must be the inverse, not the same map applied again
     assert not np.array_equal(orc.cube_gather(Y2, (8, 8, 8), cube, 512), X2)
+
+
+# --------------------------------------------------------------------------- #
+# local-cube allocation, cube-level branch, fusion (Figure 2, right)
+# --------------------------------------------------------------------------- #
+def test_force_local_brute_force():
+    """Own cube always kept, the rest of the budget = best others by (score desc, index asc);
+    pure-Python check incl. rows whose own cube would have been chosen anyway, k = 1 and ties."""
+    rng = np.random.default_rng(3)
+    nb, N = 9, 9 * 64 - 5
+    S = rng.standard_normal((1, 2, nb, nb)).astype(np.float32)
+    S[0, 0, 2, :] = 1.0          # all equal: own cube + lowest other indices
+    S[0, 1, 4, 4] = 100.0        # own cube already the best
+    for k in (1, 3, 9):
+        idx, cnt = orc.select_topk(S, k, N, force_local=True)
+        for h in range(2):
+            for i in range(nb):
+                others = sorted((j for j in range(nb) if j != i), key=lambda j: (-float(S[0, h, i, j]), j))
+                expect = sorted([i] + others[: k - 1])
+                assert cnt[0, h, i] == k and idx[0, h, i, :k].tolist() == expect
+    plain, _ = orc.select_topk(S, 3, N)
+    forced, _ = orc.select_topk(S, 3, N, force_local=True)
+    assert forced[0, 1, 4].tolist() == plain[0, 1, 4].tolist()          # diagonal was already in
+    assert forced[0, 0, 2].tolist() == [0, 1, 2]
+    # budgets of 0 keep nothing even when forced
+    bud = np.zeros((1, 2, nb), dtype=np.int32)
+    assert orc.select_topk(S, 0, N, budgets=bud, kmax=3, force_local=True)[1].sum() == 0
+
+
+def test_coarse_attn_is_sdpa_on_pooled_tensors():
+    """The cube-level branch is ordinary attention among the pooled cubes: torch SDPA (fp64) on
+    mean(Q), mean(K), mean(V).  Catches a softmax over the wrong axis, V means not taken over valid
+    tokens, a second 1/sqrt(d)."""
+    B, Hh, N, d, Nv = 1, 2, 5 * 64, 16, 5 * 64 - 23
+    Q, K, V = randn(B, Hh, N, d), randn(B, Hh, N, d), randn(B, Hh, N, d)
+    Q[..., Nv:, :] = 1e4
+    V[..., Nv:, :] = -1e4
+    S = orc.block_scores(Q, K, Nv)
+    C = orc.coarse_attn(S, V, Nv)
+    qm, km, vm = (torch.from_numpy(orc.block_means(x, Nv)) for x in (Q, K, V))
+    ref = torch.nn.functional.scaled_dot_product_attention(qm, km, vm).numpy()
+    np.testing.assert_allclose(C, ref, rtol=2e-6, atol=2e-6)  # S was rounded to fp32 once
+
+
+def test_coarse_attn_closed_forms():
+    """Equal scores -> plain average of the valid cubes' V means; one dominant score -> that cube's
+    mean; cubes without a valid token get 0 and are never averaged in."""
+    B, Hh, nb, d = 1, 1, 4, 8
+    N, Nv = nb * 64, 2 * 64 + 10  # cubes 0, 1 whole, cube 2 has 10 tokens, cube 3 none
+    V = randn(B, Hh, N, d)
+    vm = orc.block_means(V, Nv)[0, 0]
+    S = np.zeros((B, Hh, nb, nb), dtype=np.float32)
+    C = orc.coarse_attn(S, V, Nv)
+    np.testing.assert_allclose(C[0, 0, 0], vm[:3].mean(axis=0), rtol=1e-12)
+    assert np.all(C[0, 0, 3] == 0)
+    np.testing.assert_allclose(vm[2], V[0, 0, 128:138].mean(axis=0), rtol=1e-12)
+    S[0, 0, 1, 2] = 80.0
+    np.testing.assert_allclose(orc.coarse_attn(S, V, Nv)[0, 0, 1], vm[2], rtol=1e-12, atol=1e-30)
+
+
+def test_fuse_outputs_special_cases():
+    """Gates (1, 0) return the fine branch; (0, 1) the broadcast of the coarse rows (token r gets
+    row r // 64); missing gates are ones; padded rows are 0; linear in the gates."""
+    B, Hh, nb, d = 2, 2, 3, 8
+    N, Nv = nb * 64, nb * 64 - 7
+    fine, coarse = randn(B, Hh, N, d), randn(B, Hh, nb, d)
+    ones, zeros = np.ones((B, Hh, N, d)), np.zeros((B, Hh, N, d))
+    out = orc.fuse_outputs(fine, coarse, Nv, ones, zeros)
+    np.testing.assert_array_equal(out[..., :Nv, :], fine[..., :Nv, :])
+    assert np.all(out[..., Nv:, :] == 0)
+    out = orc.fuse_outputs(fine, coarse, Nv, zeros, ones)
+    for r in (0, 63, 64, 130, Nv - 1):
+        np.testing.assert_array_equal(out[1, 0, r], coarse[1, 0, r // 64])
+    np.testing.assert_array_equal(orc.fuse_outputs(fine, coarse, Nv), orc.fuse_outputs(fine, coarse, Nv, ones, ones))
+    gf, gc = randn(B, Hh, N, d), randn(B, Hh, N, d)
+    a = orc.fuse_outputs(fine, coarse, Nv, gf, gc)
+    b = orc.fuse_outputs(fine, coarse, Nv, gf, zeros) + orc.fuse_outputs(fine, coarse, Nv, zeros, gc)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-12)
+    r = 100
+    np.testing.assert_allclose(a[0, 1, r], gf[0, 1, r] * fine[0, 1, r] + gc[0, 1, r] * coarse[0, 1, 1], rtol=1e-12)
