@@ -103,6 +103,17 @@ usv_status usv_select_topk(const float* scores, const usv_shape* shape, int32_t 
                            const int32_t* budgets, int32_t kmax, int32_t* idx, int32_t* cnt,
                            void* stream);
 
+/* usv_select_topk with options.  flags = 0 is usv_select_topk itself.
+ * USV_TOPK_FORCE_LOCAL (Figure 2, right: the budget is split between "local cube
+ * attention" and "long-range sparse attention"): a row that keeps anything keeps
+ * its OWN cube i, and fills the rest of its budget with the best other cubes in
+ * the order above.  The paper gives no rule for the split; this reading spends
+ * one block of the budget on the local cube. */
+#define USV_TOPK_FORCE_LOCAL 1u
+usv_status usv_select_topk_ex(const float* scores, const usv_shape* shape, int32_t k,
+                              const int32_t* budgets, int32_t kmax, uint32_t flags, int32_t* idx,
+                              int32_t* cnt, void* stream);
+
 /*
  * Stage 3 - block-sparse attention: the masked-attention equation of Section 3.2,
  *   out = softmax(Q K^T * scale + log M) V,
@@ -135,6 +146,44 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v,
                                  const usv_shape* shape, const int32_t* idx, const int32_t* cnt,
                                  int32_t kmax, float scale, int32_t out_dtype, void* out, float* lse,
                                  void* stream);
+
+/*
+ * Cube-level branch and fusion (Figure 2, right: the branch outputs are "broadcast
+ * back to the full token grid, and fused to produce the final block output";
+ * Section 2.2: the coarse level of the coarse-to-fine scheme).  The paper prints
+ * no formula for either; the readings, following the coarse-to-fine sparse
+ * attention it builds on:
+ *   coarse[b,h,i,:] = sum_j softmax_j(scores[b,h,i,:])_j * mean(V cube j)
+ *                     over the cubes j that hold a valid token (scores as written
+ *                     by usv_block_scores: they already carry 1/sqrt(d));
+ *   out[b,h,r,:]    = gate_fine[b,h,r,:] * fine[b,h,r,:]
+ *                   + gate_coarse[b,h,r,:] * coarse[b,h,r/64,:]   (elementwise),
+ * i.e. every token of cube i receives row i of the cube-level output, and the
+ * model supplies per-token, per-channel gates (NULL gate = 1).
+ */
+
+/* Bytes of device scratch usv_coarse_attn needs (pooled fp32 means of V:
+ * B * Hh * nb * d * 4).  Returns 0 for an invalid shape. */
+size_t usv_coarse_workspace_bytes(const usv_shape* shape);
+
+/* scores : [B, Hh, nb, nb] fp32 (device, read only), from usv_block_scores
+ * v      : [B, Hh, N, d] of shape->dtype (device, read only)
+ * coarse : [B, Hh, nb, d] fp32 (device, written); rows of cubes without a valid
+ *          token are written as 0
+ * ws     : device scratch >= usv_coarse_workspace_bytes(shape); contents unspecified on return */
+usv_status usv_coarse_attn(const float* scores, const void* v, const usv_shape* shape, float* coarse,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* fine        : [B, Hh, N, d] of fine_dtype (the output of usv_block_sparse_attn)
+ * coarse      : [B, Hh, nb, d] fp32 (from usv_coarse_attn)
+ * gate_fine, gate_coarse : NULL or [B, Hh, N, d] of shape->dtype (device, read only)
+ * out         : [B, Hh, N, d] of out_dtype (written; bf16 results are rounded to
+ *               nearest even from the fp32 sum).  Rows of padded tokens are 0.
+ *               out may be the same buffer as fine when out_dtype == fine_dtype;
+ *               any other overlap is undefined. */
+usv_status usv_fuse_outputs(const void* fine, int32_t fine_dtype, const float* coarse,
+                            const void* gate_fine, const void* gate_coarse, const usv_shape* shape,
+                            int32_t out_dtype, void* out, void* stream);
 
 /*
  * Either side of the three stages: the token order (Figure 2, right: queries, keys

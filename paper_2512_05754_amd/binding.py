@@ -19,6 +19,10 @@ EXPORTED_SYMBOLS = (
     "usv_workspace_bytes",
     "usv_block_scores",
     "usv_select_topk",
+    "usv_select_topk_ex",
+    "usv_coarse_workspace_bytes",
+    "usv_coarse_attn",
+    "usv_fuse_outputs",
     "usv_block_sparse_attn",
     "usv_cube_token_order",
     "usv_cube_gather",
@@ -78,6 +82,11 @@ def lib() -> ctypes.CDLL:
     L.usv_workspace_bytes.restype, L.usv_workspace_bytes.argtypes = sz, [sp]
     L.usv_block_scores.restype, L.usv_block_scores.argtypes = i32, [vp, vp, sp, vp, vp, sz, vp]
     L.usv_select_topk.restype, L.usv_select_topk.argtypes = i32, [vp, sp, i32, vp, i32, vp, vp, vp]
+    L.usv_select_topk_ex.restype = i32
+    L.usv_select_topk_ex.argtypes = [vp, sp, i32, vp, i32, ctypes.c_uint32, vp, vp, vp]
+    L.usv_coarse_workspace_bytes.restype, L.usv_coarse_workspace_bytes.argtypes = sz, [sp]
+    L.usv_coarse_attn.restype, L.usv_coarse_attn.argtypes = i32, [vp, vp, sp, vp, vp, sz, vp]
+    L.usv_fuse_outputs.restype, L.usv_fuse_outputs.argtypes = i32, [vp, i32, vp, vp, vp, sp, i32, vp, vp]
     L.usv_block_sparse_attn.restype = i32
     L.usv_block_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, i32, f32, i32, vp, vp, vp]
     gp, stp = ctypes.POINTER(UsvGrid), ctypes.POINTER(UsvStrides)
@@ -149,8 +158,13 @@ def block_scores(q, k, seq_valid=None, out=None, workspace=None):
     return out
 
 
-def select_topk(scores, k=0, seq_valid=None, budgets=None, kmax=None, idx=None, cnt=None):
-    """usv_select_topk: scores [B, Hh, nb, nb] fp32 -> idx [B, Hh, nb, kmax] int32 (-1 padded), cnt [B, Hh, nb]."""
+TOPK_FORCE_LOCAL = 1
+
+
+def select_topk(scores, k=0, seq_valid=None, budgets=None, kmax=None, idx=None, cnt=None, force_local=False):
+    """usv_select_topk(_ex): scores [B, Hh, nb, nb] fp32 -> idx [B, Hh, nb, kmax] int32 (-1 padded), cnt [B, Hh, nb].
+
+    force_local: USV_TOPK_FORCE_LOCAL, every row keeps its own cube."""
     if scores.dim() != 4 or scores.shape[2] != scores.shape[3]:
         raise ValueError("scores must be [B, Hh, nb, nb]")
     B, Hh, nb, _ = scores.shape
@@ -163,12 +177,12 @@ def select_topk(scores, k=0, seq_valid=None, budgets=None, kmax=None, idx=None, 
     if cnt is None:
         cnt = torch.empty((B, Hh, nb), dtype=torch.int32, device=scores.device)
     bptr = None if budgets is None else _dev(budgets, "budgets", torch.int32)
-    _check(
-        lib().usv_select_topk(
-            _dev(scores, "scores", torch.float32), ctypes.byref(sh), int(k), bptr, int(kmax),
-            _dev(idx, "idx", torch.int32), _dev(cnt, "cnt", torch.int32), _stream(),
-        )
-    )
+    args = (_dev(scores, "scores", torch.float32), ctypes.byref(sh), int(k), bptr, int(kmax))
+    outs = (_dev(idx, "idx", torch.int32), _dev(cnt, "cnt", torch.int32), _stream())
+    if force_local:
+        _check(lib().usv_select_topk_ex(*args, TOPK_FORCE_LOCAL, *outs))
+    else:
+        _check(lib().usv_select_topk(*args, *outs))
     return idx, cnt
 
 
@@ -257,4 +271,51 @@ def cube_scatter(cube_major, grid, cube=(4, 4, 4), out=None):
     ptr, st = _raster(out, "raster")
     g = _grid(grid, cube)
     _check(lib().usv_cube_scatter(_dev(cube_major, "cube"), ctypes.byref(sh), ctypes.byref(g), ptr, ctypes.byref(st), _stream()))
+    return out
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return USV_F32
+    if t.dtype == torch.bfloat16:
+        return USV_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def coarse_attn(scores, v, seq_valid=None, out=None, workspace=None):
+    """usv_coarse_attn: cube-level attention output [B, Hh, nb, d] fp32 from the block scores and V."""
+    sh = _shape_of(v, seq_valid)
+    nb = sh.seq_len // BLOCK
+    if tuple(scores.shape) != (sh.batch, sh.heads, nb, nb):
+        raise ValueError("scores must be [B, Hh, nb, nb]")
+    if out is None:
+        out = torch.empty((sh.batch, sh.heads, nb, sh.head_dim), dtype=torch.float32, device=v.device)
+    need = int(lib().usv_coarse_workspace_bytes(ctypes.byref(sh)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=v.device)
+    _check(lib().usv_coarse_attn(_dev(scores, "scores", torch.float32), _dev(v, "v"), ctypes.byref(sh),
+                                 _dev(out, "coarse", torch.float32), _dev(workspace, "workspace"),
+                                 workspace.numel() * workspace.element_size(), _stream()))
+    return out
+
+
+def fuse_outputs(fine, coarse, gate_fine=None, gate_coarse=None, seq_valid=None, out=None, out_dtype=None):
+    """usv_fuse_outputs: out = gate_fine * fine + gate_coarse * broadcast(coarse); gates None = 1."""
+    B, Hh, N, d = fine.shape
+    gates = [g for g in (gate_fine, gate_coarse) if g is not None]
+    gdt = gates[0].dtype if gates else fine.dtype
+    for g in gates:
+        if g.shape != fine.shape or g.dtype != gdt:
+            raise ValueError("gates must have fine's shape and one dtype")
+    sh = UsvShape(B, Hh, N, N if seq_valid is None else int(seq_valid), d, BLOCK, USV_F32 if gdt == torch.float32 else USV_BF16)
+    if tuple(coarse.shape) != (B, Hh, N // BLOCK, d):
+        raise ValueError("coarse must be [B, Hh, nb, d]")
+    if out is None:
+        out = torch.empty_like(fine, dtype=out_dtype or fine.dtype)
+    if out.shape != fine.shape:
+        raise ValueError("out must have fine's shape")
+    _check(lib().usv_fuse_outputs(_dev(fine, "fine"), _dt(fine), _dev(coarse, "coarse", torch.float32),
+                                  None if gate_fine is None else _dev(gate_fine, "gate_fine"),
+                                  None if gate_coarse is None else _dev(gate_coarse, "gate_coarse"),
+                                  ctypes.byref(sh), _dt(out), _dev(out, "out"), _stream()))
     return out

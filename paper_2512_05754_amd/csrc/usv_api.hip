@@ -133,7 +133,13 @@ usv_status usv_block_scores(const void* q, const void* k, const usv_shape* shape
 
 usv_status usv_select_topk(const float* scores, const usv_shape* shape, int32_t k, const int32_t* budgets,
                            int32_t kmax, int32_t* idx, int32_t* cnt, void* stream) {
+  return usv_select_topk_ex(scores, shape, k, budgets, kmax, 0u, idx, cnt, stream);
+}
+
+usv_status usv_select_topk_ex(const float* scores, const usv_shape* shape, int32_t k, const int32_t* budgets,
+                              int32_t kmax, uint32_t flags, int32_t* idx, int32_t* cnt, void* stream) {
   usv::Dims s;
+  if (flags & ~(uint32_t)USV_TOPK_FORCE_LOCAL) return fail(USV_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
   USV_TRY(check_shape(shape, false, &s));
   USV_TRY(check_ptr(scores, "scores"));
   USV_TRY(check_ptr(idx, "idx"));
@@ -144,7 +150,8 @@ usv_status usv_select_topk(const float* scores, const usv_shape* shape, int32_t 
   } else if (k < 1 || k > kmax) {
     return fail(USV_ERR_INVALID_ARG, "k (%d) must be in [1, kmax = %d]", k, kmax);
   }
-  return hip_result(usv::launch_select_topk(scores, s, k, budgets, kmax, idx, cnt, static_cast<hipStream_t>(stream)),
+  return hip_result(usv::launch_select_topk(scores, s, k, budgets, kmax, (flags & USV_TOPK_FORCE_LOCAL) != 0, idx, cnt,
+                                            static_cast<hipStream_t>(stream)),
                     "usv_select_topk launch");
 }
 
@@ -172,6 +179,47 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v, co
                                     static_cast<const float*>(v), s, idx, cnt, kmax, scale, static_cast<float*>(out),
                                     lse, st);
   return hip_result(e, "usv_block_sparse_attn launch");
+}
+
+size_t usv_coarse_workspace_bytes(const usv_shape* shape) {
+  usv::Dims s;
+  if (check_shape(shape, true, &s) != USV_OK) return 0;
+  return (size_t)s.bh() * s.nb * s.d * sizeof(float);
+}
+
+usv_status usv_coarse_attn(const float* scores, const void* v, const usv_shape* shape, float* coarse, void* ws,
+                           size_t ws_bytes, void* stream) {
+  usv::Dims s;
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_ptr(scores, "scores"));
+  USV_TRY(check_ptr(v, "v"));
+  USV_TRY(check_ptr(coarse, "coarse"));
+  const size_t need = usv_coarse_workspace_bytes(shape);
+  if (!ws || !aligned16(ws) || ws_bytes < need)
+    return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = usv::launch_pool_means(v, s, static_cast<float*>(ws), st);
+  if (e == hipSuccess) e = usv::launch_coarse_attn(scores, static_cast<const float*>(ws), s, coarse, st);
+  return hip_result(e, "usv_coarse_attn launch");
+}
+
+usv_status usv_fuse_outputs(const void* fine, int32_t fine_dtype, const float* coarse, const void* gate_fine,
+                            const void* gate_coarse, const usv_shape* shape, int32_t out_dtype, void* out,
+                            void* stream) {
+  usv::Dims s;
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_ptr(fine, "fine"));
+  USV_TRY(check_ptr(coarse, "coarse"));
+  USV_TRY(check_ptr(out, "out"));
+  if (gate_fine && !aligned16(gate_fine)) return fail(USV_ERR_INVALID_ARG, "gate_fine is not 16-byte aligned");
+  if (gate_coarse && !aligned16(gate_coarse)) return fail(USV_ERR_INVALID_ARG, "gate_coarse is not 16-byte aligned");
+  if ((fine_dtype != USV_F32 && fine_dtype != USV_BF16) || (out_dtype != USV_F32 && out_dtype != USV_BF16))
+    return fail(USV_ERR_UNSUPPORTED, "fine_dtype and out_dtype must be USV_F32 or USV_BF16");
+  if (out == fine && out_dtype != fine_dtype)
+    return fail(USV_ERR_INVALID_ARG, "in-place fusion (out == fine) needs out_dtype == fine_dtype");
+  return hip_result(usv::launch_fuse_outputs(fine, fine_dtype == USV_F32, coarse, gate_fine, gate_coarse, !s.bf16, out,
+                                             out_dtype == USV_F32, s, static_cast<hipStream_t>(stream)),
+                    "usv_fuse_outputs launch");
 }
 
 usv_status usv_cube_token_order(const usv_grid* grid, int32_t* order) {

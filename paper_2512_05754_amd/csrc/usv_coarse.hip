@@ -1,0 +1,203 @@
+// Cube-level branch and output fusion (paper Figure 2, right: the outputs are "broadcast back to the
+// full token grid, and fused"; Section 2.2: the coarse level of the coarse-to-fine scheme).
+//
+//   coarse_attn   C[bh, i, :] = sum_j softmax_j(S[bh, i, :])_j * Vm[bh, j, :] over the cubes that hold a
+//                 valid token; S are the stage-1 scores, Vm the pooled fp32 means of V.  Two passes over
+//                 the 64 score rows of a workgroup: row max / sum, then P Vm on the fp32 matrix cores
+//                 (v_mfma_f32_32x32x2_f32, same operand mapping as the score product).
+//   fuse_outputs  out[r] = g_fine[r] * fine[r] + g_coarse[r] * C[cube(r)], elementwise: HBM bound.
+#include "usv_internal.h"
+
+namespace usv {
+namespace {
+
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+// grid = (ceil(nb / 64), B*Hh); 256 threads.  Output tile: 64 query cubes x D channels.
+template <int D>
+__global__ __launch_bounds__(256) void coarse_attn(const float* __restrict__ scores, const float* __restrict__ vmean,
+                                                   float* __restrict__ coarse, int nb, int nb_valid) {
+  constexpr int LD = 64 + 4;       // row stride in floats (16-byte reads of 32 consecutive rows spread over the banks)
+  constexpr int NACC = D / 64;     // 32x32 accumulators per wave
+  __shared__ __attribute__((aligned(16))) float Ps[64 * LD];  // P tile, [query cube][key cube]
+  __shared__ __attribute__((aligned(16))) float Vt[D * LD];   // Vm tile transposed, [channel][key cube]
+  __shared__ float row_max[64], row_inv[64];
+  const int bh = blockIdx.y, i0 = blockIdx.x * 64;
+  const float* S = scores + (long long)bh * nb * nb;
+  const float* vm = vmean + (long long)bh * nb * D;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  // pass 1: softmax statistics of this workgroup's 64 rows (16 rows per wave, a row per step)
+  for (int rr = 0; rr < 16; ++rr) {
+    const int row = wave * 16 + rr, i = i0 + row;
+    float m = -INFINITY, l = 0.f;
+    if (i < nb_valid) {  // wave-uniform
+      const float* srow = S + (long long)i * nb;
+      for (int j = lane; j < nb_valid; j += 64) m = fmaxf(m, srow[j]);
+      m = wave_max(m);
+      for (int j = lane; j < nb_valid; j += 64) l += expf(srow[j] - m);
+      l = wave_sum(l);
+    }
+    if (lane == 0) {
+      row_max[row] = m;
+      row_inv[row] = l > 0.f ? 1.0f / l : 0.f;
+    }
+  }
+  __syncthreads();
+
+  // pass 2: C = P Vm.  Wave (a, b): rows 32 a .. + 32, channels (D/2) b .. + D/2.
+  const int wi = (wave >> 1) * 32, wc = (wave & 1) * (D / 2);
+  const int r = lane & 31, g = lane >> 5;
+  f32x16 acc[NACC];
+#pragma unroll
+  for (int n = 0; n < NACC; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+  for (int j0 = 0; j0 < nb_valid; j0 += 64) {
+    if (j0) __syncthreads();
+    for (int e = tid; e < 64 * 64; e += 256) {
+      const int row = e >> 6, col = e & 63, i = i0 + row, j = j0 + col;
+      float p = 0.f;
+      if (i < nb_valid && j < nb_valid) p = expf(S[(long long)i * nb + j] - row_max[row]) * row_inv[row];
+      Ps[row * LD + col] = p;
+    }
+    for (int e = tid; e < 64 * (D / 4); e += 256) {
+      const int col = e / (D / 4), c = (e % (D / 4)) * 4, j = j0 + col;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j < nb_valid) v = *reinterpret_cast<const float4*>(vm + (long long)j * D + c);
+      Vt[(c + 0) * LD + col] = v.x;
+      Vt[(c + 1) * LD + col] = v.y;
+      Vt[(c + 2) * LD + col] = v.z;
+      Vt[(c + 3) * LD + col] = v.w;
+    }
+    __syncthreads();
+    // an MFMA step contracts 2 key cubes, one per 32-lane half: half g takes cube 32 g + t at step t
+    const float* ap = Ps + (wi + r) * LD + 32 * g;
+#pragma unroll
+    for (int t = 0; t < 32; t += 4) {
+      const float4 a = *reinterpret_cast<const float4*>(ap + t);
+#pragma unroll
+      for (int n = 0; n < NACC; ++n) {
+        const float4 b = *reinterpret_cast<const float4*>(Vt + (wc + 32 * n + r) * LD + 32 * g + t);
+        acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc[n], 0, 0, 0);
+        acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc[n], 0, 0, 0);
+        acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc[n], 0, 0, 0);
+        acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc[n], 0, 0, 0);
+      }
+    }
+  }
+  // accumulator register e of lane (r, g): row wi + 8 (e/4) + 4 g + (e%4), channel wc + 32 n + r
+  float* out = coarse + (long long)bh * nb * D;
+#pragma unroll
+  for (int n = 0; n < NACC; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int i = i0 + wi + 8 * (e >> 2) + 4 * g + (e & 3);
+      if (i < nb) out[(long long)i * D + wc + 32 * n + r] = i < nb_valid ? acc[n][e] : 0.f;
+    }
+}
+
+// ---- fusion --------------------------------------------------------------------------------------
+template <typename T>
+struct Elem;  // 4 consecutive channels of T <-> float4
+template <>
+struct Elem<float> {
+  __device__ static float4 load(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static void store(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+};
+template <>
+struct Elem<uint16_t> {  // bf16 bit patterns
+  __device__ static float4 load(const uint16_t* p) {
+    const uint2 w = *reinterpret_cast<const uint2*>(p);
+    return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                       __uint_as_float(w.y & 0xffff0000u));
+  }
+  __device__ static void store(uint16_t* p, float4 v) {
+    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+    bf16x4 o;
+    o[0] = (__bf16)v.x; o[1] = (__bf16)v.y; o[2] = (__bf16)v.z; o[3] = (__bf16)v.w;  // round to nearest even
+    *reinterpret_cast<bf16x4*>(p) = o;
+  }
+};
+
+// One thread per 4 channels of one token; consecutive threads -> consecutive addresses.
+template <typename FT, typename GT, typename OT>
+__global__ __launch_bounds__(256) void fuse_outputs(const FT* __restrict__ fine, const float* __restrict__ coarse,
+                                                    const GT* __restrict__ gate_fine, const GT* __restrict__ gate_coarse,
+                                                    OT* out, int N, int Nv, int d4, long long total4) {
+  const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (id >= total4) return;
+  const long long token = id / d4;  // (b*Hh + h) * N + r
+  const int c = (int)(id - token * d4) * 4;
+  const int r = (int)(token % N);
+  const long long off = id * 4;
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (r < Nv) {
+    const float4 f = Elem<FT>::load(fine + off);
+    const float4 cz = *reinterpret_cast<const float4*>(coarse + (token / kBlock) * (long long)(d4 * 4) + c);
+    float4 gf = make_float4(1.f, 1.f, 1.f, 1.f), gc = gf;
+    if (gate_fine) gf = Elem<GT>::load(gate_fine + off);
+    if (gate_coarse) gc = Elem<GT>::load(gate_coarse + off);
+    o.x = fmaf(gf.x, f.x, gc.x * cz.x);
+    o.y = fmaf(gf.y, f.y, gc.y * cz.y);
+    o.z = fmaf(gf.z, f.z, gc.z * cz.z);
+    o.w = fmaf(gf.w, f.w, gc.w * cz.w);
+  }
+  Elem<OT>::store(out + off, o);
+}
+
+template <typename FT, typename GT, typename OT>
+hipError_t run_fuse(const void* fine, const float* coarse, const void* gf, const void* gc, void* out, const Dims& s,
+                    hipStream_t st) {
+  const long long total4 = s.bh() * s.N * (s.d / 4);
+  fuse_outputs<FT, GT, OT><<<(unsigned)((total4 + 255) / 256), 256, 0, st>>>(
+      static_cast<const FT*>(fine), coarse, static_cast<const GT*>(gf), static_cast<const GT*>(gc), static_cast<OT*>(out),
+      s.N, s.Nv, s.d / 4, total4);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_coarse_attn(const float* scores, const float* vmean, const Dims& s, float* coarse, hipStream_t st) {
+  const dim3 grid((unsigned)((s.nb + 63) / 64), (unsigned)s.bh());
+  if (s.d == 128)
+    coarse_attn<128><<<grid, 256, 0, st>>>(scores, vmean, coarse, s.nb, s.nb_valid);
+  else
+    coarse_attn<64><<<grid, 256, 0, st>>>(scores, vmean, coarse, s.nb, s.nb_valid);
+  return hipGetLastError();
+}
+
+// (b*Hh + h) * N + r must fit the token arithmetic above: N <= 2^18, bh <= 65535.
+hipError_t launch_fuse_outputs(const void* fine, bool fine_f32, const float* coarse, const void* gate_fine,
+                               const void* gate_coarse, bool gates_f32, void* out, bool out_f32, const Dims& s,
+                               hipStream_t st) {
+#define USV_FUSE(FT, GT, OT) return run_fuse<FT, GT, OT>(fine, coarse, gate_fine, gate_coarse, out, s, st)
+  if (fine_f32) {
+    if (gates_f32) {
+      if (out_f32) USV_FUSE(float, float, float);
+      USV_FUSE(float, float, uint16_t);
+    }
+    if (out_f32) USV_FUSE(float, uint16_t, float);
+    USV_FUSE(float, uint16_t, uint16_t);
+  }
+  if (gates_f32) {
+    if (out_f32) USV_FUSE(uint16_t, float, float);
+    USV_FUSE(uint16_t, float, uint16_t);
+  }
+  if (out_f32) USV_FUSE(uint16_t, uint16_t, float);
+  USV_FUSE(uint16_t, uint16_t, uint16_t);
+#undef USV_FUSE
+}
+
+}  // namespace usv

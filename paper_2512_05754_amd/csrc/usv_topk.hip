@@ -27,7 +27,8 @@ template <int EPL>  // elements per lane: row length <= 64 * EPL
 __global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __restrict__ scores,
                                                                const int32_t* __restrict__ budgets, int k_uniform,
                                                                int kmax, int nb, int nb_valid, long long rows,
-                                                               int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+                                                               int force_local, int32_t* __restrict__ idx,
+                                                               int32_t* __restrict__ cnt) {
   const int lane = threadIdx.x & 63;
   const long long row = (long long)blockIdx.x * kRowsPerWg + (threadIdx.x >> 6);
   if (row >= rows) return;  // whole wavefront leaves together; no barriers in this kernel
@@ -47,6 +48,9 @@ __global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __re
       // slots beyond the valid blocks get the lowest key; `want <= nb_valid` and the index
       // tie-break keep them out of the result
       key[e] = j < nb_valid ? order_key(src[j]) : 0u;
+      // local-cube allocation: the row's own cube gets a key above every score (order_key never
+      // returns 0xffffffff), so it is kept first and the rest of the budget goes to the best others
+      if (force_local && j == i) key[e] = 0xffffffffu;
     }
     // threshold = the want-th largest key among the valid slots
     uint32_t thr = 0u;
@@ -83,21 +87,22 @@ __global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __re
 }
 
 template <int EPL>
-hipError_t run(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax, int32_t* idx,
-               int32_t* cnt, hipStream_t st) {
+hipError_t run(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax, bool force_local,
+               int32_t* idx, int32_t* cnt, hipStream_t st) {
   const long long rows = s.bh() * s.nb;
   const unsigned grid = (unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg);
-  select_topk<EPL><<<grid, 64 * kRowsPerWg, 0, st>>>(scores, budgets, k, kmax, s.nb, s.nb_valid, rows, idx, cnt);
+  select_topk<EPL><<<grid, 64 * kRowsPerWg, 0, st>>>(scores, budgets, k, kmax, s.nb, s.nb_valid, rows, force_local ? 1 : 0,
+                                                     idx, cnt);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_select_topk(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax,
-                              int32_t* idx, int32_t* cnt, hipStream_t st) {
+                              bool force_local, int32_t* idx, int32_t* cnt, hipStream_t st) {
   const int epl = (s.nb + 63) / 64;
 #define USV_TOPK_CASE(E) \
-  if (epl <= E) return run<E>(scores, s, k, budgets, kmax, idx, cnt, st)
+  if (epl <= E) return run<E>(scores, s, k, budgets, kmax, force_local, idx, cnt, st)
   USV_TOPK_CASE(1);
   USV_TOPK_CASE(2);
   USV_TOPK_CASE(4);

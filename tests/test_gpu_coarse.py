@@ -1,0 +1,124 @@
+"""GPU parity of the local-cube allocation, the cube-level branch and the fusion against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as gu
+from oracle import usv_oracle as orc
+from paper_2512_05754_amd import synth
+from paper_2512_05754_amd.synth import Workload
+
+pytestmark = pytest.mark.gpu
+
+WORKLOADS = [
+    synth.TINY,
+    Workload("f32_d128_ragged", 1, 2, 5 * 64 - 17, 128, "f32", 2.0, 2, seed=31),
+    Workload("bf16_d128_ragged", 2, 3, 9 * 64 - 9, 128, "bf16", 2.0, 4, seed=32),
+    Workload("bf16_d64_70blocks", 1, 2, 70 * 64 - 40, 64, "bf16", 1.0, 5, seed=33),
+    Workload("bf16_d128_130blocks", 1, 1, 130 * 64 - 1, 128, "bf16", 2.0, 7, seed=34),
+]
+
+
+@pytest.mark.parametrize("w", WORKLOADS, ids=lambda w: w.name)
+def test_force_local_selection_bit_exact(usv, w):
+    Q, K, _ = synth.gen_qkv(w)
+    S = usv.block_scores(gu.up(Q), gu.up(K), seq_valid=w.seq_valid)
+    S_h = gu.down(S)
+    for k in sorted({1, w.keep, min(w.nb, 9)}):
+        idx, cnt = usv.select_topk(S, k=k, seq_valid=w.seq_valid, force_local=True)
+        ridx, rcnt = orc.select_topk(S_h, k, w.seq_valid, force_local=True)
+        np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
+        np.testing.assert_array_equal(cnt.cpu().numpy(), rcnt)
+    # ragged budgets incl. zeros, with ties in the scores
+    rng = np.random.default_rng(w.seed)
+    bud = rng.integers(0, 6, size=(w.batch, w.heads, w.nb)).astype(np.int32)
+    S_t = np.round(S_h).astype(np.float32)  # many exact ties
+    idx, cnt = usv.select_topk(gu.up(S_t), seq_valid=w.seq_valid, budgets=gu.up(bud), kmax=5, force_local=True)
+    ridx, rcnt = orc.select_topk(S_t, 0, w.seq_valid, budgets=bud, kmax=5, force_local=True)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), rcnt)
+
+
+@pytest.mark.parametrize("w", WORKLOADS, ids=lambda w: w.name)
+def test_coarse_attn(usv, w):
+    Q, K, V = synth.gen_qkv(w)
+    S = usv.block_scores(gu.up(Q), gu.up(K), seq_valid=w.seq_valid)
+    C = usv.coarse_attn(S, gu.up(V), seq_valid=w.seq_valid)
+    ref = orc.coarse_attn(gu.down(S), synth.as_f32(V), w.seq_valid)
+    gu.assert_f32_close(gu.down(C), ref, w.name)
+
+
+def test_coarse_attn_fully_padded_cubes_and_peaked_rows(usv):
+    """Two cubes beyond seq_valid (their rows must be 0 and they must not be averaged in) and
+    scores scaled up so that the row softmax is sharply peaked (tests the max subtraction)."""
+    w = Workload("pad", 1, 2, 3 * 64 + 5, 64, "f32", 2.0, 1, seed=35)
+    Q, K, V = synth.gen_qkv(w)
+    pad = np.full((1, 2, 128, 64), synth.PAD_SENTINEL, dtype=np.float32)
+    Q, K, V = (np.concatenate([x, pad], axis=2) for x in (Q, K, V))
+    S = gu.down(usv.block_scores(gu.up(Q * 8), gu.up(K * 8), seq_valid=w.seq_valid))
+    C = gu.down(usv.coarse_attn(gu.up(S), gu.up(V), seq_valid=w.seq_valid))
+    assert not C[:, :, 4:].any()
+    gu.assert_f32_close(C, orc.coarse_attn(S, V, w.seq_valid))
+
+
+def storage(rng, shape, dtype):
+    x = rng.standard_normal(shape).astype(np.float32)
+    return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+
+
+@pytest.mark.parametrize("fine_dt,gate_dt,out_dt", [("f32", "bf16", "f32"), ("f32", "bf16", "bf16"), ("bf16", "bf16", "bf16"),
+                                                    ("f32", "f32", "f32"), ("bf16", "f32", "f32"), ("bf16", "bf16", "f32"),
+                                                    ("f32", "f32", "bf16"), ("bf16", "f32", "bf16")])
+@pytest.mark.parametrize("d", [64, 128])
+def test_fuse_outputs(usv, fine_dt, gate_dt, out_dt, d):
+    rng = np.random.default_rng([41, d])
+    B, Hh, nb = 2, 2, 5
+    N, Nv = nb * 64, nb * 64 - 21
+    fine, gf, gc = storage(rng, (B, Hh, N, d), fine_dt), storage(rng, (B, Hh, N, d), gate_dt), storage(rng, (B, Hh, N, d), gate_dt)
+    coarse = rng.standard_normal((B, Hh, nb, d)).astype(np.float32)
+    odt = torch.float32 if out_dt == "f32" else torch.bfloat16
+    ref = orc.fuse_outputs(synth.as_f32(fine), coarse, Nv, synth.as_f32(gf), synth.as_f32(gc))
+    got = gu.down(usv.fuse_outputs(gu.up(fine), gu.up(coarse), gu.up(gf), gu.up(gc), seq_valid=Nv, out_dtype=odt))
+    assert not got[:, :, Nv:].any()
+    if out_dt == "f32":
+        gu.assert_f32_close(got, ref)
+    else:  # one rounding of the fp32 result to bf16: half an ulp, at most 2^-8 of the value
+        ok = np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.maximum(1, np.abs(ref))
+        assert ok.all(), f"{(~ok).sum()} elements beyond half a bf16 ulp"
+    # missing gates are ones
+    got1 = gu.down(usv.fuse_outputs(gu.up(fine), gu.up(coarse), seq_valid=Nv, out_dtype=torch.float32))
+    gu.assert_f32_close(got1, orc.fuse_outputs(synth.as_f32(fine), coarse, Nv))
+
+
+def test_fuse_outputs_in_place(usv):
+    rng = np.random.default_rng(43)
+    fine = rng.standard_normal((1, 2, 128, 64)).astype(np.float32)
+    coarse = rng.standard_normal((1, 2, 2, 64)).astype(np.float32)
+    gc = synth.f32_to_bf16_bits(rng.standard_normal((1, 2, 128, 64)).astype(np.float32))
+    buf = gu.up(fine)
+    out = usv.fuse_outputs(buf, gu.up(coarse), None, gu.up(gc), seq_valid=100, out=buf)
+    assert out.data_ptr() == buf.data_ptr()
+    gu.assert_f32_close(gu.down(buf), orc.fuse_outputs(fine, coarse, 100, None, synth.as_f32(gc)))
+
+
+def test_two_branch_pipeline(usv):
+    """scores -> forced-local top-k -> sparse attention, cube-level branch, gated fusion: end to end against the oracle."""
+    w = Workload("two_branch", 1, 2, 12 * 64 - 30, 128, "bf16", 2.0, 3, seed=44)
+    Q, K, V = synth.gen_qkv(w)
+    rng = np.random.default_rng(45)
+    gf = synth.f32_to_bf16_bits(rng.uniform(0, 1, size=Q.shape).astype(np.float32))
+    gc = synth.f32_to_bf16_bits(rng.uniform(0, 1, size=Q.shape).astype(np.float32))
+    q, k, v = gu.up(Q), gu.up(K), gu.up(V)
+    S = usv.block_scores(q, k, seq_valid=w.seq_valid)
+    idx, cnt = usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, force_local=True)
+    fine = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32)
+    C = usv.coarse_attn(S, v, seq_valid=w.seq_valid)
+    out = gu.down(usv.fuse_outputs(fine, C, gu.up(gf), gu.up(gc), seq_valid=w.seq_valid))
+    S_h = gu.down(S)
+    ridx, rcnt = orc.select_topk(S_h, w.keep, w.seq_valid, force_local=True)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
+    assert all(i in ridx[0, h, i, :rcnt[0, h, i]] for h in range(2) for i in range(w.nb))
+    Qf, Kf, Vf = synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V)
+    ref = orc.fuse_outputs(orc.block_sparse_attn(Qf, Kf, Vf, ridx, rcnt, w.seq_valid)[0],
+                           orc.coarse_attn(S_h, Vf, w.seq_valid), w.seq_valid, synth.as_f32(gf), synth.as_f32(gc))
+    gu.assert_attn_close(out, ref, "bf16", False, "two-branch pipeline")

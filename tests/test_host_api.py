@@ -146,3 +146,26 @@ def test_cube_move_rejects_null_and_misaligned_pointers():
     assert L.usv_cube_gather(FAKE, None, ctypes.byref(sh), ctypes.byref(g), FAKE + 4, None) == 1
     assert L.usv_cube_scatter(FAKE, ctypes.byref(sh), None, FAKE, None, None) == 1
     assert L.usv_cube_token_order(ctypes.byref(g), None) == 1
+
+
+# --------------------------------------------------------------------------- #
+# cube-level branch, fusion, selection flags
+# --------------------------------------------------------------------------- #
+def test_coarse_and_fuse_reject_bad_arguments_before_launch():
+    L = binding.lib()
+    sh = shape()
+    need = L.usv_coarse_workspace_bytes(ctypes.byref(sh))
+    assert need == 2 * 16 * 64 * 4
+    assert L.usv_coarse_workspace_bytes(ctypes.byref(shape(head_dim=80))) == 0
+    name = lambda rc: L.usv_status_string(rc).decode()
+    assert name(L.usv_coarse_attn(FAKE, FAKE, ctypes.byref(sh), FAKE, FAKE, need - 1, None)) == "USV_ERR_WORKSPACE"
+    assert name(L.usv_coarse_attn(FAKE, FAKE, ctypes.byref(sh), FAKE, None, need, None)) == "USV_ERR_WORKSPACE"
+    assert name(L.usv_coarse_attn(None, FAKE, ctypes.byref(sh), FAKE, FAKE, need, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_coarse_attn(FAKE, FAKE, ctypes.byref(shape(block=32)), FAKE, FAKE, need, None)) == "USV_ERR_UNSUPPORTED"
+    f32, bf16 = binding.USV_F32, binding.USV_BF16
+    assert name(L.usv_fuse_outputs(FAKE, 5, FAKE, None, None, ctypes.byref(sh), f32, FAKE + 64, None)) == "USV_ERR_UNSUPPORTED"
+    assert name(L.usv_fuse_outputs(FAKE, f32, FAKE, None, None, ctypes.byref(sh), bf16, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_fuse_outputs(FAKE, f32, FAKE, FAKE + 2, None, ctypes.byref(sh), f32, FAKE + 64, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_fuse_outputs(FAKE, f32, None, None, None, ctypes.byref(sh), f32, FAKE + 64, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_select_topk_ex(FAKE, ctypes.byref(sh), 2, None, 4, 6, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert b"flag" in L.usv_last_error()
