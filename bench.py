@@ -41,9 +41,11 @@ def parse():
                     help="also run one plain 256 MiB device copy (untimed) so that a rocprofv3 --pmc run of this "
                          "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
-    ap.add_argument("--path", default="attention", choices=["attention", "reorder"],
+    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch"],
                     help="attention: the three-stage hot path (the headline metric); reorder: the raster <-> "
-                         "cube-major token reorder either side of it (gather Q, K, V + scatter O)")
+                         "cube-major token reorder either side of it (gather Q, K, V + scatter O); two_branch: the "
+                         "hot path with the local cube forced into every list, plus the cube-level branch and the "
+                         "gated fusion of the two outputs")
     ap.add_argument("--no-mfma-peak", action="store_true",
                     help="skip the MFMA-only peak probe (paper_2512_05754_amd/tools/mfma_peak, ~1 s)")
     return ap.parse_args()
@@ -59,7 +61,7 @@ def pick_workload(name):
     return synth.sweep(int(name[len("sweep"):]) / 100.0)
 
 
-def cpu_baseline(w, Q, K, V, n_heads):
+def cpu_baseline(w, Q, K, V, n_heads, two_branch=False):
     """Times the oracle (all three stages) on the first n_heads heads of batch 0."""
     import numpy as np
 
@@ -77,15 +79,17 @@ def cpu_baseline(w, Q, K, V, n_heads):
     budgets = synth.gen_budgets(w)[:1, :n_heads] if not w.keep else None
     t0 = time.perf_counter()
     S = orc.block_scores(Qf, Kf, w.seq_valid)
-    idx, cnt = orc.select_topk(S, w.keep, w.seq_valid, budgets=budgets, kmax=w.kmax)
-    orc.block_sparse_attn(Qf, Kf, Vf, idx, cnt, w.seq_valid)
+    idx, cnt = orc.select_topk(S, w.keep, w.seq_valid, budgets=budgets, kmax=w.kmax, force_local=two_branch)
+    fine = orc.block_sparse_attn(Qf, Kf, Vf, idx, cnt, w.seq_valid)[0]
+    if two_branch:
+        orc.fuse_outputs(fine, orc.coarse_attn(S, Vf, w.seq_valid), w.seq_valid, np.ones_like(fine), np.ones_like(fine))
     dt = time.perf_counter() - t0
     tiles = int(cnt.sum())
     flop = tiles * 4.0 * 64 * 64 * w.head_dim
     return {
         "value": flop / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
         "sample": f"{n_heads} of {w.batch * w.heads} heads (all {w.nb} query blocks each, {tiles} tiles), "
-                  f"3 stages, numpy fp64, {dt:.2f} s; host has {len(os.sched_getaffinity(0))} usable cores",
+                  f"{5 if two_branch else 3} stages, numpy fp64, {dt:.2f} s; host has {len(os.sched_getaffinity(0))} usable cores",
         "seconds": dt,
         "ms_per_call_extrapolated": dt * 1e3 * (w.batch * w.heads) / n_heads,
     }
@@ -232,6 +236,7 @@ def main():
 
     q, k, v = up(Q), up(K), up(V)
     budgets = None if w.keep else torch.from_numpy(synth.gen_budgets(w)).to(dev)
+    two_branch = args.path == "two_branch"
     out_dtype = torch.float32 if (args.out_dtype == "f32" or w.dtype == "f32") else torch.bfloat16
 
     # every buffer is allocated once, outside the timed region
@@ -241,6 +246,14 @@ def main():
     idx = torch.empty((B, Hh, nb, kmax), dtype=torch.int32, device=dev)
     cnt = torch.empty((B, Hh, nb), dtype=torch.int32, device=dev)
     out = torch.empty((B, Hh, N, d), dtype=out_dtype, device=dev)
+    if two_branch:
+        gen = torch.Generator(device=dev).manual_seed(w.seed)
+        gates = [torch.rand((B, Hh, N, d), device=dev, generator=gen).to(q.dtype) for _ in range(2)]
+        coarse = torch.empty((B, Hh, nb, d), dtype=torch.float32, device=dev)
+        ws_c = torch.empty(B * Hh * nb * d * 4, dtype=torch.uint8, device=dev)
+        fused = torch.empty((B, Hh, N, d), dtype=q.dtype, device=dev)
+        branch_events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    step_no = [0]
 
     def step(events=None):
         if events is not None:
@@ -248,12 +261,22 @@ def main():
         usv.block_scores(q, k, seq_valid=w.seq_valid, out=S, workspace=ws)
         if events is not None:
             events[1].record()
-        usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, budgets=budgets, kmax=kmax, idx=idx, cnt=cnt)
+        usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, budgets=budgets, kmax=kmax, idx=idx, cnt=cnt,
+                        force_local=two_branch)
         if events is not None:
             events[2].record()
         usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=out)
         if events is not None:
             events[3].record()
+        if two_branch:
+            be = branch_events[step_no[0]] if events is not None else None
+            usv.coarse_attn(S, v, seq_valid=w.seq_valid, out=coarse, workspace=ws_c)
+            if be is not None:
+                be[0].record()
+            usv.fuse_outputs(out, coarse, gates[0], gates[1], seq_valid=w.seq_valid, out=fused)
+            if be is not None:
+                be[1].record()
+                step_no[0] += 1
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -301,7 +324,8 @@ def main():
             "workload": w.name, "batch": B, "heads": Hh, "head_dim": d, "seq_len": N, "seq_valid": w.seq_valid,
             "block": 64, "blocks": nb, "keep": w.keep if w.keep else f"U[{w.budget_lo},{w.budget_hi}]",
             "computed_tiles": tiles, "flop_per_step": flop, "out_dtype": args.out_dtype if w.dtype == "bf16" else "f32",
-            "step": "usv_block_scores + usv_select_topk + usv_block_sparse_attn",
+            "step": "usv_block_scores + usv_select_topk + usv_block_sparse_attn"
+                    + (" + usv_coarse_attn + usv_fuse_outputs (local cube forced)" if two_branch else ""),
         },
         "stages_ms": {"block_scores": float(avg[0]), "select_topk": float(avg[1]), "block_sparse_attn": float(avg[2])},
         "attn_ms_min": float(st_ms[:, 2].min()),
@@ -319,11 +343,21 @@ def main():
             "avg_launch_ms": float(avg[2]),
         },
     }
+    if two_branch:
+        c_ms = float(np.mean([evs[i][3].elapsed_time(branch_events[i][0]) for i in range(args.steps)]))
+        f_ms = float(np.mean([branch_events[i][0].elapsed_time(branch_events[i][1]) for i in range(args.steps)]))
+        result["config"]["path"] = "two_branch"
+        result["stages_ms"]["coarse_attn"] = c_ms
+        result["stages_ms"]["fuse_outputs"] = f_ms
+        bytes_coarse = B * Hh * (N * d * esz + 2 * nb * nb * 4 + 3 * nb * d * 4)  # V once, S twice, means + output
+        bytes_fuse = B * Hh * N * d * (out.element_size() + 3 * esz) + B * Hh * nb * d * 4
+        result["stage_hbm_gbs"]["coarse_attn"] = bytes_coarse / (c_ms * 1e-3) / 1e9
+        result["stage_hbm_gbs"]["fuse_outputs"] = bytes_fuse / (f_ms * 1e-3) / 1e9
     if peak_probe is not None:
         # context for `frac`: what an MFMA-only loop sustains on this GPU (the clock drops with operand activity)
         result["roofline"]["measured_mfma_only_tflops"] = peak_probe
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, Q, K, V, args.cpu_sample_heads)
+        result["cpu_baseline"] = cpu_baseline(w, Q, K, V, args.cpu_sample_heads, two_branch)
     print(json.dumps(result))
 
 

@@ -3,8 +3,8 @@
 //
 //   coarse_attn   C[bh, i, :] = sum_j softmax_j(S[bh, i, :])_j * Vm[bh, j, :] over the cubes that hold a
 //                 valid token; S are the stage-1 scores, Vm the pooled fp32 means of V.  Two passes over
-//                 the 64 score rows of a workgroup: row max / sum, then P Vm on the fp32 matrix cores
-//                 (v_mfma_f32_32x32x2_f32, same operand mapping as the score product).
+//                 the 32 score rows of a workgroup: row maxima, then exp, row sums and P Vm on the fp32
+//                 matrix cores (v_mfma_f32_32x32x2_f32, same operand mapping as the score product).
 //   fuse_outputs  out[r] = g_fine[r] * fine[r] + g_coarse[r] * C[cube(r)], elementwise: HBM bound.
 #include "usv_internal.h"
 
@@ -13,83 +13,113 @@ namespace {
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-  return x;
-}
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-  return x;
-}
-
-// grid = (ceil(nb / 64), B*Hh); 256 threads.  Output tile: 64 query cubes x D channels.
+// grid = (ceil(nb / 32), B*Hh); 256 threads.  Output tile: 32 query cubes x D channels.
+// Pass A finds the row maxima; pass B walks the key cubes 64 at a time: it stages P = exp(S - max)
+// and the transposed Vm tile in LDS, accumulates the row sums (8 lanes per row), and runs P Vm on the
+// matrix cores with the four waves splitting the 64 key cubes of a tile (16 each); the waves'
+// partial tiles are then added in a fixed order.
 template <int D>
 __global__ __launch_bounds__(256) void coarse_attn(const float* __restrict__ scores, const float* __restrict__ vmean,
                                                    float* __restrict__ coarse, int nb, int nb_valid) {
+  constexpr int ROWS = 32;
   constexpr int LD = 64 + 4;       // row stride in floats (16-byte reads of 32 consecutive rows spread over the banks)
-  constexpr int NACC = D / 64;     // 32x32 accumulators per wave
-  __shared__ __attribute__((aligned(16))) float Ps[64 * LD];  // P tile, [query cube][key cube]
-  __shared__ __attribute__((aligned(16))) float Vt[D * LD];   // Vm tile transposed, [channel][key cube]
-  __shared__ float row_max[64], row_inv[64];
-  const int bh = blockIdx.y, i0 = blockIdx.x * 64;
+  constexpr int NACC = D / 32;     // 32x32 accumulators per wave: the whole 32 x D tile
+  constexpr int OLD = D + 4;       // row stride of the reduction buffer
+  __shared__ __attribute__((aligned(16))) float Ps[ROWS * LD];  // score / P tile, [query cube][key cube]
+  __shared__ __attribute__((aligned(16))) float Vt[D * LD];     // Vm tile transposed, [channel][key cube]; later the reduction buffer
+  __shared__ float row_max[ROWS], row_inv[ROWS];
+  static_assert(ROWS * OLD <= D * LD, "the reduction buffer overlays Vt");
+  const int bh = blockIdx.y, i0 = blockIdx.x * ROWS;
   const float* S = scores + (long long)bh * nb * nb;
   const float* vm = vmean + (long long)bh * nb * D;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int srow = tid >> 3, spart = tid & 7;  // row statistics: 8 lanes per row, 8 key cubes each per tile
 
-  // pass 1: softmax statistics of this workgroup's 64 rows (16 rows per wave, a row per step)
-  for (int rr = 0; rr < 16; ++rr) {
-    const int row = wave * 16 + rr, i = i0 + row;
-    float m = -INFINITY, l = 0.f;
-    if (i < nb_valid) {  // wave-uniform
-      const float* srow = S + (long long)i * nb;
-      for (int j = lane; j < nb_valid; j += 64) m = fmaxf(m, srow[j]);
-      m = wave_max(m);
-      for (int j = lane; j < nb_valid; j += 64) l += expf(srow[j] - m);
-      l = wave_sum(l);
+  // pass A: row maxima.  Wave w owns rows 8 w .. 8 w + 7; the loads of all 8 rows of a 512-cube chunk
+  // are issued together, so a chunk costs one memory latency.
+  {
+    float mx[8];
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) mx[rr] = -INFINITY;
+    for (int jc = 0; jc < nb_valid; jc += 512) {
+      float x[8][8];
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const int i = i0 + wave * 8 + rr, j = jc + 64 * t + lane;
+          x[rr][t] = (i < nb_valid && j < nb_valid) ? S[(long long)i * nb + j] : -INFINITY;
+        }
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) mx[rr] = fmaxf(mx[rr], x[rr][t]);
     }
-    if (lane == 0) {
-      row_max[row] = m;
-      row_inv[row] = l > 0.f ? 1.0f / l : 0.f;
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) {
+      float m = mx[rr];
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      if (lane == 0) row_max[wave * 8 + rr] = m == -INFINITY ? 0.f : m;  // rows of cubes without a valid token: P stays 0
     }
   }
   __syncthreads();
 
-  // pass 2: C = P Vm.  Wave (a, b): rows 32 a .. + 32, channels (D/2) b .. + D/2.
-  const int wi = (wave >> 1) * 32, wc = (wave & 1) * (D / 2);
+  // pass B: C = P Vm (unnormalised), row sums on the side.  The next tile's scores and Vm rows are
+  // fetched into registers while the current tile is in LDS.
   const int r = lane & 31, g = lane >> 5;
+  const int kofs = 16 * wave + 8 * g;  // an MFMA step contracts 2 key cubes, one per 32-lane half: wave w, half g takes cube 16 w + 8 g + t at step t
   f32x16 acc[NACC];
 #pragma unroll
   for (int n = 0; n < NACC; ++n)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
-  for (int j0 = 0; j0 < nb_valid; j0 += 64) {
-    if (j0) __syncthreads();
-    for (int e = tid; e < 64 * 64; e += 256) {
-      const int row = e >> 6, col = e & 63, i = i0 + row, j = j0 + col;
-      float p = 0.f;
-      if (i < nb_valid && j < nb_valid) p = expf(S[(long long)i * nb + j] - row_max[row]) * row_inv[row];
-      Ps[row * LD + col] = p;
+  float l = 0.f;
+  constexpr int SPT = ROWS * 64 / 256;       // scores per thread and tile
+  constexpr int VPT = 64 * (D / 4) / 256;    // float4 of Vm per thread and tile
+  float sreg[SPT];
+  float4 vreg[VPT];
+  auto fetch = [&](int j0) {
+#pragma unroll
+    for (int t = 0; t < SPT; ++t) {
+      const int e = tid + 256 * t, row = e >> 6, col = e & 63, i = i0 + row, j = j0 + col;
+      sreg[t] = (i < nb_valid && j < nb_valid) ? S[(long long)i * nb + j] : -INFINITY;
     }
-    for (int e = tid; e < 64 * (D / 4); e += 256) {
-      const int col = e / (D / 4), c = (e % (D / 4)) * 4, j = j0 + col;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (j < nb_valid) v = *reinterpret_cast<const float4*>(vm + (long long)j * D + c);
-      Vt[(c + 0) * LD + col] = v.x;
-      Vt[(c + 1) * LD + col] = v.y;
-      Vt[(c + 2) * LD + col] = v.z;
-      Vt[(c + 3) * LD + col] = v.w;
+#pragma unroll
+    for (int t = 0; t < VPT; ++t) {
+      const int e = tid + 256 * t, col = e / (D / 4), c = (e % (D / 4)) * 4, j = j0 + col;
+      vreg[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j < nb_valid) vreg[t] = *reinterpret_cast<const float4*>(vm + (long long)j * D + c);
+    }
+  };
+  fetch(0);
+  for (int j0 = 0; j0 < nb_valid; j0 += 64) {
+    if (j0) __syncthreads();  // the previous tile has been consumed
+#pragma unroll
+    for (int t = 0; t < SPT; ++t) {
+      const int e = tid + 256 * t, row = e >> 6, col = e & 63;
+      // exp2(-inf) = 0 covers the entries outside the valid cubes
+      Ps[row * LD + col] = __builtin_amdgcn_exp2f((sreg[t] - row_max[row]) * kLog2e);
+    }
+#pragma unroll
+    for (int t = 0; t < VPT; ++t) {
+      const int e = tid + 256 * t, col = e / (D / 4), c = (e % (D / 4)) * 4;
+      Vt[(c + 0) * LD + col] = vreg[t].x;
+      Vt[(c + 1) * LD + col] = vreg[t].y;
+      Vt[(c + 2) * LD + col] = vreg[t].z;
+      Vt[(c + 3) * LD + col] = vreg[t].w;
     }
     __syncthreads();
-    // an MFMA step contracts 2 key cubes, one per 32-lane half: half g takes cube 32 g + t at step t
-    const float* ap = Ps + (wi + r) * LD + 32 * g;
+    if (j0 + 64 < nb_valid) fetch(j0 + 64);
 #pragma unroll
-    for (int t = 0; t < 32; t += 4) {
+    for (int t = 0; t < 8; ++t) l += Ps[srow * LD + spart * 8 + t];
+    const float* ap = Ps + r * LD + kofs;
+#pragma unroll
+    for (int t = 0; t < 8; t += 4) {
       const float4 a = *reinterpret_cast<const float4*>(ap + t);
 #pragma unroll
       for (int n = 0; n < NACC; ++n) {
-        const float4 b = *reinterpret_cast<const float4*>(Vt + (wc + 32 * n + r) * LD + 32 * g + t);
+        const float4 b = *reinterpret_cast<const float4*>(Vt + (32 * n + r) * LD + kofs + t);
         acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc[n], 0, 0, 0);
         acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc[n], 0, 0, 0);
         acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc[n], 0, 0, 0);
@@ -97,15 +127,36 @@ __global__ __launch_bounds__(256) void coarse_attn(const float* __restrict__ sco
       }
     }
   }
-  // accumulator register e of lane (r, g): row wi + 8 (e/4) + 4 g + (e%4), channel wc + 32 n + r
-  float* out = coarse + (long long)bh * nb * D;
+  l += __shfl_xor(l, 1);
+  l += __shfl_xor(l, 2);
+  l += __shfl_xor(l, 4);
+  if (spart == 0) row_inv[srow] = l > 0.f ? 1.0f / l : 0.f;
+  __syncthreads();  // also: every wave is done reading Vt
+
+  // add the four waves' partial tiles in wave order (deterministic), then normalise and store.
+  // accumulator register e of lane (r, g): row 8 (e/4) + 4 g + (e%4), channel 32 n + r
+  float* red = Vt;
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
 #pragma unroll
-  for (int n = 0; n < NACC; ++n)
+      for (int n = 0; n < NACC; ++n)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int i = i0 + wi + 8 * (e >> 2) + 4 * g + (e & 3);
-      if (i < nb) out[(long long)i * D + wc + 32 * n + r] = i < nb_valid ? acc[n][e] : 0.f;
+        for (int e = 0; e < 16; ++e) {
+          float* p = red + (8 * (e >> 2) + 4 * g + (e & 3)) * OLD + 32 * n + r;
+          *p = (w == 0 ? 0.f : *p) + acc[n][e];
+        }
     }
+    __syncthreads();
+  }
+  float* out = coarse + (long long)bh * nb * D;
+  for (int e = tid; e < ROWS * (D / 4); e += 256) {
+    const int row = e / (D / 4), c = (e % (D / 4)) * 4, i = i0 + row;
+    if (i < nb) {
+      const float inv = i < nb_valid ? row_inv[row] : 0.f;
+      const float4 v = *reinterpret_cast<const float4*>(red + row * OLD + c);
+      *reinterpret_cast<float4*>(out + (long long)i * D + c) = make_float4(v.x * inv, v.y * inv, v.z * inv, v.w * inv);
+    }
+  }
 }
 
 // ---- fusion --------------------------------------------------------------------------------------
@@ -170,7 +221,7 @@ hipError_t run_fuse(const void* fine, const float* coarse, const void* gf, const
 }  // namespace
 
 hipError_t launch_coarse_attn(const float* scores, const float* vmean, const Dims& s, float* coarse, hipStream_t st) {
-  const dim3 grid((unsigned)((s.nb + 63) / 64), (unsigned)s.bh());
+  const dim3 grid((unsigned)((s.nb + 31) / 32), (unsigned)s.bh());
   if (s.d == 128)
     coarse_attn<128><<<grid, 256, 0, st>>>(scores, vmean, coarse, s.nb, s.nb_valid);
   else

@@ -122,3 +122,34 @@ def test_two_branch_pipeline(usv):
     ref = orc.fuse_outputs(orc.block_sparse_attn(Qf, Kf, Vf, ridx, rcnt, w.seq_valid)[0],
                            orc.coarse_attn(S_h, Vf, w.seq_valid), w.seq_valid, synth.as_f32(gf), synth.as_f32(gc))
     gu.assert_attn_close(out, ref, "bf16", False, "two-branch pipeline")
+
+
+def test_full_size_480p_two_branch(usv):
+    """The benchmark shape in the launch configuration bench.py --path two_branch times: selection bit-exact
+    on every row, the cube-level branch compared in full, the fused output on sampled query cubes."""
+    w = synth.WAN13_480P
+    Q, K, V = synth.gen_qkv(w)
+    q, k, v = gu.up(Q), gu.up(K), gu.up(V)
+    gen = torch.Generator(device=gu.DEV).manual_seed(7)
+    gf, gc = (torch.rand(q.shape, device=gu.DEV, generator=gen).to(torch.bfloat16) for _ in range(2))
+    S = usv.block_scores(q, k, seq_valid=w.seq_valid)
+    idx, cnt = usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, force_local=True)
+    fine = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32)
+    C = usv.coarse_attn(S, v, seq_valid=w.seq_valid)
+    out = usv.fuse_outputs(fine, C, gf, gc, seq_valid=w.seq_valid, out_dtype=torch.float32)
+    S_h, idx_h, cnt_h = gu.down(S), gu.down(idx), gu.down(cnt)
+    ridx, rcnt = orc.select_topk(S_h, w.keep, w.seq_valid, force_local=True)
+    np.testing.assert_array_equal(idx_h, ridx)
+    np.testing.assert_array_equal(cnt_h, rcnt)
+    C_ref = orc.coarse_attn(S_h, synth.as_f32(V), w.seq_valid)
+    gu.assert_f32_close(gu.down(C), C_ref, "coarse 480p")
+    rng = np.random.default_rng(9)
+    for h in (0, 5, 11):
+        blocks = sorted(set(rng.choice(w.nb, size=6, replace=False).tolist()) | {w.nb - 1})
+        fine_ref = gu.oracle_attn_blocks(Q[0, h], K[0, h], V[0, h], idx_h[0, h], cnt_h[0, h], w.seq_valid, blocks)
+        for i in blocks:
+            sl = slice(64 * i, 64 * i + 64)
+            nv = max(0, min(64, w.seq_valid - 64 * i))
+            ref = gu.down(gf[0, h, sl]).astype(np.float64) * fine_ref[i][0] + gu.down(gc[0, h, sl]).astype(np.float64) * C_ref[0, h, i]
+            ref[nv:] = 0.0
+            gu.assert_attn_close(gu.down(out[0, h, sl]), ref, "bf16", False, f"fused head {h} cube {i}")
