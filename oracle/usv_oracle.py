@@ -32,6 +32,12 @@ description; Figure 2's "top-k cube selection"):
                     the cube-level branch and the fusion of Figure 2 (right), for which the
                     paper prints no formula: the readings below.
 
+  attention_entropy / entropy_allocate
+                    Section 3.4 ("Entropy-aware dynamic sparsification policy"): the
+                    key marginal of the attention weights averaged over heads and
+                    queries, its normalised entropy, the weight (1 - h)^gamma and the
+                    clipped, mean-preserving redistribution of a base sparsity.
+
 Every function is pinned by tests/test_oracle_pins.py against something other
 than itself (closed forms, torch's scaled_dot_product_attention in fp64,
 pure-Python brute force, invariants).  No function here is "parity unpinned".
@@ -57,6 +63,11 @@ Readings taken where the paper is silent (also listed in the design notes):
   * fusion ("broadcast back to the full token grid, and fused"): every token r of cube i
     receives C_i; out_r = g_fine[r] * O_fine[r] + g_coarse[r] * C_cube(r), elementwise, with
     per-token, per-channel gates supplied by the model (absent gate = 1).
+  * attention entropy: the paper takes the marginal of the full N x N attention weights,
+    which a sparse kernel never forms (and does not say how it obtains them); here the
+    weights are the cube-level ones, A[h,i,:] = softmax_j(S[h,i,:]) over the cubes with a
+    valid token, and N in the equations is the number of such cubes.  With one token per
+    cube this is the paper's definition exactly.  0 log 0 = 0; one cube gives h = 0.
   * padded keys (token >= seq_valid) are masked; padded query rows output 0 and
     lse = -inf; a query cube with an empty list outputs 0.
 """
@@ -307,3 +318,31 @@ def fuse_outputs(fine, coarse, seq_valid, gate_fine=None, gate_coarse=None, bloc
     out[..., seq_valid:, :] = 0.0
     assert out.shape[-2] == N
     return out
+
+
+# --------------------------------------------------------------------------- #
+# entropy-aware allocation of sparsity (Section 3.4)
+# --------------------------------------------------------------------------- #
+def attention_entropy(S, seq_valid, block=BLOCK):
+    """Normalised entropy of the key marginal of the cube-level attention weights, one value per batch element.
+
+    S: fp32 scores [B,Hh,nb,nb].  A = row softmax over the valid cubes; marginal a(j) = mean over heads
+    and valid query cubes of A[h,i,j]; h = -sum_j a(j) log a(j) / log(n) with n the number of valid cubes."""
+    S = _f64(S)
+    n = (seq_valid + block - 1) // block
+    L = S[..., :n, :n]
+    A = np.exp(L - L.max(axis=-1, keepdims=True))
+    A = A / A.sum(axis=-1, keepdims=True)
+    a = A.mean(axis=(1, 2))  # [B, n]
+    if n == 1:
+        return np.zeros(S.shape[0])
+    with np.errstate(divide="ignore", invalid="ignore"):
+        terms = np.where(a > 0, a * np.log(a), 0.0)
+    return -terms.sum(axis=-1) / math.log(n)
+
+
+def entropy_allocate(h, rho_bar, gamma, rho_min, rho_max):
+    """Per-layer sparsity from per-layer entropies h[l]: w = (1 - h)^gamma, rho[l] = clip(rho_bar * w[l] / mean(w))."""
+    h = _f64(h)
+    w = (1.0 - h) ** gamma
+    return np.clip(rho_bar * w / w.mean(), rho_min, rho_max)

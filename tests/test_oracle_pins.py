@@ -473,3 +473,59 @@ def test_fuse_outputs_special_cases():
     np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-12)
     r = 100
     np.testing.assert_allclose(a[0, 1, r], gf[0, 1, r] * fine[0, 1, r] + gc[0, 1, r] * coarse[0, 1, 1], rtol=1e-12)
+
+
+# --------------------------------------------------------------------------- #
+# entropy-aware allocation (Section 3.4)
+# --------------------------------------------------------------------------- #
+def test_entropy_equals_token_level_definition_with_one_token_per_cube():
+    """With block = 1 the 'cubes' are tokens and the scores are the dense logits, so the oracle must
+    reproduce the paper's definition evaluated on torch's softmax of QK^T/sqrt(d) (library routine)."""
+    B, Hh, N, d = 2, 3, 24, 8
+    Q, K = randn(B, Hh, N, d), randn(B, Hh, N, d)
+    S = orc.block_scores(Q, K, N, block=1)
+    got = orc.attention_entropy(S, N, block=1)
+    A = torch.softmax(torch.from_numpy(Q) @ torch.from_numpy(K).transpose(-1, -2) / math.sqrt(d), dim=-1).numpy()
+    for b in range(B):
+        a = np.array([sum(A[b, h, i, j] for h in range(Hh) for i in range(N)) / (Hh * N) for j in range(N)])
+        h = -sum(x * math.log(x) for x in a) / math.log(N)
+        assert abs(got[b] - h) < 1e-6  # S was rounded to fp32 once
+
+
+def test_entropy_closed_forms():
+    """Equal scores -> uniform marginal -> h = 1; every query on one key -> h = 0; every query split
+    evenly over two keys -> log 2 / log n; cubes without a valid token are ignored; one cube -> 0."""
+    nb, N = 8, 8 * 64
+    S = np.zeros((1, 2, nb, nb), dtype=np.float32)
+    assert abs(orc.attention_entropy(S, N)[0] - 1.0) < 1e-12
+    S[..., 3] = 200.0
+    assert abs(orc.attention_entropy(S, N)[0]) < 1e-12
+    S[..., 5] = 200.0
+    assert abs(orc.attention_entropy(S, N)[0] - math.log(2) / math.log(nb)) < 1e-12
+    # only 6 valid cubes: the last two columns/rows (garbage) must not count, n = 6
+    S = np.zeros((1, 1, nb, nb), dtype=np.float32)
+    S[..., 6:] = 1e4
+    S[:, :, 6:, :] = -1e4
+    assert abs(orc.attention_entropy(S, 6 * 64 - 3)[0] - 1.0) < 1e-12
+    assert orc.attention_entropy(np.zeros((3, 1, 1, 1), dtype=np.float32), 10).tolist() == [0.0, 0.0, 0.0]
+    # marginal averages over queries BEFORE the entropy: two queries on different single keys -> log 2 / log n
+    S = np.full((1, 1, 4, 4), -200.0, dtype=np.float32)
+    S[0, 0, [0, 1], 0] = 200.0
+    S[0, 0, [2, 3], 2] = 200.0
+    assert abs(orc.attention_entropy(S, 256)[0] - math.log(2) / math.log(4)) < 1e-12
+
+
+def test_entropy_allocate_properties():
+    """Hand-computed example; without clipping the mean over layers equals the base sparsity (the
+    property the paper states); lower entropy -> more sparsity; clip bounds hold; gamma sharpens."""
+    rho = orc.entropy_allocate([0.5, 0.0, 0.75], 0.8, 2.0, 0.0, 10.0)
+    w = np.array([0.25, 1.0, 0.0625])
+    np.testing.assert_allclose(rho, 0.8 * w / (1.3125 / 3), rtol=1e-14)
+    assert abs(rho.mean() - 0.8) < 1e-14 and rho[1] > rho[0] > rho[2]
+    clipped = orc.entropy_allocate([0.5, 0.0, 0.75], 0.8, 2.0, 0.3, 0.95)
+    np.testing.assert_allclose(clipped, [0.8 * 0.25 / 0.4375, 0.95, 0.3], rtol=1e-14)
+    flat = orc.entropy_allocate([0.2, 0.2, 0.2, 0.2], 0.9, 3.0, 0.0, 1.0)
+    np.testing.assert_allclose(flat, 0.9, rtol=1e-14)
+    g1 = orc.entropy_allocate([0.2, 0.6], 0.5, 1.0, 0.0, 1.0)
+    g4 = orc.entropy_allocate([0.2, 0.6], 0.5, 4.0, 0.0, 1.0)
+    assert g4[0] - g4[1] > g1[0] - g1[1] > 0
