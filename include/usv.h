@@ -186,6 +186,42 @@ usv_status usv_fuse_outputs(const void* fine, int32_t fine_dtype, const float* c
                             int32_t out_dtype, void* out, void* stream);
 
 /*
+ * Entropy-aware allocation of sparsity (Section 3.4).  The paper averages the
+ * attention weights over heads and queries into a marginal over keys, takes its
+ * entropy normalised by log N, turns it into a weight (1 - h)^gamma and spreads
+ * a base sparsity over the layers in proportion to the weights, clipped.
+ * The full N x N weights are never formed by a sparse kernel and the paper does
+ * not say where it takes them from; here they are the cube-level weights
+ *   A[b,h,i,:] = softmax_j(scores[b,h,i,:]) over the cubes j with a valid token,
+ *   a[b,j]     = mean over h and valid i of A[b,h,i,j],
+ *   entropy[b] = - sum_j a[b,j] log a[b,j] / log n,   n = number of valid cubes
+ * (0 log 0 = 0; n = 1 gives 0).  With one token per cube this is the paper's
+ * definition exactly.
+ */
+
+/* Bytes of device scratch usv_attn_entropy needs (per-tile column sums:
+ * B * Hh * ceil(nb_valid / 32) * nb * 4).  Returns 0 for an invalid shape. */
+size_t usv_entropy_workspace_bytes(const usv_shape* shape);
+
+/* scores  : [B, Hh, nb, nb] fp32 (device, read only), from usv_block_scores
+ * entropy : [B] fp32 (device, written), each in [0, 1]
+ * ws      : device scratch >= usv_entropy_workspace_bytes(shape)
+ * Only shape->batch/heads/seq_len/seq_valid/block are used.  The summation order
+ * is fixed: the result is bit-reproducible. */
+usv_status usv_attn_entropy(const float* scores, const usv_shape* shape, float* entropy, void* ws,
+                            size_t ws_bytes, void* stream);
+
+/* HOST helper, launches nothing.  entropy[l], l < layers: the entropies of the
+ * layers of one diffusion step (host array, each in [0, 1]).
+ *   w[l]   = (1 - entropy[l])^gamma,            gamma >= 1
+ *   rho[l] = clip(rho_min, rho_max, rho_bar * w[l] / mean_l(w))
+ * Without clipping the mean of rho over the layers is rho_bar.  If every weight
+ * is 0, rho[l] = clip(rho_bar).  A sparsity rho turns into a per-row budget as
+ * k = max(1, floor((1 - rho) * nb)) in the caller. */
+usv_status usv_entropy_allocate(const float* entropy, int32_t layers, float rho_bar, float gamma,
+                                float rho_min, float rho_max, float* rho);
+
+/*
  * Either side of the three stages: the token order (Figure 2, right: queries, keys
  * and values are "partitioned into local 3D cubes"; the outputs are "broadcast back
  * to the full token grid").  A model holds tokens in raster order of the latent

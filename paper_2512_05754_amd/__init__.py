@@ -8,6 +8,8 @@ _BINDING_NAMES = (
     "block_scores",
     "select_topk",
     "block_sparse_attn",
+    "attn_entropy",
+    "entropy_allocate",
     "coarse_attn",
     "fuse_outputs",
     "cube_token_order",

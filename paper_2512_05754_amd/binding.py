@@ -23,6 +23,9 @@ EXPORTED_SYMBOLS = (
     "usv_coarse_workspace_bytes",
     "usv_coarse_attn",
     "usv_fuse_outputs",
+    "usv_entropy_workspace_bytes",
+    "usv_attn_entropy",
+    "usv_entropy_allocate",
     "usv_block_sparse_attn",
     "usv_cube_token_order",
     "usv_cube_gather",
@@ -87,6 +90,10 @@ def lib() -> ctypes.CDLL:
     L.usv_coarse_workspace_bytes.restype, L.usv_coarse_workspace_bytes.argtypes = sz, [sp]
     L.usv_coarse_attn.restype, L.usv_coarse_attn.argtypes = i32, [vp, vp, sp, vp, vp, sz, vp]
     L.usv_fuse_outputs.restype, L.usv_fuse_outputs.argtypes = i32, [vp, i32, vp, vp, vp, sp, i32, vp, vp]
+    L.usv_entropy_workspace_bytes.restype, L.usv_entropy_workspace_bytes.argtypes = sz, [sp]
+    L.usv_attn_entropy.restype, L.usv_attn_entropy.argtypes = i32, [vp, sp, vp, vp, sz, vp]
+    L.usv_entropy_allocate.restype = i32
+    L.usv_entropy_allocate.argtypes = [vp, i32, f32, f32, f32, f32, vp]
     L.usv_block_sparse_attn.restype = i32
     L.usv_block_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, i32, f32, i32, vp, vp, vp]
     gp, stp = ctypes.POINTER(UsvGrid), ctypes.POINTER(UsvStrides)
@@ -319,3 +326,31 @@ def fuse_outputs(fine, coarse, gate_fine=None, gate_coarse=None, seq_valid=None,
                                   None if gate_coarse is None else _dev(gate_coarse, "gate_coarse"),
                                   ctypes.byref(sh), _dt(out), _dev(out, "out"), _stream()))
     return out
+
+
+def attn_entropy(scores, seq_valid=None, out=None, workspace=None):
+    """usv_attn_entropy: normalised entropy [B] fp32 of the key marginal of the cube-level attention weights."""
+    if scores.dim() != 4 or scores.shape[2] != scores.shape[3]:
+        raise ValueError("scores must be [B, Hh, nb, nb]")
+    B, Hh, nb, _ = scores.shape
+    N = nb * BLOCK
+    sh = UsvShape(B, Hh, N, N if seq_valid is None else int(seq_valid), 0, BLOCK, USV_F32)
+    if out is None:
+        out = torch.empty((B,), dtype=torch.float32, device=scores.device)
+    need = int(lib().usv_entropy_workspace_bytes(ctypes.byref(sh)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=scores.device)
+    _check(lib().usv_attn_entropy(_dev(scores, "scores", torch.float32), ctypes.byref(sh), _dev(out, "entropy", torch.float32),
+                                  _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()))
+    return out
+
+
+def entropy_allocate(entropy, rho_bar, gamma=1.0, rho_min=0.0, rho_max=1.0):
+    """usv_entropy_allocate (host): per-layer sparsity ratios from per-layer entropies."""
+    import numpy as np
+
+    h = np.ascontiguousarray(np.asarray(entropy, dtype=np.float32).reshape(-1))
+    rho = np.empty_like(h)
+    _check(lib().usv_entropy_allocate(h.ctypes.data_as(ctypes.c_void_p), int(h.size), float(rho_bar), float(gamma),
+                                      float(rho_min), float(rho_max), rho.ctypes.data_as(ctypes.c_void_p)))
+    return rho

@@ -222,6 +222,49 @@ usv_status usv_fuse_outputs(const void* fine, int32_t fine_dtype, const float* c
                     "usv_fuse_outputs launch");
 }
 
+size_t usv_entropy_workspace_bytes(const usv_shape* shape) {
+  usv::Dims s;
+  if (check_shape(shape, false, &s) != USV_OK) return 0;
+  return (size_t)s.bh() * ((s.nb_valid + 31) / 32) * s.nb * sizeof(float);
+}
+
+usv_status usv_attn_entropy(const float* scores, const usv_shape* shape, float* entropy, void* ws, size_t ws_bytes,
+                            void* stream) {
+  usv::Dims s;
+  USV_TRY(check_shape(shape, false, &s));
+  USV_TRY(check_ptr(scores, "scores"));
+  if (!entropy) return fail(USV_ERR_INVALID_ARG, "entropy is NULL");
+  if (reinterpret_cast<uintptr_t>(entropy) & 3u) return fail(USV_ERR_INVALID_ARG, "entropy is not 4-byte aligned");
+  const size_t need = usv_entropy_workspace_bytes(shape);
+  if (!ws || !aligned16(ws) || ws_bytes < need)
+    return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
+  return hip_result(usv::launch_attn_entropy(scores, s, entropy, static_cast<float*>(ws), static_cast<hipStream_t>(stream)),
+                    "usv_attn_entropy launch");
+}
+
+usv_status usv_entropy_allocate(const float* entropy, int32_t layers, float rho_bar, float gamma, float rho_min,
+                                float rho_max, float* rho) {
+  if (!entropy || !rho) return fail(USV_ERR_INVALID_ARG, "entropy or rho is NULL");
+  if (layers < 1) return fail(USV_ERR_INVALID_ARG, "layers must be >= 1");
+  if (!(gamma >= 1.0f)) return fail(USV_ERR_INVALID_ARG, "gamma must be >= 1");
+  if (!(rho_min <= rho_max)) return fail(USV_ERR_INVALID_ARG, "rho_min must be <= rho_max");
+  double mean = 0.0;
+  for (int l = 0; l < layers; ++l) {
+    if (!(entropy[l] >= 0.0f && entropy[l] <= 1.0f + 1e-6f))
+      return fail(USV_ERR_INVALID_ARG, "entropy[%d] = %g is outside [0, 1]", l, (double)entropy[l]);
+    mean += std::pow(std::fmax(0.0, 1.0 - (double)entropy[l]), (double)gamma);
+  }
+  mean /= layers;
+  for (int l = 0; l < layers; ++l) {
+    const double w = std::pow(std::fmax(0.0, 1.0 - (double)entropy[l]), (double)gamma);
+    // every layer at entropy 1 carries no weight at all: keep the base schedule
+    const double r = mean > 0.0 ? (double)rho_bar * w / mean : (double)rho_bar;
+    rho[l] = (float)std::fmin(std::fmax(r, (double)rho_min), (double)rho_max);
+  }
+  g_err[0] = '\0';
+  return USV_OK;
+}
+
 usv_status usv_cube_token_order(const usv_grid* grid, int32_t* order) {
   usv::CubeGrid g;
   USV_TRY(check_grid(grid, nullptr, &g));

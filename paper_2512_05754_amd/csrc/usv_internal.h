@@ -41,6 +41,7 @@ hipError_t launch_select_topk(const float* scores, const Dims& s, int k, const i
                               bool force_local, int32_t* idx, int32_t* cnt, hipStream_t st);
 hipError_t launch_pool_means(const void* x, const Dims& s, float* means, hipStream_t st);
 hipError_t launch_coarse_attn(const float* scores, const float* vmean, const Dims& s, float* coarse, hipStream_t st);
+hipError_t launch_attn_entropy(const float* scores, const Dims& s, float* entropy, float* ws, hipStream_t st);
 hipError_t launch_fuse_outputs(const void* fine, bool fine_f32, const float* coarse, const void* gate_fine,
                                const void* gate_coarse, bool gates_f32, void* out, bool out_f32, const Dims& s,
                                hipStream_t st);

@@ -169,3 +169,45 @@ def test_coarse_and_fuse_reject_bad_arguments_before_launch():
     assert name(L.usv_fuse_outputs(FAKE, f32, None, None, None, ctypes.byref(sh), f32, FAKE + 64, None)) == "USV_ERR_INVALID_ARG"
     assert name(L.usv_select_topk_ex(FAKE, ctypes.byref(sh), 2, None, 4, 6, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
     assert b"flag" in L.usv_last_error()
+
+
+# --------------------------------------------------------------------------- #
+# entropy-aware allocation: the host helper against the oracle
+# --------------------------------------------------------------------------- #
+def test_entropy_allocate_matches_oracle():
+    import numpy as np
+
+    from oracle import usv_oracle as orc
+
+    rng = np.random.default_rng(0)
+    for L, gamma, bar, lo, hi in [(30, 2.0, 0.9, 0.5, 0.98), (1, 1.0, 0.8, 0.0, 1.0), (7, 4.0, 0.95, 0.9, 0.99),
+                                  (12, 1.5, 0.5, 0.0, 10.0)]:
+        h = rng.uniform(0, 1, size=L).astype(np.float32)
+        got = binding.entropy_allocate(h, bar, gamma, lo, hi)
+        ref = orc.entropy_allocate(h.astype(np.float64), bar, gamma, lo, hi)
+        np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-7)
+    # without clipping the layer mean is the base sparsity
+    h = rng.uniform(0, 1, size=16).astype(np.float32)
+    assert abs(binding.entropy_allocate(h, 0.8, 2.0, 0.0, 100.0).mean() - 0.8) < 1e-6
+    # all layers at entropy 1: no weight anywhere, the base schedule is kept
+    assert binding.entropy_allocate([1.0, 1.0], 0.7, 2.0, 0.0, 1.0).tolist() == pytest.approx([0.7, 0.7])
+
+
+def test_entropy_calls_reject_bad_arguments():
+    L = binding.lib()
+    name = lambda rc: L.usv_status_string(rc).decode()
+    sh = shape()
+    need = L.usv_entropy_workspace_bytes(ctypes.byref(sh))
+    assert need == 2 * 1 * 16 * 4  # B*Hh = 2, one 32-row tile of 16 cubes
+    assert name(L.usv_attn_entropy(FAKE, ctypes.byref(sh), FAKE, FAKE, need - 1, None)) == "USV_ERR_WORKSPACE"
+    assert name(L.usv_attn_entropy(FAKE, ctypes.byref(sh), None, FAKE, need, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_attn_entropy(None, ctypes.byref(sh), FAKE, FAKE, need, None)) == "USV_ERR_INVALID_ARG"
+    buf = (ctypes.c_float * 3)(0.1, 0.2, 1.5)
+    out = (ctypes.c_float * 3)()
+    assert name(L.usv_entropy_allocate(buf, 3, 0.8, 2.0, 0.0, 1.0, out)) == "USV_ERR_INVALID_ARG"  # entropy > 1
+    buf[2] = 0.5
+    assert name(L.usv_entropy_allocate(buf, 3, 0.8, 0.5, 0.0, 1.0, out)) == "USV_ERR_INVALID_ARG"  # gamma < 1
+    assert name(L.usv_entropy_allocate(buf, 3, 0.8, 2.0, 0.9, 0.1, out)) == "USV_ERR_INVALID_ARG"  # min > max
+    assert name(L.usv_entropy_allocate(buf, 0, 0.8, 2.0, 0.0, 1.0, out)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_entropy_allocate(None, 3, 0.8, 2.0, 0.0, 1.0, out)) == "USV_ERR_INVALID_ARG"
+    assert L.usv_entropy_allocate(buf, 3, 0.8, 2.0, 0.0, 1.0, out) == 0
