@@ -83,13 +83,14 @@ def cpu_baseline(w, Q, K, V, n_heads, two_branch=False):
     fine = orc.block_sparse_attn(Qf, Kf, Vf, idx, cnt, w.seq_valid)[0]
     if two_branch:
         orc.fuse_outputs(fine, orc.coarse_attn(S, Vf, w.seq_valid), w.seq_valid, np.ones_like(fine), np.ones_like(fine))
+        orc.attention_entropy(S, w.seq_valid)
     dt = time.perf_counter() - t0
     tiles = int(cnt.sum())
     flop = tiles * 4.0 * 64 * 64 * w.head_dim
     return {
         "value": flop / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
         "sample": f"{n_heads} of {w.batch * w.heads} heads (all {w.nb} query blocks each, {tiles} tiles), "
-                  f"{5 if two_branch else 3} stages, numpy fp64, {dt:.2f} s; host has {len(os.sched_getaffinity(0))} usable cores",
+                  f"{6 if two_branch else 3} stages, numpy fp64, {dt:.2f} s; host has {len(os.sched_getaffinity(0))} usable cores",
         "seconds": dt,
         "ms_per_call_extrapolated": dt * 1e3 * (w.batch * w.heads) / n_heads,
     }
@@ -252,6 +253,8 @@ def main():
         coarse = torch.empty((B, Hh, nb, d), dtype=torch.float32, device=dev)
         ws_c = torch.empty(B * Hh * nb * d * 4, dtype=torch.uint8, device=dev)
         fused = torch.empty((B, Hh, N, d), dtype=q.dtype, device=dev)
+        ent = torch.empty((B,), dtype=torch.float32, device=dev)
+        ws_e = torch.empty(B * Hh * ((nb + 31) // 32) * nb * 4, dtype=torch.uint8, device=dev)
         branch_events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     step_no = [0]
 
@@ -276,6 +279,9 @@ def main():
             usv.fuse_outputs(out, coarse, gates[0], gates[1], seq_valid=w.seq_valid, out=fused)
             if be is not None:
                 be[1].record()
+            usv.attn_entropy(S, seq_valid=w.seq_valid, out=ent, workspace=ws_e)  # feeds the next step's budgets
+            if be is not None:
+                be[2].record()
                 step_no[0] += 1
 
     if args.copy_calibration:
@@ -325,7 +331,7 @@ def main():
             "block": 64, "blocks": nb, "keep": w.keep if w.keep else f"U[{w.budget_lo},{w.budget_hi}]",
             "computed_tiles": tiles, "flop_per_step": flop, "out_dtype": args.out_dtype if w.dtype == "bf16" else "f32",
             "step": "usv_block_scores + usv_select_topk + usv_block_sparse_attn"
-                    + (" + usv_coarse_attn + usv_fuse_outputs (local cube forced)" if two_branch else ""),
+                    + (" + usv_coarse_attn + usv_fuse_outputs + usv_attn_entropy (local cube forced)" if two_branch else ""),
         },
         "stages_ms": {"block_scores": float(avg[0]), "select_topk": float(avg[1]), "block_sparse_attn": float(avg[2])},
         "attn_ms_min": float(st_ms[:, 2].min()),
@@ -346,6 +352,10 @@ def main():
     if two_branch:
         c_ms = float(np.mean([evs[i][3].elapsed_time(branch_events[i][0]) for i in range(args.steps)]))
         f_ms = float(np.mean([branch_events[i][0].elapsed_time(branch_events[i][1]) for i in range(args.steps)]))
+        e_ms = float(np.mean([branch_events[i][1].elapsed_time(branch_events[i][2]) for i in range(args.steps)]))
+        result["stages_ms"]["attn_entropy"] = e_ms
+        result["stage_hbm_gbs"]["attn_entropy"] = B * Hh * nb * nb * 4 / (e_ms * 1e-3) / 1e9
+        result["config"]["attn_entropy"] = [float(x) for x in ent.cpu()]
         result["config"]["path"] = "two_branch"
         result["stages_ms"]["coarse_attn"] = c_ms
         result["stages_ms"]["fuse_outputs"] = f_ms

@@ -89,21 +89,40 @@ __global__ __launch_bounds__(256) void entropy_partials(const float* __restrict_
   }
 }
 
-// grid = B; 256 threads.
-__global__ __launch_bounds__(256) void entropy_finish(const float* __restrict__ partial, float* __restrict__ entropy,
-                                                      int nb, int nb_valid, int Hh, int tiles) {
+// grid = B; 1024 threads: 256 columns x 4 row groups.  Row group q adds partial rows q, q + 4, ... (eight
+// loads in flight), the four group sums are added in a fixed order.
+__global__ __launch_bounds__(1024) void entropy_finish(const float* __restrict__ partial, float* __restrict__ entropy,
+                                                       int nb, int nb_valid, int Hh, int tiles) {
+  __shared__ float grp[4][256];
   __shared__ float red[256];
-  const int b = blockIdx.x, tid = threadIdx.x;
-  const float* p = partial + (long long)b * Hh * tiles * nb;
+  const int b = blockIdx.x, tid = threadIdx.x, col = tid & 255, q = tid >> 8;
+  const int T = Hh * tiles;
+  const float* p = partial + (long long)b * T * nb;
   const float inv_rows = 1.0f / ((float)Hh * (float)nb_valid);
   float acc = 0.f;
-  for (int j = tid; j < nb_valid; j += 256) {
+  for (int j0 = 0; j0 < nb_valid; j0 += 256) {  // uniform trip count: barriers inside
+    const int j = j0 + col;
     float a = 0.f;
-    for (int t = 0; t < Hh * tiles; ++t) a += p[(long long)t * nb + j];
-    a *= inv_rows;
-    if (a > 0.f) acc += a * logf(a);
+    if (j < nb_valid) {
+      int t = q;
+      for (; t + 28 < T; t += 32) {
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = p[(long long)(t + 4 * u) * nb + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += x[u];
+      }
+      for (; t < T; t += 4) a += p[(long long)t * nb + j];
+    }
+    grp[q][col] = a;
+    __syncthreads();
+    if (q == 0 && j < nb_valid) {
+      const float m = (((grp[0][col] + grp[1][col]) + grp[2][col]) + grp[3][col]) * inv_rows;
+      if (m > 0.f) acc += m * logf(m);
+    }
+    __syncthreads();
   }
-  red[tid] = acc;
+  if (q == 0) red[col] = acc;
   __syncthreads();
   for (int s = 128; s >= 1; s >>= 1) {
     if (tid < s) red[tid] += red[tid + s];
@@ -120,7 +139,7 @@ hipError_t launch_attn_entropy(const float* scores, const Dims& s, float* entrop
   entropy_partials<<<dim3((unsigned)tiles, (unsigned)s.bh()), 256, 0, st>>>(scores, ws, s.nb, s.nb_valid, tiles);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  entropy_finish<<<(unsigned)s.B, 256, 0, st>>>(ws, entropy, s.nb, s.nb_valid, s.Hh, tiles);
+  entropy_finish<<<(unsigned)s.B, 1024, 0, st>>>(ws, entropy, s.nb, s.nb_valid, s.Hh, tiles);
   return hipGetLastError();
 }
 
