@@ -38,6 +38,13 @@ description; Figure 2's "top-k cube selection"):
                     queries, its normalised entropy, the weight (1 - h)^gamma and the
                     clipped, mean-preserving redistribution of a base sparsity.
 
+  merge_plan / merge_apply / unmerge_apply
+                    Section 3.3 ("Token merging for video"): 3-D bipartite partition,
+                    head-averaged key descriptors, cosine similarity, the r most
+                    confident sources, mean aggregation into the destinations, the
+                    merged sequence [unmerged sources || destinations], and the
+                    exact unmerge.
+
 Every function is pinned by tests/test_oracle_pins.py against something other
 than itself (closed forms, torch's scaled_dot_product_attention in fp64,
 pure-Python brute force, invariants).  No function here is "parity unpinned".
@@ -68,6 +75,15 @@ Readings taken where the paper is silent (also listed in the design notes):
     weights are the cube-level ones, A[h,i,:] = softmax_j(S[h,i,:]) over the cubes with a
     valid token, and N in the equations is the number of such cubes.  With one token per
     cube this is the paper's definition exactly.  0 log 0 = 0; one cube gives h = 0.
+  * token merging: tokens are in raster order of the T x H x W grid; the merge blocks
+    (s_t, s_h, s_w) tile the grid from the origin and are cut by its boundary; the
+    destination of a block is its first token (local coordinates 0,0,0), every other token
+    of the block is a source.  "Sources and destinations are restricted to local 3D blocks":
+    the only candidate destination of a source is the one of its own block, so j*(i) is that
+    token and u_i their cosine similarity (a zero descriptor gives similarity 0).  The r
+    selected sources are the first r in the order (u descending, raster index ascending);
+    the merged sequence lists the unmerged sources, then the destinations, each in ascending
+    raster index.
   * padded keys (token >= seq_valid) are masked; padded query rows output 0 and
     lse = -inf; a query cube with an empty list outputs 0.
 """
@@ -346,3 +362,79 @@ def entropy_allocate(h, rho_bar, gamma, rho_min, rho_max):
     h = _f64(h)
     w = (1.0 - h) ** gamma
     return np.clip(rho_bar * w / w.mean(), rho_min, rho_max)
+
+
+# --------------------------------------------------------------------------- #
+# token merging (Section 3.3)
+# --------------------------------------------------------------------------- #
+def merge_partition(grid, mblock):
+    """dst[i] = raster index of the destination token of token i's merge block (dst[i] == i for destinations)."""
+    T, H, W = grid
+    st, sh, sw = mblock
+    dst = np.empty(T * H * W, dtype=np.int64)
+    for t in range(T):
+        for h in range(H):
+            for w in range(W):
+                dst[(t * H + h) * W + w] = ((t - t % st) * H + (h - h % sh)) * W + (w - w % sw)
+    return dst
+
+
+def merge_similarity(K, grid, mblock):
+    """u[b, i]: cosine similarity between the head-averaged key descriptors of source i and of its
+    destination; -inf at the destinations themselves.  K: [B, Hh, N, d] in raster order."""
+    m = _f64(K).mean(axis=1)  # head-averaged descriptors [B, N, d]
+    dst = merge_partition(grid, mblock)
+    norm = np.sqrt((m * m).sum(axis=-1))
+    dot = (m * m[:, dst, :]).sum(axis=-1)
+    den = norm * norm[:, dst]
+    u = np.where(den > 0, dot / np.where(den > 0, den, 1.0), 0.0)
+    u[:, dst == np.arange(len(dst))] = -np.inf
+    return u
+
+
+def merge_plan(u, grid, mblock, r):
+    """From the similarities u [B, N] (fp32 values as handed over): which sources merge and where every
+    token's features end up.  Returns row_of [B, N] (row of the merged sequence that token k reads back
+    from: its own row, or its destination's if it was merged) and src_of [B, N - r] (raster index of
+    the token that owns each merged row)."""
+    u = np.asarray(u, dtype=np.float32)
+    B, N = u.shape
+    dst = merge_partition(grid, mblock)
+    is_dst = dst == np.arange(N)
+    sources = np.nonzero(~is_dst)[0]
+    assert 0 <= r <= len(sources)
+    row_of = np.empty((B, N), dtype=np.int32)
+    src_of = np.empty((B, N - r), dtype=np.int32)
+    for b in range(B):
+        order = sorted(sources.tolist(), key=lambda i: (-float(u[b, i]), i))
+        merged = set(order[:r])
+        unmerged = [i for i in sources.tolist() if i not in merged]
+        seq = unmerged + np.nonzero(is_dst)[0].tolist()
+        src_of[b] = seq
+        pos = {tok: p for p, tok in enumerate(seq)}
+        for k in range(N):
+            row_of[b, k] = pos[int(dst[k])] if k in merged else pos[k]
+    return row_of, src_of
+
+
+def merge_apply(X, row_of, src_of, seq_len):
+    """Merged features: row p is the mean of the features of every token that reads back from row p
+    (a destination with its merged sources; an unmerged source alone).  X: [B, Hh, N, d] ->
+    [B, Hh, seq_len, d] (fp64), rows past N - r are zero."""
+    X = _f64(X)
+    B, Hh, N, d = X.shape
+    out = np.zeros((B, Hh, seq_len, d))
+    for b in range(B):
+        count = np.zeros(src_of.shape[1])
+        acc = np.zeros((Hh, src_of.shape[1], d))
+        for k in range(N):
+            acc[:, row_of[b, k], :] += X[b, :, k, :]
+            count[row_of[b, k]] += 1
+        out[b, :, : src_of.shape[1], :] = acc / count[None, :, None]
+    return out
+
+
+def unmerge_apply(Y, row_of):
+    """Token k takes row row_of[k] of the merged sequence.  Y: [B, Hh, seq_len, d] -> [B, Hh, N, d]."""
+    Y = np.asarray(Y)
+    return np.stack([Y[b][:, row_of[b], :] for b in range(Y.shape[0])])

@@ -529,3 +529,104 @@ def test_entropy_allocate_properties():
     g1 = orc.entropy_allocate([0.2, 0.6], 0.5, 1.0, 0.0, 1.0)
     g4 = orc.entropy_allocate([0.2, 0.6], 0.5, 4.0, 0.0, 1.0)
     assert g4[0] - g4[1] > g1[0] - g1[1] > 0
+
+
+# --------------------------------------------------------------------------- #
+# token merging (Section 3.3)
+# --------------------------------------------------------------------------- #
+def test_merge_hand_example():
+    """1 x 2 x 4 grid, blocks 1 x 2 x 2, two heads, written out by hand.
+    Raster indices: row 0 = 0 1 2 3, row 1 = 4 5 6 7.  Blocks {0,1,4,5} (destination 0) and {2,3,6,7}
+    (destination 2).  Head-averaged descriptors (d = 2):
+      m0=(1,0) m1=(1,0) m4=(0,1) m5=(1,1) | m2=(0,2) m3=(0,-1) m6=(3,4) m7=(0,5)
+    cosines to the block's destination: u1=1, u4=0, u5=1/sqrt2 | u3=-1, u6=0.8, u7=1.
+    r = 3 -> merged = {1, 7, 6} (u = 1, 1, 0.8; the tie 1 vs 7 goes to the lower index but both are in).
+    merged sequence = unmerged sources [3, 4, 5] then destinations [0, 2]."""
+    grid, mb = (1, 2, 4), (1, 2, 2)
+    m = np.array([[1, 0], [1, 0], [0, 2], [0, -1], [0, 1], [1, 1], [3, 4], [0, 5]], dtype=np.float64)
+    K = np.stack([m + 0.5, m - 0.5])[None]  # two heads whose mean is m
+    u = orc.merge_similarity(K, grid, mb)
+    expect_u = [-np.inf, 1.0, -np.inf, -1.0, 0.0, 1 / math.sqrt(2), 0.8, 1.0]
+    np.testing.assert_allclose(u[0], expect_u, rtol=1e-12, atol=1e-12)
+    row_of, src_of = orc.merge_plan(u, grid, mb, 3)
+    assert src_of[0].tolist() == [3, 4, 5, 0, 2]
+    assert row_of[0].tolist() == [3, 3, 4, 0, 1, 2, 4, 4]
+    X = np.arange(8, dtype=np.float64).reshape(1, 1, 8, 1) * 10
+    Y = orc.merge_apply(X, row_of, src_of, 8)
+    assert Y[0, 0, :, 0].tolist() == [30, 40, 50, (0 + 10) / 2, (20 + 60 + 70) / 3, 0, 0, 0]
+    Z = orc.unmerge_apply(Y, row_of)
+    assert Z[0, 0, :, 0].tolist() == [5, 5, 50, 30, 40, 50, 50, 50]
+    # r = 2 with a tie at the boundary: u1 = u7 = 1 both in; r = 1 keeps only the lower index
+    assert orc.merge_plan(u, grid, mb, 1)[1][0].tolist() == [3, 4, 5, 6, 7, 0, 2]
+
+
+def test_merge_everything_is_average_pooling():
+    """r = |A| merges every source: the merged sequence is the block means (NumPy reshape + mean on a
+    divisible grid) and unmerging broadcasts them back (np.repeat-style upsampling)."""
+    grid, mb = (2, 4, 6), (2, 2, 3)
+    N = 48
+    K, X = randn(2, 3, N, 4), randn(2, 3, N, 5)
+    u = orc.merge_similarity(K, grid, mb)
+    n_dst = 1 * 2 * 2
+    row_of, src_of = orc.merge_plan(u, grid, mb, N - n_dst)
+    Y = orc.merge_apply(X, row_of, src_of, n_dst)
+    pooled = X.reshape(2, 3, 1, 2, 2, 2, 2, 3, 5).mean(axis=(3, 5, 7)).reshape(2, 3, n_dst, 5)
+    np.testing.assert_allclose(Y, pooled, rtol=1e-12, atol=1e-12)
+    up = np.broadcast_to(pooled.reshape(2, 3, 1, 1, 2, 1, 2, 1, 5), (2, 3, 1, 2, 2, 2, 2, 3, 5)).reshape(2, 3, N, 5)
+    np.testing.assert_allclose(orc.unmerge_apply(Y, row_of), up, rtol=1e-12, atol=1e-12)
+
+
+def test_merge_plan_properties_on_a_cut_grid():
+    """Cut blocks, batch-dependent selections: the merged sequence has N - r rows, lists unmerged
+    sources then destinations in ascending raster order, the r merged sources are exactly the r best
+    by (u desc, index asc) (checked with lexsort), merged tokens read their destination's row, and a
+    tensor that is constant inside every merged group survives merge + unmerge unchanged."""
+    grid, mb = (3, 5, 7), (2, 2, 4)
+    N = 105
+    K = randn(2, 4, N, 6)
+    u = orc.merge_similarity(K, grid, mb).astype(np.float32)
+    u[0, 1] = u[0, 2]  # a tie
+    dst = orc.merge_partition(grid, mb)
+    # brute-force partition check: same block <=> same (t//2, h//2, w//4)
+    t, h, w = np.arange(N) // 35, (np.arange(N) // 7) % 5, np.arange(N) % 7
+    key = (t // 2) * 100 + (h // 2) * 10 + w // 4
+    assert all(key[i] == key[dst[i]] and dst[i] <= i for i in range(N))
+    assert len(set(dst.tolist())) == len(set(key.tolist()))
+    sources = np.nonzero(dst != np.arange(N))[0]
+    for r in (0, 17, len(sources)):
+        row_of, src_of = orc.merge_plan(u, grid, mb, r)
+        assert src_of.shape == (2, N - r)
+        for b in range(2):
+            best = sources[np.lexsort((sources, -u[b, sources].astype(np.float64)))][:r]
+            merged = set(best.tolist())
+            seq = src_of[b].tolist()
+            n_unmerged = len(sources) - r
+            assert seq[:n_unmerged] == sorted(set(sources.tolist()) - merged)
+            assert seq[n_unmerged:] == sorted(set(dst.tolist()))
+            for k in range(N):
+                owner = dst[k] if k in merged else k
+                assert seq[row_of[b, k]] == owner
+        X = randn(2, 1, N, 3)
+        for b in range(2):  # make X constant inside every merged group
+            X[b, :, :, :] = X[b][:, np.asarray(src_of[b])[row_of[b]], :]
+        Y = orc.merge_apply(X, row_of, src_of, N - r + 3)
+        assert not Y[:, :, N - r:].any()
+        np.testing.assert_allclose(orc.unmerge_apply(Y, row_of), X, rtol=1e-12, atol=1e-12)
+
+
+def test_merge_similarity_definition():
+    """u against an explicit per-token loop: head mean, dot over norms; zero descriptor -> 0."""
+    grid, mb = (2, 3, 3), (2, 2, 2)
+    K = randn(1, 3, 18, 5)
+    K[0, :, 4, :] = 0.0
+    u = orc.merge_similarity(K, grid, mb)
+    dst = orc.merge_partition(grid, mb)
+    for i in range(18):
+        mi = sum(K[0, h, i] for h in range(3)) / 3
+        mj = sum(K[0, h, dst[i]] for h in range(3)) / 3
+        if dst[i] == i:
+            assert np.isneginf(u[0, i])
+        elif i == 4:
+            assert u[0, i] == 0.0
+        else:
+            assert abs(u[0, i] - float(mi @ mj) / math.sqrt(float(mi @ mi) * float(mj @ mj))) < 1e-12
