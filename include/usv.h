@@ -241,8 +241,8 @@ usv_status usv_entropy_allocate(const float* entropy, int32_t layers, float rho_
 
 /* Token grid and cube (host struct). */
 typedef struct {
-  int32_t T, H, W;    /* latent grid, T*H*W == shape->seq_valid */
-  int32_t ct, ch, cw; /* cube, ct*ch*cw == shape->block */
+  int32_t T, H, W;    /* latent grid, T*H*W == shape->seq_valid (merge calls: see there) */
+  int32_t ct, ch, cw; /* cube, ct*ch*cw == shape->block (in the merge calls: the merge block, any size) */
 } usv_grid;
 
 /* Element strides of a raster-ordered tensor whose channel index is contiguous
@@ -274,6 +274,59 @@ usv_status usv_cube_gather(const void* raster, const usv_strides* strides, const
  * `raster` written and `cube` read only. */
 usv_status usv_cube_scatter(const void* cube, const usv_shape* shape, const usv_grid* grid,
                             void* raster, const usv_strides* strides, void* stream);
+
+/*
+ * Token merging (Section 3.3, "Token merging for video").  Tokens are in RASTER
+ * order of the T x H x W grid.  The grid is tiled from the origin by merge blocks
+ * of s_t x s_h x s_w tokens (usv_grid.ct/ch/cw; cut at the boundary).  The first
+ * token of a block (local 0,0,0) is its destination, the others are sources.
+ *   descriptor  m_i = mean over heads of K[b,h,i,:]                       (fp32)
+ *   similarity  u_i = cos(m_i, m_dst(i)) for a source i, -inf for a destination
+ *               (the paper restricts sources and destinations to local 3-D blocks:
+ *               a source's only candidate is the destination of its own block;
+ *               a zero descriptor gives 0)
+ *   selection   the r sources first in the order (u descending, index ascending)
+ *               are merged into their destinations; r <= number of sources
+ *   merge       destination row = mean of its own and its merged sources' rows;
+ *               unmerged sources keep theirs
+ *   sequence    [unmerged sources, ascending index] then [destinations, ascending
+ *               index]: N - r rows
+ *   unmerge     token k reads its own row, a merged source its destination's row
+ * In these calls `shape` describes the MERGED tensors: seq_valid = N - r rows are
+ * real, seq_len (a multiple of 64) is the padded row count; r is therefore
+ * T*H*W - seq_valid.  Raster tensors are contiguous [B, Hh, T*H*W, d].  After
+ * merging, the three stages run on the merged tensors with the same shape.
+ */
+
+/* Bytes of device scratch usv_merge_similarity needs (descriptors and their
+ * squared norms: B * T*H*W * (d + 1) * 4).  Returns 0 for invalid arguments. */
+size_t usv_merge_workspace_bytes(const usv_shape* shape, const usv_grid* grid);
+
+/* k  : [B, Hh, T*H*W, d] of shape->dtype, raster order (device, read only)
+ * u  : [B, T*H*W] fp32 (device, written) */
+usv_status usv_merge_similarity(const void* k, const usv_shape* shape, const usv_grid* grid, float* u,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/* u      : [B, T*H*W] fp32 (device, read only); compared on canonical values
+ *          (-0 equals +0, NaN ranks lowest); the result is a pure function of u
+ * row_of : [B, T*H*W] int32 (device, written): the merged row token k reads back
+ * src_of : [B, N - r] int32 (device, written): the raster index of the token that
+ *          owns each merged row */
+usv_status usv_merge_plan(const float* u, const usv_shape* shape, const usv_grid* grid, int32_t* row_of,
+                          int32_t* src_of, void* stream);
+
+/* x   : [B, Hh, T*H*W, d] of shape->dtype, raster order (device, read only)
+ * out : [B, Hh, seq_len, d] of shape->dtype (device, written); means are taken in
+ *       fp32 and rounded once; rows seq_valid <= p < seq_len are written as zero */
+usv_status usv_merge_apply(const void* x, const usv_shape* shape, const usv_grid* grid,
+                           const int32_t* row_of, const int32_t* src_of, void* out, void* stream);
+
+/* y   : [B, Hh, seq_len, d] of shape->dtype (device, read only)
+ * out : [B, Hh, T*H*W, d] of shape->dtype (device, written): out[k] = y[row_of[k]]
+ *       (shape->dtype is the element type of THIS tensor, e.g. USV_F32 for an fp32
+ *       attention output) */
+usv_status usv_unmerge_apply(const void* y, const usv_shape* shape, const usv_grid* grid,
+                             const int32_t* row_of, void* out, void* stream);
 
 /* Static string for a status code. */
 const char* usv_status_string(int32_t status);

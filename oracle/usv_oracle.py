@@ -82,8 +82,8 @@ Readings taken where the paper is silent (also listed in the design notes):
     the only candidate destination of a source is the one of its own block, so j*(i) is that
     token and u_i their cosine similarity (a zero descriptor gives similarity 0).  The r
     selected sources are the first r in the order (u descending, raster index ascending);
-    the merged sequence lists the unmerged sources, then the destinations, each in ascending
-    raster index.
+    on canonical values as in the top-k selection (-0 equals +0, NaN ranks lowest); the merged
+    sequence lists the unmerged sources, then the destinations, each in ascending raster index.
   * padded keys (token >= seq_valid) are masked; padded query rows output 0 and
     lse = -inf; a query cube with an empty list outputs 0.
 """
@@ -406,7 +406,9 @@ def merge_plan(u, grid, mblock, r):
     row_of = np.empty((B, N), dtype=np.int32)
     src_of = np.empty((B, N - r), dtype=np.int32)
     for b in range(B):
-        order = sorted(sources.tolist(), key=lambda i: (-float(u[b, i]), i))
+        # u descending, then index ascending, on canonical values: -0 equals +0 (they compare equal as
+        # floats) and NaN ranks after every number, as in the top-k selection
+        order = sorted(sources.tolist(), key=lambda i: (bool(np.isnan(u[b, i])), 0.0 if np.isnan(u[b, i]) else -float(u[b, i]), i))
         merged = set(order[:r])
         unmerged = [i for i in sources.tolist() if i not in merged]
         seq = unmerged + np.nonzero(is_dst)[0].tolist()

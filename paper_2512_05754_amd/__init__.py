@@ -8,6 +8,10 @@ _BINDING_NAMES = (
     "block_scores",
     "select_topk",
     "block_sparse_attn",
+    "merge_similarity",
+    "merge_plan",
+    "merge_apply",
+    "unmerge_apply",
     "attn_entropy",
     "entropy_allocate",
     "coarse_attn",

@@ -27,6 +27,11 @@ EXPORTED_SYMBOLS = (
     "usv_attn_entropy",
     "usv_entropy_allocate",
     "usv_block_sparse_attn",
+    "usv_merge_workspace_bytes",
+    "usv_merge_similarity",
+    "usv_merge_plan",
+    "usv_merge_apply",
+    "usv_unmerge_apply",
     "usv_cube_token_order",
     "usv_cube_gather",
     "usv_cube_scatter",
@@ -100,6 +105,11 @@ def lib() -> ctypes.CDLL:
     L.usv_cube_token_order.restype, L.usv_cube_token_order.argtypes = i32, [gp, vp]
     L.usv_cube_gather.restype, L.usv_cube_gather.argtypes = i32, [vp, stp, sp, gp, vp, vp]
     L.usv_cube_scatter.restype, L.usv_cube_scatter.argtypes = i32, [vp, sp, gp, vp, stp, vp]
+    L.usv_merge_workspace_bytes.restype, L.usv_merge_workspace_bytes.argtypes = sz, [sp, gp]
+    L.usv_merge_similarity.restype, L.usv_merge_similarity.argtypes = i32, [vp, sp, gp, vp, vp, sz, vp]
+    L.usv_merge_plan.restype, L.usv_merge_plan.argtypes = i32, [vp, sp, gp, vp, vp, vp]
+    L.usv_merge_apply.restype, L.usv_merge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp, vp]
+    L.usv_unmerge_apply.restype, L.usv_unmerge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp]
     L.usv_status_string.restype, L.usv_status_string.argtypes = ctypes.c_char_p, [i32]
     L.usv_last_error.restype, L.usv_last_error.argtypes = ctypes.c_char_p, []
     _lib = L
@@ -354,3 +364,65 @@ def entropy_allocate(entropy, rho_bar, gamma=1.0, rho_min=0.0, rho_max=1.0):
     _check(lib().usv_entropy_allocate(h.ctypes.data_as(ctypes.c_void_p), int(h.size), float(rho_bar), float(gamma),
                                       float(rho_min), float(rho_max), rho.ctypes.data_as(ctypes.c_void_p)))
     return rho
+
+
+def _merge_shape(B, Hh, d, dtype, grid, r, seq_len=None) -> UsvShape:
+    """Shape of the MERGED tensors: seq_valid = T*H*W - r rows, padded to seq_len (default: next multiple of 64)."""
+    n_valid = int(grid[0]) * int(grid[1]) * int(grid[2]) - int(r)
+    if seq_len is None:
+        seq_len = -(-n_valid // BLOCK) * BLOCK
+    return UsvShape(B, Hh, int(seq_len), n_valid, d, BLOCK, USV_BF16 if dtype == torch.bfloat16 else USV_F32)
+
+
+def merge_similarity(k, grid, mblock, out=None, workspace=None):
+    """usv_merge_similarity: K [B, Hh, T*H*W, d] in raster order -> u [B, T*H*W] fp32 (-inf at destinations)."""
+    B, Hh, N, d = k.shape
+    sh = _merge_shape(B, Hh, d, k.dtype, grid, 0)
+    g = _grid(grid, mblock)
+    if out is None:
+        out = torch.empty((B, N), dtype=torch.float32, device=k.device)
+    need = int(lib().usv_merge_workspace_bytes(ctypes.byref(sh), ctypes.byref(g)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=k.device)
+    _check(lib().usv_merge_similarity(_dev(k, "k"), ctypes.byref(sh), ctypes.byref(g), _dev(out, "u", torch.float32),
+                                      _dev(workspace, "workspace"), workspace.numel(), _stream()))
+    return out
+
+
+def merge_plan(u, grid, mblock, r, row_of=None, src_of=None):
+    """usv_merge_plan: u [B, T*H*W] fp32 -> row_of [B, T*H*W], src_of [B, T*H*W - r] (int32)."""
+    B, N = u.shape
+    sh = _merge_shape(B, 1, 64, torch.float32, grid, r)
+    g = _grid(grid, mblock)
+    if row_of is None:
+        row_of = torch.empty((B, N), dtype=torch.int32, device=u.device)
+    if src_of is None:
+        src_of = torch.empty((B, max(N - int(r), 1)), dtype=torch.int32, device=u.device)[:, : N - int(r)]
+    _check(lib().usv_merge_plan(_dev(u, "u", torch.float32), ctypes.byref(sh), ctypes.byref(g),
+                                _dev(row_of, "row_of", torch.int32), _dev(src_of, "src_of", torch.int32), _stream()))
+    return row_of, src_of
+
+
+def merge_apply(x, grid, mblock, row_of, src_of, seq_len=None, out=None):
+    """usv_merge_apply: raster x [B, Hh, T*H*W, d] -> merged [B, Hh, seq_len, d] (padding rows zero)."""
+    B, Hh, N, d = x.shape
+    sh = _merge_shape(B, Hh, d, x.dtype, grid, N - src_of.shape[1], seq_len)
+    g = _grid(grid, mblock)
+    if out is None:
+        out = torch.empty((B, Hh, sh.seq_len, d), dtype=x.dtype, device=x.device)
+    _check(lib().usv_merge_apply(_dev(x, "x"), ctypes.byref(sh), ctypes.byref(g), _dev(row_of, "row_of", torch.int32),
+                                 _dev(src_of, "src_of", torch.int32), _dev(out, "out"), _stream()))
+    return out
+
+
+def unmerge_apply(y, grid, mblock, row_of, n_merged_rows, out=None):
+    """usv_unmerge_apply: merged y [B, Hh, seq_len, d] (n_merged_rows real rows) -> raster [B, Hh, T*H*W, d]."""
+    B, Hh, Np, d = y.shape
+    N = row_of.shape[1]
+    sh = _merge_shape(B, Hh, d, y.dtype, grid, N - int(n_merged_rows), Np)
+    g = _grid(grid, mblock)
+    if out is None:
+        out = torch.empty((B, Hh, N, d), dtype=y.dtype, device=y.device)
+    _check(lib().usv_unmerge_apply(_dev(y, "y"), ctypes.byref(sh), ctypes.byref(g), _dev(row_of, "row_of", torch.int32),
+                                   _dev(out, "out"), _stream()))
+    return out

@@ -11,7 +11,8 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libusv.so")
 SOURCES = ("usv_api.hip", "usv_scores.hip", "usv_topk.hip", "usv_attn_f32.hip", "usv_attn_bf16.hip",
-           "usv_reorder.hip", "usv_coarse.hip", "usv_entropy.hip")
+           "usv_reorder.hip", "usv_coarse.hip", "usv_entropy.hip",
+           "usv_merge.hip")
 
 
 def hipcc() -> str:

@@ -101,6 +101,28 @@ usv_status check_strides(const usv_strides* st, const usv::Dims& s, long long ou
   return USV_OK;
 }
 
+// Token merging: `sh` describes the merged tensors, `g` the raster grid and the merge block.
+// Fills Dims, MergeGrid, the raster token count N and r = N - seq_valid (sources to merge).
+usv_status check_merge(const usv_shape* sh, const usv_grid* g, usv::Dims* s, usv::MergeGrid* mg, int* N, int* r) {
+  const usv_status st = check_shape(sh, true, s);
+  if (st != USV_OK) return st;
+  if (!g) return fail(USV_ERR_INVALID_ARG, "grid is NULL");
+  if (g->T < 1 || g->H < 1 || g->W < 1) return fail(USV_ERR_INVALID_ARG, "grid extents must be >= 1");
+  if (g->ct < 1 || g->ch < 1 || g->cw < 1) return fail(USV_ERR_INVALID_ARG, "merge block extents must be >= 1");
+  const long long tokens = (long long)g->T * g->H * g->W;
+  if (tokens > (long long)USV_MAX_BLOCKS * usv::kBlock)
+    return fail(USV_ERR_UNSUPPORTED, "grid holds more than %d tokens", USV_MAX_BLOCKS * usv::kBlock);
+  *mg = usv::MergeGrid{g->T, g->H, g->W, g->ct, g->ch, g->cw, (g->T + g->ct - 1) / g->ct, (g->H + g->ch - 1) / g->ch,
+                       (g->W + g->cw - 1) / g->cw};
+  const long long n_dst = (long long)mg->nT * mg->nH * mg->nW;
+  if (sh->seq_valid > tokens || sh->seq_valid < n_dst)
+    return fail(USV_ERR_INVALID_ARG, "seq_valid (%d merged rows) must lie between the %lld destinations and the %lld tokens of the grid",
+                sh->seq_valid, n_dst, tokens);
+  *N = (int)tokens;
+  *r = (int)(tokens - sh->seq_valid);
+  return USV_OK;
+}
+
 #define USV_TRY(expr)                    \
   do {                                   \
     const usv_status st__ = (expr);      \
@@ -263,6 +285,69 @@ usv_status usv_entropy_allocate(const float* entropy, int32_t layers, float rho_
   }
   g_err[0] = '\0';
   return USV_OK;
+}
+
+size_t usv_merge_workspace_bytes(const usv_shape* shape, const usv_grid* grid) {
+  usv::Dims s;
+  usv::MergeGrid g;
+  int N, r;
+  if (check_merge(shape, grid, &s, &g, &N, &r) != USV_OK) return 0;
+  return (size_t)s.B * N * (s.d + 1) * sizeof(float);
+}
+
+usv_status usv_merge_similarity(const void* k, const usv_shape* shape, const usv_grid* grid, float* u, void* ws,
+                                size_t ws_bytes, void* stream) {
+  usv::Dims s;
+  usv::MergeGrid g;
+  int N, r;
+  USV_TRY(check_merge(shape, grid, &s, &g, &N, &r));
+  USV_TRY(check_ptr(k, "k"));
+  USV_TRY(check_ptr(u, "u"));
+  const size_t need = usv_merge_workspace_bytes(shape, grid);
+  if (!ws || !aligned16(ws) || ws_bytes < need)
+    return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
+  return hip_result(usv::launch_merge_similarity(k, s, g, N, u, static_cast<float*>(ws), static_cast<hipStream_t>(stream)),
+                    "usv_merge_similarity launch");
+}
+
+usv_status usv_merge_plan(const float* u, const usv_shape* shape, const usv_grid* grid, int32_t* row_of,
+                          int32_t* src_of, void* stream) {
+  usv::Dims s;
+  usv::MergeGrid g;
+  int N, r;
+  USV_TRY(check_merge(shape, grid, &s, &g, &N, &r));
+  USV_TRY(check_ptr(u, "u"));
+  USV_TRY(check_ptr(row_of, "row_of"));
+  USV_TRY(check_ptr(src_of, "src_of"));
+  return hip_result(usv::launch_merge_select(u, g, s.B, N, r, row_of, src_of, static_cast<hipStream_t>(stream)),
+                    "usv_merge_plan launch");
+}
+
+usv_status usv_merge_apply(const void* x, const usv_shape* shape, const usv_grid* grid, const int32_t* row_of,
+                           const int32_t* src_of, void* out, void* stream) {
+  usv::Dims s;
+  usv::MergeGrid g;
+  int N, r;
+  USV_TRY(check_merge(shape, grid, &s, &g, &N, &r));
+  USV_TRY(check_ptr(x, "x"));
+  USV_TRY(check_ptr(row_of, "row_of"));
+  USV_TRY(check_ptr(src_of, "src_of"));
+  USV_TRY(check_ptr(out, "out"));
+  return hip_result(usv::launch_merge_rows(x, s, g, N, row_of, src_of, out, static_cast<hipStream_t>(stream)),
+                    "usv_merge_apply launch");
+}
+
+usv_status usv_unmerge_apply(const void* y, const usv_shape* shape, const usv_grid* grid, const int32_t* row_of,
+                             void* out, void* stream) {
+  usv::Dims s;
+  usv::MergeGrid g;
+  int N, r;
+  USV_TRY(check_merge(shape, grid, &s, &g, &N, &r));
+  USV_TRY(check_ptr(y, "y"));
+  USV_TRY(check_ptr(row_of, "row_of"));
+  USV_TRY(check_ptr(out, "out"));
+  return hip_result(usv::launch_unmerge_rows(y, s, N, row_of, out, static_cast<hipStream_t>(stream)),
+                    "usv_unmerge_apply launch");
 }
 
 usv_status usv_cube_token_order(const usv_grid* grid, int32_t* order) {

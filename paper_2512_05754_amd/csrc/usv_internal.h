@@ -27,6 +27,11 @@ struct CubeGrid {
 // Cube-major position of raster token (t, h, w): the one definition the kernel and the host helper share.
 __host__ __device__ long long cube_position(const CubeGrid& g, int t, int h, int w);
 
+// Token grid T x H x W tiled by st x sh x sw merge blocks (cut at the boundary); nT, nH, nW = blocks along each axis.
+struct MergeGrid {
+  int T, H, W, st, sh, sw, nT, nH, nW;
+};
+
 // Workgroups are dealt round-robin to the 8 XCDs.  Map the hardware block id to a logical
 // work id so that each XCD walks one contiguous range of work items (consecutive heads and
 // query blocks share K/V in that XCD's L2).  `per_xcd` = ceil(total / 8); ids >= total idle.
@@ -54,5 +59,14 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const D
 // gather: raster -> cube-major (+ zeroed padding); else cube-major -> raster.  Strides of the raster tensor in BYTES.
 hipError_t launch_cube_move(bool gather, const void* src, void* dst, const CubeGrid& g, const Dims& s, long long sb,
                             long long sh, long long st, hipStream_t stream);
+
+// Token merging.  `s` describes the MERGED tensors (s.N padded rows, s.Nv = N - r valid rows); N = raster tokens.
+hipError_t launch_merge_similarity(const void* k, const Dims& s, const MergeGrid& g, int N, float* u, float* ws,
+                                   hipStream_t st);
+hipError_t launch_merge_select(const float* u, const MergeGrid& g, int B, int N, int r, int32_t* row_of, int32_t* src_of,
+                               hipStream_t st);
+hipError_t launch_merge_rows(const void* x, const Dims& s, const MergeGrid& g, int N, const int32_t* row_of,
+                             const int32_t* src_of, void* out, hipStream_t st);
+hipError_t launch_unmerge_rows(const void* y, const Dims& s, int N, const int32_t* row_of, void* out, hipStream_t st);
 
 }  // namespace usv

@@ -1,0 +1,409 @@
+// Token merging (paper Section 3.3): 3-D bipartite partition of the raster token grid into merge
+// blocks with one destination each, head-averaged key descriptors, cosine similarity of every source
+// to its block's destination, the r most similar sources merged into their destinations by mean
+// aggregation, the merged sequence [unmerged sources || destinations], and the exact unmerge.
+//
+//   merge_descriptors  HBM bound: reads K once, m[b,i,:] = mean over heads (fp32) and |m|^2
+//   merge_similarity   u[b,i] = cos(m_i, m_dst(i)); -inf at destinations
+//   merge_select       one workgroup per batch element: radix search (4 bits per step) for the r-th
+//                      largest source key, then one ordered sweep that ranks ties by index and
+//                      assigns the rows of the merged sequence (ballot prefix counts, no atomics)
+//   merge_rows         merged features: a destination row is the mean of itself and its merged
+//                      sources (found by scanning its own block), other rows are copies
+//   unmerge_rows       gather: token k reads row row_of[k]
+#include "usv_internal.h"
+
+namespace usv {
+namespace {
+
+// raster index -> coordinates, destination of the block, rank of a destination among destinations
+struct Tok {
+  int t, h, w;
+};
+__device__ __forceinline__ Tok coords(const MergeGrid& g, int i) {
+  const int hw = g.H * g.W;
+  Tok c;
+  c.t = i / hw;
+  const int rem = i - c.t * hw;
+  c.h = rem / g.W;
+  c.w = rem - c.h * g.W;
+  return c;
+}
+__device__ __forceinline__ int dst_index(const MergeGrid& g, const Tok& c) {
+  return ((c.t - c.t % g.st) * g.H + (c.h - c.h % g.sh)) * g.W + (c.w - c.w % g.sw);
+}
+__device__ __forceinline__ bool is_dst(const MergeGrid& g, const Tok& c) {
+  return c.t % g.st == 0 && c.h % g.sh == 0 && c.w % g.sw == 0;
+}
+// destinations in ascending raster order = ascending (t/st, h/sh, w/sw)
+__device__ __forceinline__ int dst_rank(const MergeGrid& g, const Tok& c) {
+  return ((c.t / g.st) * g.nH + c.h / g.sh) * g.nW + c.w / g.sw;
+}
+
+template <typename T>
+struct Row;  // 16 bytes of a row <-> floats
+template <>
+struct Row<float> {
+  static constexpr int kElems = 4;
+  __device__ static void load(const float* p, float (&o)[4]) {
+    const float4 v = *reinterpret_cast<const float4*>(p);
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  }
+  __device__ static void store(float* p, const float (&o)[4]) { *reinterpret_cast<float4*>(p) = make_float4(o[0], o[1], o[2], o[3]); }
+};
+template <>
+struct Row<uint16_t> {
+  static constexpr int kElems = 8;
+  __device__ static void load(const uint16_t* p, float (&o)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = __uint_as_float(w[i] << 16);
+      o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  __device__ static void store(uint16_t* p, const float (&o)[8]) {
+    typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (__bf16)o[i];  // round to nearest even
+    *reinterpret_cast<bf16x8*>(p) = v;
+  }
+};
+
+// grid = (ceil(N / rows_per_wg), B); a group of LPR lanes owns one token.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_descriptors(const T* __restrict__ k, float* __restrict__ m,
+                                                         float* __restrict__ norm2, int N, int Hh) {
+  constexpr int VEC = Row<T>::kElems, LPR = D / VEC, RPW = 256 / LPR;
+  const int b = blockIdx.y, row = blockIdx.x * RPW + threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * VEC;
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  if (row < N) {
+    const T* src = k + ((long long)b * Hh * N + row) * D + c0;
+    const long long hs = (long long)N * D;
+    int h = 0;
+    for (; h + 4 <= Hh; h += 4) {  // four heads in flight
+      float x[4][VEC];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) Row<T>::load(src + (h + u) * hs, x[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += x[u][e];
+    }
+    for (; h < Hh; ++h) {
+      float x[VEC];
+      Row<T>::load(src + h * hs, x);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += x[e];
+    }
+  }
+  const float inv = 1.0f / (float)Hh;
+  float n2 = 0.f;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    acc[e] *= inv;
+    n2 = fmaf(acc[e], acc[e], n2);
+  }
+#pragma unroll
+  for (int o = LPR / 2; o >= 1; o >>= 1) n2 += __shfl_xor(n2, o);  // LPR <= 32 consecutive lanes of one wave
+  if (row < N) {
+    float* dst = m + ((long long)b * N + row) * D + c0;
+#pragma unroll
+    for (int e = 0; e < VEC; e += 4) *reinterpret_cast<float4*>(dst + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+    if (threadIdx.x % LPR == 0) norm2[(long long)b * N + row] = n2;
+  }
+}
+
+// grid = (ceil(N / (256 / (D/4))), B); D/4 lanes per token.
+template <int D>
+__global__ __launch_bounds__(256) void merge_similarity(const float* __restrict__ m, const float* __restrict__ norm2,
+                                                        float* __restrict__ u, MergeGrid g, int N) {
+  constexpr int LPR = D / 4, RPW = 256 / LPR;
+  const int b = blockIdx.y, i = blockIdx.x * RPW + threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * 4;
+  int j = 0;
+  bool dst = false;
+  float dot = 0.f;
+  if (i < N) {
+    const Tok c = coords(g, i);
+    dst = is_dst(g, c);
+    j = dst_index(g, c);
+    const float4 a = *reinterpret_cast<const float4*>(m + ((long long)b * N + i) * D + c0);
+    const float4 d = *reinterpret_cast<const float4*>(m + ((long long)b * N + j) * D + c0);
+    dot = fmaf(a.x, d.x, fmaf(a.y, d.y, fmaf(a.z, d.z, a.w * d.w)));
+  }
+#pragma unroll
+  for (int o = LPR / 2; o >= 1; o >>= 1) dot += __shfl_xor(dot, o);
+  if (i < N && threadIdx.x % LPR == 0) {
+    const float den = sqrtf(norm2[(long long)b * N + i]) * sqrtf(norm2[(long long)b * N + j]);
+    u[(long long)b * N + i] = dst ? -INFINITY : (den > 0.f ? dot / den : 0.f);
+  }
+}
+
+// Order-preserving key of a canonicalised fp32: -0 == +0, NaN below everything.
+__device__ __forceinline__ uint32_t order_key(float x) {
+  uint32_t b = __float_as_uint(x);
+  if ((b & 0x7fffffffu) > 0x7f800000u) return 0u;
+  if (b == 0x80000000u) b = 0u;
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+
+// Exclusive prefix of a 0/1 flag over the workgroup, in thread order; *total = number of set flags.
+// `wave_tot` is LDS scratch of kSelWaves ints.  Contains two barriers.
+__device__ __forceinline__ int block_rank(bool flag, int* wave_tot, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned long long bal = __ballot(flag);
+  if (lane == 0) wave_tot[wave] = __popcll(bal);
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int c = wave_tot[w];
+    before += w < wave ? c : 0;
+    all += c;
+  }
+  __syncthreads();
+  *total = all;
+  return before + __popcll(bal & ((1ull << lane) - 1ull));
+}
+
+// grid = B; 1024 threads.  r = number of sources to merge (0 <= r <= number of sources).
+__global__ __launch_bounds__(kSelThreads) void merge_select(const float* __restrict__ u, int32_t* __restrict__ row_of,
+                                                            int32_t* __restrict__ src_of, MergeGrid g, int N, int r) {
+  __shared__ int hist[kSelWaves][16];
+  __shared__ int wave_tot[kSelWaves];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_want;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* ub = u + (long long)b * N;
+  const int n_dst = g.nT * g.nH * g.nW;
+  const int n_unmerged = N - n_dst - r;
+
+  // ---- the r-th largest source key, 4 bits per step ------------------------------------------
+  uint32_t thr = 0xffffffffu;  // r == 0: nothing is above or at the threshold
+  int need_eq = 0;
+  if (r > 0) {
+    uint32_t prefix = 0u;
+    int want = r;  // rank (1 = largest) of the wanted key among the keys that share the prefix
+    for (int shift = 28; shift >= 0; shift -= 4) {
+      int cnt[16];
+#pragma unroll
+      for (int d = 0; d < 16; ++d) cnt[d] = 0;
+      for (int i = tid; i < N; i += kSelThreads) {
+        const Tok c = coords(g, i);
+        const uint32_t key = order_key(ub[i]);
+        const bool in = !is_dst(g, c) && (shift == 28 || (key >> (shift + 4)) == (prefix >> (shift + 4)));
+        const int dig = (key >> shift) & 15;
+#pragma unroll
+        for (int d = 0; d < 16; ++d) cnt[d] += (in && dig == d) ? 1 : 0;
+      }
+#pragma unroll
+      for (int d = 0; d < 16; ++d) {
+        int v = cnt[d];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+        if (lane == 0) hist[wave][d] = v;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int w = want;
+        int dsel = 0;
+        for (int d = 15; d >= 0; --d) {
+          int c = 0;
+          for (int q = 0; q < kSelWaves; ++q) c += hist[q][d];
+          if (w <= c) {
+            dsel = d;
+            break;
+          }
+          w -= c;
+        }
+        s_prefix = prefix | ((uint32_t)dsel << shift);
+        s_want = w;
+      }
+      __syncthreads();
+      prefix = s_prefix;
+      want = s_want;
+      __syncthreads();
+    }
+    thr = prefix;
+    need_eq = want;  // among the sources whose key equals thr, the first `want` by index are merged
+  }
+
+  // ---- one ordered sweep: ranks of ties, rows of the merged sequence ----------------------------
+  int eq_base = 0, un_base = 0;
+  for (int i0 = 0; i0 < N; i0 += kSelThreads) {  // uniform trip count: barriers inside
+    const int i = i0 + tid;
+    const bool live = i < N;
+    Tok c = {0, 0, 0};
+    uint32_t key = 0u;
+    bool dst = false;
+    if (live) {
+      c = coords(g, i);
+      dst = is_dst(g, c);
+      key = order_key(ub[i]);
+    }
+    const bool src = live && !dst;
+    const bool eq = src && key == thr;
+    int eq_tot, un_tot;
+    const int eq_rank = eq_base + block_rank(eq, wave_tot, &eq_tot);
+    const bool merged = src && (key > thr || (eq && eq_rank < need_eq));
+    const bool unmerged = src && !merged;
+    const int un_rank = un_base + block_rank(unmerged, wave_tot, &un_tot);
+    if (live) {
+      int row;
+      if (dst) {
+        row = n_unmerged + dst_rank(g, c);
+      } else if (unmerged) {
+        row = un_rank;
+      } else {
+        const Tok d = {c.t - c.t % g.st, c.h - c.h % g.sh, c.w - c.w % g.sw};
+        row = n_unmerged + dst_rank(g, d);
+      }
+      row_of[(long long)b * N + i] = row;
+      if (!merged) src_of[(long long)b * (N - r) + row] = i;
+    }
+    eq_base += eq_tot;
+    un_base += un_tot;
+  }
+}
+
+// grid = (ceil(Np / rows_per_wg), Hh, B): merged rows.  Nm = N - r valid merged rows.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_rows(const T* __restrict__ x, const int32_t* __restrict__ row_of,
+                                                  const int32_t* __restrict__ src_of, T* __restrict__ out, MergeGrid g,
+                                                  int N, int Nm, int Np, int Hh) {
+  constexpr int VEC = Row<T>::kElems, LPR = D / VEC, RPW = 256 / LPR;
+  const int b = blockIdx.z, h = blockIdx.y, p = blockIdx.x * RPW + threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * VEC;
+  if (p >= Np) return;
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  if (p < Nm) {
+    const int s = src_of[(long long)b * Nm + p];
+    const T* xb = x + ((long long)(b * Hh + h) * N) * D + c0;
+    const Tok c = coords(g, s);
+    Row<T>::load(xb + (long long)s * D, acc);
+    if (is_dst(g, c)) {
+      // the merged sources of this destination are the tokens of its block that read back from row p
+      const int32_t* ro = row_of + (long long)b * N;
+      const int et = min(g.st, g.T - c.t), eh = min(g.sh, g.H - c.h), ew = min(g.sw, g.W - c.w);
+      int count = 1;
+      for (int lt = 0; lt < et; ++lt)
+        for (int lh = 0; lh < eh; ++lh)
+          for (int lw = 0; lw < ew; ++lw) {
+            const int k = ((c.t + lt) * g.H + c.h + lh) * g.W + c.w + lw;
+            if (k != s && ro[k] == p) {
+              float v[VEC];
+              Row<T>::load(xb + (long long)k * D, v);
+#pragma unroll
+              for (int e = 0; e < VEC; ++e) acc[e] += v[e];
+              ++count;
+            }
+          }
+      if (count > 1) {
+        const float inv = 1.0f / (float)count;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] *= inv;
+      }
+    }
+  }
+  Row<T>::store(out + ((long long)(b * Hh + h) * Np + p) * D + c0, acc);
+}
+
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned chunk_t;  // 16 bytes
+
+// grid = (ceil(N / 64), B*Hh): 64 raster tokens per workgroup, <= 4 pieces of 16 bytes per lane.
+template <int CHUNKS>
+__global__ __launch_bounds__(CHUNKS >= 32 ? 512 : 256) void unmerge_rows(const unsigned char* __restrict__ y,
+                                                                         const int32_t* __restrict__ row_of,
+                                                                         unsigned char* __restrict__ out, int N, int Np,
+                                                                         int Hh) {
+  constexpr int kThreads = CHUNKS >= 32 ? 512 : 256;
+  constexpr int kRowBytes = CHUNKS * 16, PER_THREAD = kBlock * CHUNKS / kThreads;
+  __shared__ int row[kBlock];
+  const int tid = threadIdx.x, k0 = blockIdx.x * kBlock, bh = blockIdx.y, b = bh / Hh;
+  if (tid < kBlock) row[tid] = k0 + tid < N ? row_of[(long long)b * N + k0 + tid] : 0;
+  __syncthreads();
+  const unsigned char* src = y + (long long)bh * Np * kRowBytes;
+  unsigned char* dst = out + ((long long)bh * N + k0) * kRowBytes;
+  chunk_t val[PER_THREAD];
+#pragma unroll
+  for (int it = 0; it < PER_THREAD; ++it) {
+    const int c = it * kThreads + tid, rr = c / CHUNKS, ch = c - rr * CHUNKS;
+    val[it] = chunk_t{0u, 0u, 0u, 0u};
+    if (k0 + rr < N) val[it] = *reinterpret_cast<const chunk_t*>(src + (long long)row[rr] * kRowBytes + ch * 16);
+  }
+#pragma unroll
+  for (int it = 0; it < PER_THREAD; ++it) {
+    const int c = it * kThreads + tid, rr = c / CHUNKS, ch = c - rr * CHUNKS;
+    if (k0 + rr < N) *reinterpret_cast<chunk_t*>(dst + (long long)rr * kRowBytes + ch * 16) = val[it];
+  }
+}
+
+}  // namespace
+
+// ws: m [B, N, d] fp32, then |m|^2 [B, N] fp32
+hipError_t launch_merge_similarity(const void* k, const Dims& s, const MergeGrid& g, int N, float* u, float* ws,
+                                   hipStream_t st) {
+  float* m = ws;
+  float* n2 = ws + (long long)s.B * N * s.d;
+  const int vec = s.bf16 ? 8 : 4, rpw = 256 / (s.d / vec);
+  const dim3 grid_d((unsigned)((N + rpw - 1) / rpw), (unsigned)s.B);
+  if (s.bf16) {
+    if (s.d == 128) merge_descriptors<uint16_t, 128><<<grid_d, 256, 0, st>>>(static_cast<const uint16_t*>(k), m, n2, N, s.Hh);
+    else merge_descriptors<uint16_t, 64><<<grid_d, 256, 0, st>>>(static_cast<const uint16_t*>(k), m, n2, N, s.Hh);
+  } else {
+    if (s.d == 128) merge_descriptors<float, 128><<<grid_d, 256, 0, st>>>(static_cast<const float*>(k), m, n2, N, s.Hh);
+    else merge_descriptors<float, 64><<<grid_d, 256, 0, st>>>(static_cast<const float*>(k), m, n2, N, s.Hh);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int rpw2 = 256 / (s.d / 4);
+  const dim3 grid_s((unsigned)((N + rpw2 - 1) / rpw2), (unsigned)s.B);
+  if (s.d == 128) merge_similarity<128><<<grid_s, 256, 0, st>>>(m, n2, u, g, N);
+  else merge_similarity<64><<<grid_s, 256, 0, st>>>(m, n2, u, g, N);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_select(const float* u, const MergeGrid& g, int B, int N, int r, int32_t* row_of, int32_t* src_of,
+                               hipStream_t st) {
+  merge_select<<<(unsigned)B, kSelThreads, 0, st>>>(u, row_of, src_of, g, N, r);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_rows(const void* x, const Dims& s, const MergeGrid& g, int N, const int32_t* row_of,
+                             const int32_t* src_of, void* out, hipStream_t st) {
+  const int vec = s.bf16 ? 8 : 4, rpw = 256 / (s.d / vec);
+  const dim3 grid((unsigned)((s.N + rpw - 1) / rpw), (unsigned)s.Hh, (unsigned)s.B);
+#define USV_MERGE_ROWS(T, DD) \
+  merge_rows<T, DD><<<grid, 256, 0, st>>>(static_cast<const T*>(x), row_of, src_of, static_cast<T*>(out), g, N, s.Nv, s.N, s.Hh)
+  if (s.bf16) {
+    if (s.d == 128) USV_MERGE_ROWS(uint16_t, 128);
+    else USV_MERGE_ROWS(uint16_t, 64);
+  } else {
+    if (s.d == 128) USV_MERGE_ROWS(float, 128);
+    else USV_MERGE_ROWS(float, 64);
+  }
+#undef USV_MERGE_ROWS
+  return hipGetLastError();
+}
+
+hipError_t launch_unmerge_rows(const void* y, const Dims& s, int N, const int32_t* row_of, void* out, hipStream_t st) {
+  const int chunks = s.d * (s.bf16 ? 2 : 4) / 16;
+  const dim3 grid((unsigned)((N + kBlock - 1) / kBlock), (unsigned)s.bh());
+  auto Y = static_cast<const unsigned char*>(y);
+  auto O = static_cast<unsigned char*>(out);
+  if (chunks == 8) unmerge_rows<8><<<grid, 256, 0, st>>>(Y, row_of, O, N, s.N, s.Hh);
+  else if (chunks == 16) unmerge_rows<16><<<grid, 256, 0, st>>>(Y, row_of, O, N, s.N, s.Hh);
+  else if (chunks == 32) unmerge_rows<32><<<grid, 512, 0, st>>>(Y, row_of, O, N, s.N, s.Hh);
+  else return hipErrorInvalidValue;  // unreachable: d in {64, 128}, bf16 or fp32
+  return hipGetLastError();
+}
+
+}  // namespace usv

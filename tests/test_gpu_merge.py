@@ -1,0 +1,117 @@
+"""GPU parity of token merging (Section 3.3) against the oracle.
+
+The similarities are compared at the fp32 bound; the plan (which sources merge, where every token
+reads back) is compared bit-exactly, the oracle selecting from the SAME fp32 similarities the GPU
+produced; merged features at the fp32 bound (bf16 storage: one rounding); the unmerge is byte work."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as gu
+from oracle import usv_oracle as orc
+from paper_2512_05754_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # grid, merge block, B, Hh, d, dtype
+    ((4, 6, 8), (2, 2, 2), 2, 3, 64, "f32"),
+    ((5, 7, 9), (2, 2, 4), 1, 4, 128, "bf16"),     # cut blocks on every axis
+    ((3, 10, 13), (1, 2, 2), 2, 2, 128, "f32"),
+    ((2, 33, 70), (2, 4, 4), 1, 5, 64, "bf16"),    # 4620 tokens: several sweeps of the 1024-thread selection
+    ((6, 4, 4), (4, 4, 4), 1, 2, 128, "bf16"),     # the attention cube as the merge block
+]
+
+
+def make(rng, shape, dtype, smooth=None):
+    x = rng.standard_normal(shape).astype(np.float32)
+    if smooth is not None:
+        x = x + 2.0 * smooth
+    return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+
+
+def bf16_round_ok(got, ref):
+    return np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.maximum(1, np.abs(ref))
+
+
+@pytest.mark.parametrize("grid,mb,B,Hh,d,dtype", CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_merge_pipeline(usv, grid, mb, B, Hh, d, dtype):
+    rng = np.random.default_rng([61, *grid, d])
+    N = grid[0] * grid[1] * grid[2]
+    base = rng.standard_normal((B, 1, N, d)).astype(np.float32)  # shared by the heads: descriptors do not average out
+    K = make(rng, (B, Hh, N, d), dtype, base)
+    X = make(rng, (B, Hh, N, d), dtype)
+    Kf, Xf = synth.as_f32(K), synth.as_f32(X)
+    u = usv.merge_similarity(gu.up(K), grid, mb)
+    u_h = gu.down(u)
+    u_ref = orc.merge_similarity(Kf, grid, mb)
+    assert np.array_equal(np.isneginf(u_h), np.isneginf(u_ref))
+    gu.assert_f32_close(u_h, u_ref, "similarity")
+    n_src = int((~np.isneginf(u_ref[0])).sum())
+    for r in sorted({0, 1, n_src // 3, n_src // 2, n_src}):
+        row_of, src_of = usv.merge_plan(u, grid, mb, r)
+        rr, rs = orc.merge_plan(u_h, grid, mb, r)
+        np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
+        np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
+        Np = -(-(N - r) // 64) * 64 + 64
+        y = usv.merge_apply(gu.up(X), grid, mb, row_of, src_of, seq_len=Np)
+        y_ref = orc.merge_apply(Xf, rr, rs, Np)
+        y_h = gu.down(y)
+        assert not y_h[:, :, N - r:].any()
+        if dtype == "f32":
+            gu.assert_f32_close(y_h, y_ref, f"merge r={r}")
+        else:
+            ok = bf16_round_ok(y_h, y_ref)
+            assert ok.all(), f"merge r={r}: {(~ok).sum()} elements beyond one bf16 rounding"
+        z = usv.unmerge_apply(y, grid, mb, row_of, N - r)
+        z_ref = orc.unmerge_apply(y_h, rr)
+        np.testing.assert_array_equal(gu.down(z), z_ref)
+
+
+def test_merge_plan_ties_and_special_values(usv):
+    """Engineered similarities: many exact ties across the sweep boundary of the selection, signed zeros,
+    NaN (ranks lowest), several batch elements with different values."""
+    grid, mb = (3, 20, 40), (1, 2, 2)
+    N = 2400
+    rng = np.random.default_rng(7)
+    dst = orc.merge_partition(grid, mb)
+    u = np.round(rng.standard_normal((3, N)) * 2).astype(np.float32) / 4  # heavy ties
+    u[1, ::7] = -0.0
+    u[1, 3::11] = 0.0
+    u[2, 5::13] = np.nan
+    u[:, dst == np.arange(N)] = -np.inf
+    n_src = int((dst != np.arange(N)).sum())
+    for r in (1, 37, 1000, 1024, 1500, n_src - 1, n_src):
+        row_of, src_of = usv.merge_plan(gu.up(u), grid, mb, r)
+        rr, rs = orc.merge_plan(u, grid, mb, r)
+        np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
+        np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
+
+
+def test_merge_then_attention_then_unmerge(usv):
+    """Raster Q/K/V -> merge (half of the tokens) -> three-stage hot path on the merged sequence -> unmerge,
+    against the oracle doing the same with the GPU's own similarities and scores."""
+    grid, mb = (4, 8, 12), (2, 2, 2)
+    B, Hh, d, N = 1, 2, 128, 384
+    rng = np.random.default_rng(71)
+    base = rng.standard_normal((B, 1, N, d)).astype(np.float32)
+    Q, K, V = (make(rng, (B, Hh, N, d), "bf16", base) for _ in range(3))
+    r = N // 2 - 5  # 197 merged rows: a ragged tail inside the last 64-row block
+    u = usv.merge_similarity(gu.up(K), grid, mb)
+    row_of, src_of = usv.merge_plan(u, grid, mb, r)
+    q, k, v = (usv.merge_apply(gu.up(x), grid, mb, row_of, src_of) for x in (Q, K, V))
+    Nm = N - r
+    S = usv.block_scores(q, k, seq_valid=Nm)
+    idx, cnt = usv.select_topk(S, k=2, seq_valid=Nm)
+    o = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=Nm, out_dtype=torch.float32)
+    out = gu.down(usv.unmerge_apply(o, grid, mb, row_of, Nm))
+    # oracle: same plan from the same u; merged tensors as the GPU stored them (bf16), then fp64 throughout
+    rr, rs = orc.merge_plan(gu.down(u), grid, mb, r)
+    np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
+    qm, km, vm = gu.down(q).astype(np.float64), gu.down(k).astype(np.float64), gu.down(v).astype(np.float64)
+    for got, raw in ((qm, Q), (km, K), (vm, V)):
+        assert bf16_round_ok(got, orc.merge_apply(synth.as_f32(raw), rr, rs, q.shape[2])).all()
+    ridx, rcnt = orc.select_topk(gu.down(S), 2, Nm)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
+    ref = orc.unmerge_apply(orc.block_sparse_attn(qm, km, vm, ridx, rcnt, Nm)[0], rr)
+    gu.assert_attn_close(out, ref, "bf16", False, "merged pipeline")

@@ -630,3 +630,13 @@ def test_merge_similarity_definition():
             assert u[0, i] == 0.0
         else:
             assert abs(u[0, i] - float(mi @ mj) / math.sqrt(float(mi @ mi) * float(mj @ mj))) < 1e-12
+
+
+def test_merge_plan_special_values():
+    """Signed zeros tie (lower index first) and NaN ranks after every number, also after -1."""
+    grid, mb = (1, 1, 8), (1, 1, 8)  # one block: destination 0, sources 1..7
+    u = np.array([[-np.inf, 0.0, np.nan, -0.0, 0.5, -1.0, np.nan, 0.0]], dtype=np.float32)
+    # order of the sources: 4 (0.5), then the zeros 1, 3, 7 by index, then 5 (-1), then the NaNs 2, 6
+    for r, merged in [(1, {4}), (2, {4, 1}), (3, {4, 1, 3}), (4, {4, 1, 3, 7}), (5, {4, 1, 3, 7, 5}), (6, {4, 1, 3, 7, 5, 2})]:
+        row_of, src_of = orc.merge_plan(u, grid, mb, r)
+        assert set(range(1, 8)) - set(src_of[0].tolist()) == merged
