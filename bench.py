@@ -41,11 +41,12 @@ def parse():
                     help="also run one plain 256 MiB device copy (untimed) so that a rocprofv3 --pmc run of this "
                          "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
-    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch"],
+    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch", "merge"],
                     help="attention: the three-stage hot path (the headline metric); reorder: the raster <-> "
                          "cube-major token reorder either side of it (gather Q, K, V + scatter O); two_branch: the "
                          "hot path with the local cube forced into every list, plus the cube-level branch and the "
-                         "gated fusion of the two outputs")
+                         "gated fusion of the two outputs; merge: token merging (similarity, plan, merge Q/K/V, "
+                         "unmerge O) with half of the tokens merged")
     ap.add_argument("--no-mfma-peak", action="store_true",
                     help="skip the MFMA-only peak probe (paper_2512_05754_amd/tools/mfma_peak, ~1 s)")
     return ap.parse_args()
@@ -205,6 +206,104 @@ def reorder_main(args):
     print(json.dumps(result))
 
 
+def merge_main(args):
+    """Times token merging at the workload's latent grid with 2x2x2 merge blocks and r = N/2 (HBM roofline)."""
+    import numpy as np
+    import torch
+
+    import paper_2512_05754_amd as usv
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = pick_workload(args.workload)
+    if w.name not in GRIDS:
+        print(f"bench.py: --path merge needs a workload with a latent grid ({sorted(GRIDS)})", file=sys.stderr)
+        sys.exit(2)
+    grid, mb = GRIDS[w.name], (2, 2, 2)
+    B, Hh, N, d = w.batch, w.heads, w.seq_valid, w.head_dim
+    r = N // 2
+    Nm = N - r
+    Np = -(-Nm // 64) * 64
+    gen = torch.Generator(device=dev).manual_seed(w.seed)
+    base = torch.randn((B, 1, N, d), device=dev, generator=gen)
+    q, k, v = ((torch.randn((B, Hh, N, d), device=dev, generator=gen) + 2 * base).to(torch.bfloat16) for _ in range(3))
+    u = torch.empty((B, N), dtype=torch.float32, device=dev)
+    ws = torch.empty(B * N * (d + 1) * 4, dtype=torch.uint8, device=dev)
+    row_of = torch.empty((B, N), dtype=torch.int32, device=dev)
+    src_of = torch.empty((B, Nm), dtype=torch.int32, device=dev)
+    merged = [torch.empty((B, Hh, Np, d), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+    o_merged = torch.randn((B, Hh, Np, d), device=dev, generator=gen)  # stands for the fp32 attention output
+    o_raster = torch.empty((B, Hh, N, d), dtype=torch.float32, device=dev)
+    names = ["merge_similarity", "merge_plan", "merge_apply_x3", "unmerge_apply"]
+
+    def step(events=None):
+        rec = (lambda i: events[i].record()) if events is not None else (lambda i: None)
+        rec(0)
+        usv.merge_similarity(k, grid, mb, out=u, workspace=ws)
+        rec(1)
+        usv.merge_plan(u, grid, mb, r, row_of=row_of, src_of=src_of)
+        rec(2)
+        for x, y in zip((q, k, v), merged):
+            usv.merge_apply(x, grid, mb, row_of, src_of, seq_len=Np, out=y)
+        rec(3)
+        usv.unmerge_apply(o_merged, grid, mb, row_of, Nm, out=o_raster)
+        rec(4)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    st_ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in evs]).mean(axis=0)
+    rows = B * Hh
+    bytes_sim = rows * N * d * 2 + B * N * (d + 1) * 4 * 2 + B * N * 4       # K once; descriptors written and read
+    bytes_plan = B * N * 4 * 2 + B * (N + Nm) * 4                             # u read by search and sweep; row_of, src_of
+    bytes_apply = rows * (N + Np) * d * 2                                     # per tensor: every raster row once, merged rows
+    bytes_unmerge = rows * (Nm + N) * d * 4
+    total = bytes_sim + bytes_plan + 3 * bytes_apply + bytes_unmerge
+    apply_ms = float(st_ms[2]) / 3
+    result = {
+        "metric": "GB/s of token merging (similarity + plan + merge Q, K, V + unmerge O), algorithmic bytes",
+        "value": total / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "path": "merge", "grid": list(grid), "merge_block": list(mb), "batch": B, "heads": Hh,
+                   "head_dim": d, "tokens": N, "merged_sources": r, "merged_rows": Nm, "bytes_per_step": total,
+                   "step": "usv_merge_similarity + usv_merge_plan + 3 x usv_merge_apply (bf16) + usv_unmerge_apply (fp32)"},
+        "stages_ms": {n: float(t) for n, t in zip(names, st_ms)},
+        "stage_hbm_gbs": {"merge_similarity": bytes_sim / (st_ms[0] * 1e-3) / 1e9, "merge_plan": bytes_plan / (st_ms[1] * 1e-3) / 1e9,
+                          "merge_apply": bytes_apply / (apply_ms * 1e-3) / 1e9, "unmerge_apply": bytes_unmerge / (st_ms[3] * 1e-3) / 1e9},
+        "roofline": {"kernel": "usv_merge_apply (merge_rows<bf16, 128>)", "bound": "hbm",
+                     "achieved": bytes_apply / (apply_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": bytes_apply / (apply_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": measured_traffic("merge:" + w.name, "apply_hbm_bytes_per_launch"), "avg_launch_ms": apply_ms},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import usv_oracle as orc
+
+        hs = min(2, Hh)
+        kh = k[:, :hs].float().cpu().numpy()
+        t0 = time.perf_counter()
+        uo = orc.merge_similarity(kh, grid, mb).astype(np.float32)
+        rr, rs = orc.merge_plan(uo, grid, mb, r)
+        ym = orc.merge_apply(kh, rr, rs, Np)
+        orc.unmerge_apply(ym, rr)
+        dt = time.perf_counter() - t0
+        sample = bytes_sim * hs / Hh + bytes_plan + bytes_apply * hs / Hh + bytes_unmerge * hs / Hh
+        result["cpu_baseline"] = {"value": sample / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"{hs} of {Hh} heads: similarity, plan, one merge, one unmerge (numpy / python loops), {dt:.2f} s"}
+    print(json.dumps(result))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -212,6 +311,8 @@ def main():
         sys.exit(2)
     if args.path == "reorder":
         return reorder_main(args)
+    if args.path == "merge":
+        return merge_main(args)
 
     peak_probe = None if args.no_mfma_peak else mfma_only_peak()
 

@@ -173,7 +173,8 @@ __device__ __forceinline__ int block_rank(bool flag, int* wave_tot, int* total) 
   return before + __popcll(bal & ((1ull << lane) - 1ull));
 }
 
-// grid = B; 1024 threads.  r = number of sources to merge (0 <= r <= number of sources).
+// grid = B; 1024 threads.  r = number of sources to merge (0 <= r <= number of sources).  General
+// version: keys are re-read from memory in every step (used when they do not fit the registers).
 __global__ __launch_bounds__(kSelThreads) void merge_select(const float* __restrict__ u, int32_t* __restrict__ row_of,
                                                             int32_t* __restrict__ src_of, MergeGrid g, int N, int r) {
   __shared__ int hist[kSelWaves][16];
@@ -270,6 +271,145 @@ __global__ __launch_bounds__(kSelThreads) void merge_select(const float* __restr
     }
     eq_base += eq_tot;
     un_base += un_tot;
+  }
+}
+
+// Exclusive prefix of an integer over the workgroup, in thread order; *total = sum.  Two barriers.
+__device__ __forceinline__ int block_exclusive(int v, int* wave_tot, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int c = wave_tot[w];
+    before += w < wave ? c : 0;
+    all += c;
+  }
+  __syncthreads();
+  *total = all;
+  return before + inc - v;
+}
+
+// Walks consecutive raster tokens while keeping each coordinate's position inside its merge block
+// (tm, hm, wm) and its block index (tq, hq, wq) by increments: no division after the first token.
+struct Walk {
+  int t, h, w, tm, hm, wm, tq, hq, wq;
+};
+__device__ __forceinline__ Walk walk_from(const MergeGrid& g, int i) {
+  const Tok c = coords(g, i);
+  Walk k;
+  k.t = c.t; k.h = c.h; k.w = c.w;
+  k.tq = c.t / g.st; k.tm = c.t - k.tq * g.st;
+  k.hq = c.h / g.sh; k.hm = c.h - k.hq * g.sh;
+  k.wq = c.w / g.sw; k.wm = c.w - k.wq * g.sw;
+  return k;
+}
+__device__ __forceinline__ void walk_next(const MergeGrid& g, Walk& k) {
+  ++k.w;
+  if (++k.wm == g.sw) k.wm = 0, ++k.wq;
+  if (k.w == g.W) {
+    k.w = 0; k.wm = 0; k.wq = 0;
+    ++k.h;
+    if (++k.hm == g.sh) k.hm = 0, ++k.hq;
+    if (k.h == g.H) {
+      k.h = 0; k.hm = 0; k.hq = 0;
+      ++k.t;
+      if (++k.tm == g.st) k.tm = 0, ++k.tq;
+    }
+  }
+}
+
+// The same selection for N <= 1024 * KPT with every key held in registers: thread t owns the KPT
+// consecutive tokens [t * KPT, t * KPT + KPT), so the search never re-reads memory and the ordered
+// sweep needs two workgroup scans in all.  Keys: 0 = not a source (destination or past the end),
+// sources >= 1 (a NaN similarity, the lowest rank, maps to 1; every number maps above 0x007fffff).
+// The r-th largest key is found bit by bit from the top (a compare and a wave-wide count per key and
+// bit); r <= number of sources keeps the key-0 entries out of the result.
+template <int KPT>
+__global__ __launch_bounds__(kSelThreads) void merge_select_reg(const float* __restrict__ u, int32_t* __restrict__ row_of,
+                                                                int32_t* __restrict__ src_of, MergeGrid g, int N, int r) {
+  __shared__ int wave_cnt[2][kSelWaves];
+  __shared__ int wave_tot[kSelWaves];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* ub = u + (long long)b * N;
+  const int n_dst = g.nT * g.nH * g.nW;
+  const int n_unmerged = N - n_dst - r;
+  const int first = tid * KPT;
+
+  uint32_t key[KPT];
+  {
+    Walk c = walk_from(g, first < N ? first : 0);
+#pragma unroll
+    for (int n = 0; n < KPT; ++n) {
+      const float x = first + n < N ? ub[first + n] : 0.f;
+      const uint32_t k = order_key(x);
+      key[n] = (first + n < N && (c.tm | c.hm | c.wm) != 0) ? (k ? k : 1u) : 0u;
+      walk_next(g, c);
+    }
+  }
+
+  // count of keys >= cand over the workgroup; `buf` alternates so that one barrier per call is enough
+  auto count_ge = [&](uint32_t cand, int buf) {
+    int c = 0;
+#pragma unroll
+    for (int n = 0; n < KPT; ++n) c += __popcll(__ballot(key[n] >= cand));
+    if (lane == 0) wave_cnt[buf][wave] = c;
+    __syncthreads();
+    int all = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) all += wave_cnt[buf][w];
+    return all;
+  };
+
+  uint32_t thr = 0xffffffffu;
+  int need_eq = 0;
+  if (r > 0) {  // uniform
+    thr = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = thr | (1u << bit);
+      if (count_ge(cand, bit & 1) >= r) thr = cand;
+    }
+    // thr is the r-th largest key; cand = thr + 1 counts the keys above it (thr < 0xffffffff: no key is)
+    need_eq = r - count_ge(thr + 1u, 0);
+    __syncthreads();
+  }
+
+  int eq_local = 0;
+#pragma unroll
+  for (int n = 0; n < KPT; ++n) eq_local += key[n] == thr ? 1 : 0;
+  int tot;
+  int eq_rank = block_exclusive(eq_local, wave_tot, &tot);
+  int un_local = 0;
+  uint32_t merged_lo = 0u, merged_mid = 0u, merged_hi = 0u;  // bit n: token first + n is merged (KPT <= 96)
+  static_assert(KPT <= 96, "three 32-bit masks");
+#pragma unroll
+  for (int n = 0; n < KPT; ++n) {
+    const bool eq = key[n] == thr;
+    const bool merged = key[n] != 0u && (key[n] > thr || (eq && eq_rank < need_eq));
+    eq_rank += eq ? 1 : 0;
+    un_local += (key[n] != 0u && !merged) ? 1 : 0;
+    if (merged) (n < 32 ? merged_lo : n < 64 ? merged_mid : merged_hi) |= 1u << (n & 31);
+  }
+  int un_rank = block_exclusive(un_local, wave_tot, &tot);
+  Walk c = walk_from(g, first < N ? first : 0);
+#pragma unroll
+  for (int n = 0; n < KPT; ++n) {
+    const int i = first + n;
+    if (i < N) {
+      const bool merged = ((n < 32 ? merged_lo : n < 64 ? merged_mid : merged_hi) >> (n & 31)) & 1u;
+      // a destination's row, and the row a merged source reads back: the block's rank among the destinations
+      const int row = (key[n] == 0u || merged) ? n_unmerged + (c.tq * g.nH + c.hq) * g.nW + c.wq : un_rank++;
+      row_of[(long long)b * N + i] = row;
+      if (!merged) src_of[(long long)b * (N - r) + row] = i;
+    }
+    walk_next(g, c);
   }
 }
 
@@ -373,7 +513,12 @@ hipError_t launch_merge_similarity(const void* k, const Dims& s, const MergeGrid
 
 hipError_t launch_merge_select(const float* u, const MergeGrid& g, int B, int N, int r, int32_t* row_of, int32_t* src_of,
                                hipStream_t st) {
-  merge_select<<<(unsigned)B, kSelThreads, 0, st>>>(u, row_of, src_of, g, N, r);
+  if (N <= kSelThreads * 32)
+    merge_select_reg<32><<<(unsigned)B, kSelThreads, 0, st>>>(u, row_of, src_of, g, N, r);
+  else if (N <= kSelThreads * 80)
+    merge_select_reg<80><<<(unsigned)B, kSelThreads, 0, st>>>(u, row_of, src_of, g, N, r);
+  else
+    merge_select<<<(unsigned)B, kSelThreads, 0, st>>>(u, row_of, src_of, g, N, r);
   return hipGetLastError();
 }
 

@@ -115,3 +115,31 @@ def test_merge_then_attention_then_unmerge(usv):
     np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
     ref = orc.unmerge_apply(orc.block_sparse_attn(qm, km, vm, ridx, rcnt, Nm)[0], rr)
     gu.assert_attn_close(out, ref, "bf16", False, "merged pipeline")
+
+
+def test_full_size_480p_half_merged(usv):
+    """The benchmark shape of bench.py --path merge: 21 x 30 x 52 tokens, 12 heads, 2x2x2 blocks, half of the
+    tokens merged.  Plan bit-exact on all 32760 tokens; features on sampled heads; unmerge bit-exact."""
+    grid, mb, Hh, d = (21, 30, 52), (2, 2, 2), 12, 128
+    N = 32760
+    r = N // 2
+    gen = torch.Generator(device=gu.DEV).manual_seed(5)
+    base = torch.randn((1, 1, N, d), device=gu.DEV, generator=gen)
+    k = (torch.randn((1, Hh, N, d), device=gu.DEV, generator=gen) + 2 * base).to(torch.bfloat16)
+    x = torch.randn((1, Hh, N, d), device=gu.DEV, generator=gen).to(torch.bfloat16)
+    u = usv.merge_similarity(k, grid, mb)
+    u_h = gu.down(u)
+    gu.assert_f32_close(u_h, orc.merge_similarity(gu.down(k).astype(np.float64), grid, mb), "similarity 480p")
+    row_of, src_of = usv.merge_plan(u, grid, mb, r)
+    rr, rs = orc.merge_plan(u_h, grid, mb, r)
+    np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
+    np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
+    y = usv.merge_apply(x, grid, mb, row_of, src_of)
+    assert y.shape[2] == 16384
+    for h in (0, 7):
+        ref = orc.merge_apply(gu.down(x[:, h:h + 1]).astype(np.float64), rr, rs, 16384)
+        ok = bf16_round_ok(gu.down(y[:, h:h + 1]), ref)
+        assert ok.all(), f"head {h}: {(~ok).sum()} elements beyond one bf16 rounding"
+    z = usv.unmerge_apply(y, grid, mb, row_of, N - r)
+    idx = torch.from_numpy(rr[0].astype(np.int64)).to(gu.DEV)
+    assert torch.equal(z.view(torch.int16), y[:, :, idx, :].view(torch.int16))
