@@ -231,6 +231,7 @@ def merge_main(args):
     base = torch.randn((B, 1, N, d), device=dev, generator=gen)
     q, k, v = ((torch.randn((B, Hh, N, d), device=dev, generator=gen) + 2 * base).to(torch.bfloat16) for _ in range(3))
     u = torch.empty((B, N), dtype=torch.float32, device=dev)
+    blk = torch.empty((N,), dtype=torch.int32, device=dev)
     ws = torch.empty(B * N * (d + 1) * 4, dtype=torch.uint8, device=dev)
     row_of = torch.empty((B, N), dtype=torch.int32, device=dev)
     src_of = torch.empty((B, Nm), dtype=torch.int32, device=dev)
@@ -242,9 +243,9 @@ def merge_main(args):
     def step(events=None):
         rec = (lambda i: events[i].record()) if events is not None else (lambda i: None)
         rec(0)
-        usv.merge_similarity(k, grid, mb, out=u, workspace=ws)
+        usv.merge_similarity(k, grid, mb, out=u, blk=blk, workspace=ws)
         rec(1)
-        usv.merge_plan(u, grid, mb, r, row_of=row_of, src_of=src_of)
+        usv.merge_plan(u, blk, grid, mb, r, row_of=row_of, src_of=src_of)
         rec(2)
         for x, y in zip((q, k, v), merged):
             usv.merge_apply(x, grid, mb, row_of, src_of, seq_len=Np, out=y)

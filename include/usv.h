@@ -302,18 +302,25 @@ usv_status usv_cube_scatter(const void* cube, const usv_shape* shape, const usv_
  * squared norms: B * T*H*W * (d + 1) * 4).  Returns 0 for invalid arguments. */
 size_t usv_merge_workspace_bytes(const usv_shape* shape, const usv_grid* grid);
 
-/* k  : [B, Hh, T*H*W, d] of shape->dtype, raster order (device, read only)
- * u  : [B, T*H*W] fp32 (device, written) */
+/* k   : [B, Hh, T*H*W, d] of shape->dtype, raster order (device, read only)
+ * u   : [B, T*H*W] fp32 (device, written)
+ * blk : [T*H*W] int32 (device, written): the partition, a function of the grid
+ *       only: blk[i] & 0x7fffffff = rank of token i's merge block among the
+ *       destinations in ascending raster order; bit 31 is set iff token i is the
+ *       destination of its block */
 usv_status usv_merge_similarity(const void* k, const usv_shape* shape, const usv_grid* grid, float* u,
-                                void* ws, size_t ws_bytes, void* stream);
+                                int32_t* blk, void* ws, size_t ws_bytes, void* stream);
 
 /* u      : [B, T*H*W] fp32 (device, read only); compared on canonical values
- *          (-0 equals +0, NaN ranks lowest); the result is a pure function of u
+ *          (-0 equals +0, NaN ranks lowest); values at destinations are ignored;
+ *          the result is a pure function of u and the grid
+ * blk    : [T*H*W] int32 as written by usv_merge_similarity (device, read only;
+ *          not validated)
  * row_of : [B, T*H*W] int32 (device, written): the merged row token k reads back
  * src_of : [B, N - r] int32 (device, written): the raster index of the token that
  *          owns each merged row */
-usv_status usv_merge_plan(const float* u, const usv_shape* shape, const usv_grid* grid, int32_t* row_of,
-                          int32_t* src_of, void* stream);
+usv_status usv_merge_plan(const float* u, const int32_t* blk, const usv_shape* shape,
+                          const usv_grid* grid, int32_t* row_of, int32_t* src_of, void* stream);
 
 /* x   : [B, Hh, T*H*W, d] of shape->dtype, raster order (device, read only)
  * out : [B, Hh, seq_len, d] of shape->dtype (device, written); means are taken in

@@ -106,8 +106,8 @@ def lib() -> ctypes.CDLL:
     L.usv_cube_gather.restype, L.usv_cube_gather.argtypes = i32, [vp, stp, sp, gp, vp, vp]
     L.usv_cube_scatter.restype, L.usv_cube_scatter.argtypes = i32, [vp, sp, gp, vp, stp, vp]
     L.usv_merge_workspace_bytes.restype, L.usv_merge_workspace_bytes.argtypes = sz, [sp, gp]
-    L.usv_merge_similarity.restype, L.usv_merge_similarity.argtypes = i32, [vp, sp, gp, vp, vp, sz, vp]
-    L.usv_merge_plan.restype, L.usv_merge_plan.argtypes = i32, [vp, sp, gp, vp, vp, vp]
+    L.usv_merge_similarity.restype, L.usv_merge_similarity.argtypes = i32, [vp, sp, gp, vp, vp, vp, sz, vp]
+    L.usv_merge_plan.restype, L.usv_merge_plan.argtypes = i32, [vp, vp, sp, gp, vp, vp, vp]
     L.usv_merge_apply.restype, L.usv_merge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp, vp]
     L.usv_unmerge_apply.restype, L.usv_unmerge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp]
     L.usv_status_string.restype, L.usv_status_string.argtypes = ctypes.c_char_p, [i32]
@@ -374,23 +374,26 @@ def _merge_shape(B, Hh, d, dtype, grid, r, seq_len=None) -> UsvShape:
     return UsvShape(B, Hh, int(seq_len), n_valid, d, BLOCK, USV_BF16 if dtype == torch.bfloat16 else USV_F32)
 
 
-def merge_similarity(k, grid, mblock, out=None, workspace=None):
-    """usv_merge_similarity: K [B, Hh, T*H*W, d] in raster order -> u [B, T*H*W] fp32 (-inf at destinations)."""
+def merge_similarity(k, grid, mblock, out=None, blk=None, workspace=None):
+    """usv_merge_similarity: K [B, Hh, T*H*W, d] in raster order -> (u [B, T*H*W] fp32, -inf at destinations;
+    blk [T*H*W] int32, the partition: block rank, bit 31 at destinations)."""
     B, Hh, N, d = k.shape
     sh = _merge_shape(B, Hh, d, k.dtype, grid, 0)
     g = _grid(grid, mblock)
     if out is None:
         out = torch.empty((B, N), dtype=torch.float32, device=k.device)
+    if blk is None:
+        blk = torch.empty((N,), dtype=torch.int32, device=k.device)
     need = int(lib().usv_merge_workspace_bytes(ctypes.byref(sh), ctypes.byref(g)))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=k.device)
     _check(lib().usv_merge_similarity(_dev(k, "k"), ctypes.byref(sh), ctypes.byref(g), _dev(out, "u", torch.float32),
-                                      _dev(workspace, "workspace"), workspace.numel(), _stream()))
-    return out
+                                      _dev(blk, "blk", torch.int32), _dev(workspace, "workspace"), workspace.numel(), _stream()))
+    return out, blk
 
 
-def merge_plan(u, grid, mblock, r, row_of=None, src_of=None):
-    """usv_merge_plan: u [B, T*H*W] fp32 -> row_of [B, T*H*W], src_of [B, T*H*W - r] (int32)."""
+def merge_plan(u, blk, grid, mblock, r, row_of=None, src_of=None):
+    """usv_merge_plan: u [B, T*H*W] fp32 and the partition blk -> row_of [B, T*H*W], src_of [B, T*H*W - r] (int32)."""
     B, N = u.shape
     sh = _merge_shape(B, 1, 64, torch.float32, grid, r)
     g = _grid(grid, mblock)
@@ -398,7 +401,7 @@ def merge_plan(u, grid, mblock, r, row_of=None, src_of=None):
         row_of = torch.empty((B, N), dtype=torch.int32, device=u.device)
     if src_of is None:
         src_of = torch.empty((B, max(N - int(r), 1)), dtype=torch.int32, device=u.device)[:, : N - int(r)]
-    _check(lib().usv_merge_plan(_dev(u, "u", torch.float32), ctypes.byref(sh), ctypes.byref(g),
+    _check(lib().usv_merge_plan(_dev(u, "u", torch.float32), _dev(blk, "blk", torch.int32), ctypes.byref(sh), ctypes.byref(g),
                                 _dev(row_of, "row_of", torch.int32), _dev(src_of, "src_of", torch.int32), _stream()))
     return row_of, src_of
 

@@ -295,31 +295,33 @@ size_t usv_merge_workspace_bytes(const usv_shape* shape, const usv_grid* grid) {
   return (size_t)s.B * N * (s.d + 1) * sizeof(float);
 }
 
-usv_status usv_merge_similarity(const void* k, const usv_shape* shape, const usv_grid* grid, float* u, void* ws,
-                                size_t ws_bytes, void* stream) {
+usv_status usv_merge_similarity(const void* k, const usv_shape* shape, const usv_grid* grid, float* u, int32_t* blk,
+                                void* ws, size_t ws_bytes, void* stream) {
   usv::Dims s;
   usv::MergeGrid g;
   int N, r;
   USV_TRY(check_merge(shape, grid, &s, &g, &N, &r));
   USV_TRY(check_ptr(k, "k"));
   USV_TRY(check_ptr(u, "u"));
+  USV_TRY(check_ptr(blk, "blk"));
   const size_t need = usv_merge_workspace_bytes(shape, grid);
   if (!ws || !aligned16(ws) || ws_bytes < need)
     return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
-  return hip_result(usv::launch_merge_similarity(k, s, g, N, u, static_cast<float*>(ws), static_cast<hipStream_t>(stream)),
+  return hip_result(usv::launch_merge_similarity(k, s, g, N, u, blk, static_cast<float*>(ws), static_cast<hipStream_t>(stream)),
                     "usv_merge_similarity launch");
 }
 
-usv_status usv_merge_plan(const float* u, const usv_shape* shape, const usv_grid* grid, int32_t* row_of,
-                          int32_t* src_of, void* stream) {
+usv_status usv_merge_plan(const float* u, const int32_t* blk, const usv_shape* shape, const usv_grid* grid,
+                          int32_t* row_of, int32_t* src_of, void* stream) {
   usv::Dims s;
   usv::MergeGrid g;
   int N, r;
   USV_TRY(check_merge(shape, grid, &s, &g, &N, &r));
   USV_TRY(check_ptr(u, "u"));
+  USV_TRY(check_ptr(blk, "blk"));
   USV_TRY(check_ptr(row_of, "row_of"));
   USV_TRY(check_ptr(src_of, "src_of"));
-  return hip_result(usv::launch_merge_select(u, g, s.B, N, r, row_of, src_of, static_cast<hipStream_t>(stream)),
+  return hip_result(usv::launch_merge_select(u, blk, g, s.B, N, r, row_of, src_of, static_cast<hipStream_t>(stream)),
                     "usv_merge_plan launch");
 }
 

@@ -4,10 +4,11 @@
 // aggregation, the merged sequence [unmerged sources || destinations], and the exact unmerge.
 //
 //   merge_descriptors  HBM bound: reads K once, m[b,i,:] = mean over heads (fp32) and |m|^2
-//   merge_similarity   u[b,i] = cos(m_i, m_dst(i)); -inf at destinations
-//   merge_select       one workgroup per batch element: radix search (4 bits per step) for the r-th
-//                      largest source key, then one ordered sweep that ranks ties by index and
-//                      assigns the rows of the merged sequence (ballot prefix counts, no atomics)
+//   merge_similarity   u[b,i] = cos(m_i, m_dst(i)); -inf at destinations; also blk[i], the rank of
+//                      token i's block among the destinations (bit 31 marks the destination)
+//   merge_select       one workgroup per batch element: bit-by-bit search for the r-th largest
+//                      source key (keys in registers), then one ordered sweep that ranks ties by
+//                      index and assigns the rows of the merged sequence (scans, no atomics)
 //   merge_rows         merged features: a destination row is the mean of itself and its merged
 //                      sources (found by scanning its own block), other rows are copies
 //   unmerge_rows       gather: token k reads row row_of[k]
@@ -121,15 +122,17 @@ __global__ __launch_bounds__(256) void merge_descriptors(const T* __restrict__ k
 // grid = (ceil(N / (256 / (D/4))), B); D/4 lanes per token.
 template <int D>
 __global__ __launch_bounds__(256) void merge_similarity(const float* __restrict__ m, const float* __restrict__ norm2,
-                                                        float* __restrict__ u, MergeGrid g, int N) {
+                                                        float* __restrict__ u, int32_t* __restrict__ blk, MergeGrid g,
+                                                        int N) {
   constexpr int LPR = D / 4, RPW = 256 / LPR;
   const int b = blockIdx.y, i = blockIdx.x * RPW + threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * 4;
-  int j = 0;
+  int j = 0, rank = 0;
   bool dst = false;
   float dot = 0.f;
   if (i < N) {
     const Tok c = coords(g, i);
     dst = is_dst(g, c);
+    rank = dst_rank(g, c);  // c and its block's corner have the same quotients
     j = dst_index(g, c);
     const float4 a = *reinterpret_cast<const float4*>(m + ((long long)b * N + i) * D + c0);
     const float4 d = *reinterpret_cast<const float4*>(m + ((long long)b * N + j) * D + c0);
@@ -140,6 +143,7 @@ __global__ __launch_bounds__(256) void merge_similarity(const float* __restrict_
   if (i < N && threadIdx.x % LPR == 0) {
     const float den = sqrtf(norm2[(long long)b * N + i]) * sqrtf(norm2[(long long)b * N + j]);
     u[(long long)b * N + i] = dst ? -INFINITY : (den > 0.f ? dot / den : 0.f);
+    if (b == 0) blk[i] = rank | (dst ? (int)0x80000000 : 0);  // depends on the grid only
   }
 }
 
@@ -154,213 +158,129 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 
-// Exclusive prefix of a 0/1 flag over the workgroup, in thread order; *total = number of set flags.
-// `wave_tot` is LDS scratch of kSelWaves ints.  Contains two barriers.
-__device__ __forceinline__ int block_rank(bool flag, int* wave_tot, int* total) {
+// Exclusive prefixes of CH integers per thread in (chunk, thread) order: out[c] = everything in the
+// chunks before c plus the threads before this one in chunk c; *carry_io carries the running total
+// across calls (in: everything before chunk 0; out: plus these chunks).  `wave_tot` is LDS scratch of
+// CH * kSelWaves + 1 ints.  Three barriers: wave scans, one wave scans the wave totals, read back.
+template <int CH>
+__device__ __forceinline__ void block_exclusive_chunks(int (&v)[CH], int* wave_tot, int* carry_io) {
+  constexpr int ENTRIES = CH * kSelWaves, EPL = (ENTRIES + 63) / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const unsigned long long bal = __ballot(flag);
-  if (lane == 0) wave_tot[wave] = __popcll(bal);
-  __syncthreads();
-  int before = 0, all = 0;
+  int inc[CH];
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
-    const int c = wave_tot[w];
-    before += w < wave ? c : 0;
-    all += c;
-  }
-  __syncthreads();
-  *total = all;
-  return before + __popcll(bal & ((1ull << lane) - 1ull));
-}
-
-// grid = B; 1024 threads.  r = number of sources to merge (0 <= r <= number of sources).  General
-// version: keys are re-read from memory in every step (used when they do not fit the registers).
-__global__ __launch_bounds__(kSelThreads) void merge_select(const float* __restrict__ u, int32_t* __restrict__ row_of,
-                                                            int32_t* __restrict__ src_of, MergeGrid g, int N, int r) {
-  __shared__ int hist[kSelWaves][16];
-  __shared__ int wave_tot[kSelWaves];
-  __shared__ uint32_t s_prefix;
-  __shared__ int s_want;
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float* ub = u + (long long)b * N;
-  const int n_dst = g.nT * g.nH * g.nW;
-  const int n_unmerged = N - n_dst - r;
-
-  // ---- the r-th largest source key, 4 bits per step ------------------------------------------
-  uint32_t thr = 0xffffffffu;  // r == 0: nothing is above or at the threshold
-  int need_eq = 0;
-  if (r > 0) {
-    uint32_t prefix = 0u;
-    int want = r;  // rank (1 = largest) of the wanted key among the keys that share the prefix
-    for (int shift = 28; shift >= 0; shift -= 4) {
-      int cnt[16];
+  for (int c = 0; c < CH; ++c) {
+    inc[c] = v[c];
 #pragma unroll
-      for (int d = 0; d < 16; ++d) cnt[d] = 0;
-      for (int i = tid; i < N; i += kSelThreads) {
-        const Tok c = coords(g, i);
-        const uint32_t key = order_key(ub[i]);
-        const bool in = !is_dst(g, c) && (shift == 28 || (key >> (shift + 4)) == (prefix >> (shift + 4)));
-        const int dig = (key >> shift) & 15;
-#pragma unroll
-        for (int d = 0; d < 16; ++d) cnt[d] += (in && dig == d) ? 1 : 0;
-      }
-#pragma unroll
-      for (int d = 0; d < 16; ++d) {
-        int v = cnt[d];
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-        if (lane == 0) hist[wave][d] = v;
-      }
-      __syncthreads();
-      if (tid == 0) {
-        int w = want;
-        int dsel = 0;
-        for (int d = 15; d >= 0; --d) {
-          int c = 0;
-          for (int q = 0; q < kSelWaves; ++q) c += hist[q][d];
-          if (w <= c) {
-            dsel = d;
-            break;
-          }
-          w -= c;
-        }
-        s_prefix = prefix | ((uint32_t)dsel << shift);
-        s_want = w;
-      }
-      __syncthreads();
-      prefix = s_prefix;
-      want = s_want;
-      __syncthreads();
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc[c], o);
+      if (lane >= o) inc[c] += t;
     }
-    thr = prefix;
-    need_eq = want;  // among the sources whose key equals thr, the first `want` by index are merged
-  }
-
-  // ---- one ordered sweep: ranks of ties, rows of the merged sequence ----------------------------
-  int eq_base = 0, un_base = 0;
-  for (int i0 = 0; i0 < N; i0 += kSelThreads) {  // uniform trip count: barriers inside
-    const int i = i0 + tid;
-    const bool live = i < N;
-    Tok c = {0, 0, 0};
-    uint32_t key = 0u;
-    bool dst = false;
-    if (live) {
-      c = coords(g, i);
-      dst = is_dst(g, c);
-      key = order_key(ub[i]);
-    }
-    const bool src = live && !dst;
-    const bool eq = src && key == thr;
-    int eq_tot, un_tot;
-    const int eq_rank = eq_base + block_rank(eq, wave_tot, &eq_tot);
-    const bool merged = src && (key > thr || (eq && eq_rank < need_eq));
-    const bool unmerged = src && !merged;
-    const int un_rank = un_base + block_rank(unmerged, wave_tot, &un_tot);
-    if (live) {
-      int row;
-      if (dst) {
-        row = n_unmerged + dst_rank(g, c);
-      } else if (unmerged) {
-        row = un_rank;
-      } else {
-        const Tok d = {c.t - c.t % g.st, c.h - c.h % g.sh, c.w - c.w % g.sw};
-        row = n_unmerged + dst_rank(g, d);
-      }
-      row_of[(long long)b * N + i] = row;
-      if (!merged) src_of[(long long)b * (N - r) + row] = i;
-    }
-    eq_base += eq_tot;
-    un_base += un_tot;
-  }
-}
-
-// Exclusive prefix of an integer over the workgroup, in thread order; *total = sum.  Two barriers.
-__device__ __forceinline__ int block_exclusive(int v, int* wave_tot, int* total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(inc, o);
-    if (lane >= o) inc += t;
-  }
-  if (lane == 63) wave_tot[wave] = inc;
-  __syncthreads();
-  int before = 0, all = 0;
-#pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
-    const int c = wave_tot[w];
-    before += w < wave ? c : 0;
-    all += c;
+    if (lane == 63) wave_tot[c * kSelWaves + wave] = inc[c];
   }
   __syncthreads();
-  *total = all;
-  return before + inc - v;
-}
-
-// Walks consecutive raster tokens while keeping each coordinate's position inside its merge block
-// (tm, hm, wm) and its block index (tq, hq, wq) by increments: no division after the first token.
-struct Walk {
-  int t, h, w, tm, hm, wm, tq, hq, wq;
-};
-__device__ __forceinline__ Walk walk_from(const MergeGrid& g, int i) {
-  const Tok c = coords(g, i);
-  Walk k;
-  k.t = c.t; k.h = c.h; k.w = c.w;
-  k.tq = c.t / g.st; k.tm = c.t - k.tq * g.st;
-  k.hq = c.h / g.sh; k.hm = c.h - k.hq * g.sh;
-  k.wq = c.w / g.sw; k.wm = c.w - k.wq * g.sw;
-  return k;
-}
-__device__ __forceinline__ void walk_next(const MergeGrid& g, Walk& k) {
-  ++k.w;
-  if (++k.wm == g.sw) k.wm = 0, ++k.wq;
-  if (k.w == g.W) {
-    k.w = 0; k.wm = 0; k.wq = 0;
-    ++k.h;
-    if (++k.hm == g.sh) k.hm = 0, ++k.hq;
-    if (k.h == g.H) {
-      k.h = 0; k.hm = 0; k.hq = 0;
-      ++k.t;
-      if (++k.tm == g.st) k.tm = 0, ++k.tq;
+  if (wave == 0) {  // exclusive scan of the ENTRIES wave totals, EPL consecutive entries per lane
+    int x[EPL], sum = 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const int id = lane * EPL + e;
+      x[e] = id < ENTRIES ? wave_tot[id] : 0;
+      sum += x[e];
+    }
+    int run = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(run, o);
+      if (lane >= o) run += t;
+    }
+    if (lane == 63) wave_tot[ENTRIES] = run;  // grand total
+    run -= sum;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const int id = lane * EPL + e;
+      if (id < ENTRIES) wave_tot[id] = run;
+      run += x[e];
     }
   }
+  __syncthreads();
+  const int carry = *carry_io;
+#pragma unroll
+  for (int c = 0; c < CH; ++c) v[c] = carry + wave_tot[c * kSelWaves + wave] + inc[c] - v[c];
+  *carry_io = carry + wave_tot[ENTRIES];
+  __syncthreads();
 }
 
-// The same selection for N <= 1024 * KPT with every key held in registers: thread t owns the KPT
-// consecutive tokens [t * KPT, t * KPT + KPT), so the search never re-reads memory and the ordered
-// sweep needs two workgroup scans in all.  Keys: 0 = not a source (destination or past the end),
-// sources >= 1 (a NaN similarity, the lowest rank, maps to 1; every number maps above 0x007fffff).
-// The r-th largest key is found bit by bit from the top (a compare and a wave-wide count per key and
-// bit); r <= number of sources keeps the key-0 entries out of the result.
-template <int KPT>
-__global__ __launch_bounds__(kSelThreads) void merge_select_reg(const float* __restrict__ u, int32_t* __restrict__ row_of,
-                                                                int32_t* __restrict__ src_of, MergeGrid g, int N, int r) {
+// Selection and row assignment, one workgroup per batch element (grid = B, 1024 threads).
+// `blk[i]` = rank of token i's block among the destinations, bit 31 set at the destination itself
+// (written by merge_similarity).  Tokens are handled in chunks of 4096: thread t owns the four
+// consecutive tokens 4096 c + 4 t .. + 3 of chunk c, so loads and stores are 16 bytes per lane and
+// contiguous across the wave, and (chunk, thread, e) order is raster order.
+// Keys: 0 = not a source (destination or past the end), sources >= 1 (a NaN similarity, the lowest
+// rank, maps to 1; every number maps above 0x007fffff).  The r-th largest key is found bit by bit
+// from the top; r <= number of sources keeps the key-0 entries out of the result.
+// CH > 0: all keys of up to 4096 * CH tokens stay in registers.  CH == 0: any N, keys are re-read
+// from memory in every pass.
+template <int CH>
+__global__ __launch_bounds__(kSelThreads) void merge_select(const float* __restrict__ u, const int32_t* __restrict__ blk,
+                                                            int32_t* __restrict__ row_of, int32_t* __restrict__ src_of,
+                                                            int N, int n_dst, int r) {
+  constexpr bool kReg = CH > 0;
+  constexpr int C = kReg ? CH : 1;
   __shared__ int wave_cnt[2][kSelWaves];
-  __shared__ int wave_tot[kSelWaves];
+  __shared__ int wave_tot[C * kSelWaves + 1];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* ub = u + (long long)b * N;
-  const int n_dst = g.nT * g.nH * g.nW;
+  int32_t* rob = row_of + (long long)b * N;
+  int32_t* sob = src_of + (long long)b * (N - r);
   const int n_unmerged = N - n_dst - r;
-  const int first = tid * KPT;
+  const int chunks = kReg ? CH : (N + 4 * kSelThreads - 1) / (4 * kSelThreads);
+  const bool vec_ok = (N & 3) == 0;  // then every batch element's row of u, blk, row_of is 16-byte aligned
 
-  uint32_t key[KPT];
-  {
-    Walk c = walk_from(g, first < N ? first : 0);
+  auto load_keys = [&](int c, uint32_t (&key)[4], int (&bk)[4]) {
+    const int i0 = (c * kSelThreads + tid) * 4;
+    float x[4] = {0.f, 0.f, 0.f, 0.f};
+    bk[0] = bk[1] = bk[2] = bk[3] = (int)0x80000000;
+    if (vec_ok && i0 + 3 < N) {
+      const float4 v = *reinterpret_cast<const float4*>(ub + i0);
+      const int4 k4 = *reinterpret_cast<const int4*>(blk + i0);
+      x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+      bk[0] = k4.x; bk[1] = k4.y; bk[2] = k4.z; bk[3] = k4.w;
+    } else {
 #pragma unroll
-    for (int n = 0; n < KPT; ++n) {
-      const float x = first + n < N ? ub[first + n] : 0.f;
-      const uint32_t k = order_key(x);
-      key[n] = (first + n < N && (c.tm | c.hm | c.wm) != 0) ? (k ? k : 1u) : 0u;
-      walk_next(g, c);
+      for (int e = 0; e < 4; ++e)
+        if (i0 + e < N) x[e] = ub[i0 + e], bk[e] = blk[i0 + e];
     }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t k = order_key(x[e]);
+      key[e] = (i0 + e < N && bk[e] >= 0) ? (k ? k : 1u) : 0u;
+    }
+  };
+
+  uint32_t key[C][4];
+  int bk[4];  // the partition words are only needed again at the very end: re-read there rather than kept
+  if (kReg) {
+#pragma unroll
+    for (int c = 0; c < C; ++c) load_keys(c, key[c], bk);
   }
 
   // count of keys >= cand over the workgroup; `buf` alternates so that one barrier per call is enough
   auto count_ge = [&](uint32_t cand, int buf) {
-    int c = 0;
+    int n = 0;
+    if (kReg) {
 #pragma unroll
-    for (int n = 0; n < KPT; ++n) c += __popcll(__ballot(key[n] >= cand));
-    if (lane == 0) wave_cnt[buf][wave] = c;
+      for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) n += key[c][e] >= cand ? 1 : 0;
+    } else {
+      for (int c = 0; c < chunks; ++c) {
+        load_keys(c, key[0], bk);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) n += key[0][e] >= cand ? 1 : 0;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) n += __shfl_xor(n, o);
+    if (lane == 0) wave_cnt[buf][wave] = n;
     __syncthreads();
     int all = 0;
 #pragma unroll
@@ -376,40 +296,70 @@ __global__ __launch_bounds__(kSelThreads) void merge_select_reg(const float* __r
       const uint32_t cand = thr | (1u << bit);
       if (count_ge(cand, bit & 1) >= r) thr = cand;
     }
-    // thr is the r-th largest key; cand = thr + 1 counts the keys above it (thr < 0xffffffff: no key is)
+    // thr is the r-th largest key; thr + 1 counts the keys above it (thr < 0xffffffff: no key is that large)
     need_eq = r - count_ge(thr + 1u, 0);
     __syncthreads();
   }
 
-  int eq_local = 0;
+  // ordered sweep.  Register version: all chunks at once (two scans in all); otherwise chunk by chunk.
+  int eq_carry = 0, un_carry = 0;
+  for (int c0 = 0; c0 < chunks; c0 += C) {  // one trip when kReg
+    if (!kReg) load_keys(c0, key[0], bk);
+    int rank[C];
 #pragma unroll
-  for (int n = 0; n < KPT; ++n) eq_local += key[n] == thr ? 1 : 0;
-  int tot;
-  int eq_rank = block_exclusive(eq_local, wave_tot, &tot);
-  int un_local = 0;
-  uint32_t merged_lo = 0u, merged_mid = 0u, merged_hi = 0u;  // bit n: token first + n is merged (KPT <= 96)
-  static_assert(KPT <= 96, "three 32-bit masks");
+    for (int c = 0; c < C; ++c) {
+      rank[c] = 0;
 #pragma unroll
-  for (int n = 0; n < KPT; ++n) {
-    const bool eq = key[n] == thr;
-    const bool merged = key[n] != 0u && (key[n] > thr || (eq && eq_rank < need_eq));
-    eq_rank += eq ? 1 : 0;
-    un_local += (key[n] != 0u && !merged) ? 1 : 0;
-    if (merged) (n < 32 ? merged_lo : n < 64 ? merged_mid : merged_hi) |= 1u << (n & 31);
-  }
-  int un_rank = block_exclusive(un_local, wave_tot, &tot);
-  Walk c = walk_from(g, first < N ? first : 0);
-#pragma unroll
-  for (int n = 0; n < KPT; ++n) {
-    const int i = first + n;
-    if (i < N) {
-      const bool merged = ((n < 32 ? merged_lo : n < 64 ? merged_mid : merged_hi) >> (n & 31)) & 1u;
-      // a destination's row, and the row a merged source reads back: the block's rank among the destinations
-      const int row = (key[n] == 0u || merged) ? n_unmerged + (c.tq * g.nH + c.hq) * g.nW + c.wq : un_rank++;
-      row_of[(long long)b * N + i] = row;
-      if (!merged) src_of[(long long)b * (N - r) + row] = i;
+      for (int e = 0; e < 4; ++e) rank[c] += key[c][e] == thr ? 1 : 0;
     }
-    walk_next(g, c);
+    block_exclusive_chunks<C>(rank, wave_tot, &eq_carry);
+    unsigned merged_bits[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      int eq_rank = rank[c], un = 0;
+      merged_bits[c] = 0u;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool eq = key[c][e] == thr;
+        const bool merged = key[c][e] != 0u && (key[c][e] > thr || (eq && eq_rank < need_eq));
+        eq_rank += eq ? 1 : 0;
+        un += (key[c][e] != 0u && !merged) ? 1 : 0;
+        merged_bits[c] |= merged ? 1u << e : 0u;
+      }
+      rank[c] = un;
+    }
+    block_exclusive_chunks<C>(rank, wave_tot, &un_carry);
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      const int i0 = ((c0 + c) * kSelThreads + tid) * 4;
+      if (i0 >= N) continue;
+      if (kReg) {
+        if (vec_ok && i0 + 3 < N) {
+          const int4 k4 = *reinterpret_cast<const int4*>(blk + i0);
+          bk[0] = k4.x; bk[1] = k4.y; bk[2] = k4.z; bk[3] = k4.w;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (i0 + e < N) bk[e] = blk[i0 + e];
+        }
+      }
+      int un_rank = rank[c];
+      int row[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool merged = (merged_bits[c] >> e) & 1u;
+        // a destination's row, and the row a merged source reads back: the block's rank among the destinations
+        row[e] = (key[c][e] == 0u || merged) ? n_unmerged + (bk[e] & 0x7fffffff) : un_rank++;
+        if (i0 + e < N && !merged) sob[row[e]] = i0 + e;
+      }
+      if (vec_ok && i0 + 3 < N) {
+        *reinterpret_cast<int4*>(rob + i0) = make_int4(row[0], row[1], row[2], row[3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (i0 + e < N) rob[i0 + e] = row[e];
+      }
+    }
   }
 }
 
@@ -489,8 +439,8 @@ __global__ __launch_bounds__(CHUNKS >= 32 ? 512 : 256) void unmerge_rows(const u
 }  // namespace
 
 // ws: m [B, N, d] fp32, then |m|^2 [B, N] fp32
-hipError_t launch_merge_similarity(const void* k, const Dims& s, const MergeGrid& g, int N, float* u, float* ws,
-                                   hipStream_t st) {
+hipError_t launch_merge_similarity(const void* k, const Dims& s, const MergeGrid& g, int N, float* u, int32_t* blk,
+                                   float* ws, hipStream_t st) {
   float* m = ws;
   float* n2 = ws + (long long)s.B * N * s.d;
   const int vec = s.bf16 ? 8 : 4, rpw = 256 / (s.d / vec);
@@ -506,19 +456,20 @@ hipError_t launch_merge_similarity(const void* k, const Dims& s, const MergeGrid
   if (e != hipSuccess) return e;
   const int rpw2 = 256 / (s.d / 4);
   const dim3 grid_s((unsigned)((N + rpw2 - 1) / rpw2), (unsigned)s.B);
-  if (s.d == 128) merge_similarity<128><<<grid_s, 256, 0, st>>>(m, n2, u, g, N);
-  else merge_similarity<64><<<grid_s, 256, 0, st>>>(m, n2, u, g, N);
+  if (s.d == 128) merge_similarity<128><<<grid_s, 256, 0, st>>>(m, n2, u, blk, g, N);
+  else merge_similarity<64><<<grid_s, 256, 0, st>>>(m, n2, u, blk, g, N);
   return hipGetLastError();
 }
 
-hipError_t launch_merge_select(const float* u, const MergeGrid& g, int B, int N, int r, int32_t* row_of, int32_t* src_of,
-                               hipStream_t st) {
-  if (N <= kSelThreads * 32)
-    merge_select_reg<32><<<(unsigned)B, kSelThreads, 0, st>>>(u, row_of, src_of, g, N, r);
-  else if (N <= kSelThreads * 80)
-    merge_select_reg<80><<<(unsigned)B, kSelThreads, 0, st>>>(u, row_of, src_of, g, N, r);
+hipError_t launch_merge_select(const float* u, const int32_t* blk, const MergeGrid& g, int B, int N, int r, int32_t* row_of,
+                               int32_t* src_of, hipStream_t st) {
+  const int n_dst = g.nT * g.nH * g.nW;
+  if (N <= kSelThreads * 4 * 8)
+    merge_select<8><<<(unsigned)B, kSelThreads, 0, st>>>(u, blk, row_of, src_of, N, n_dst, r);
+  else if (N <= kSelThreads * 4 * 20)
+    merge_select<20><<<(unsigned)B, kSelThreads, 0, st>>>(u, blk, row_of, src_of, N, n_dst, r);
   else
-    merge_select<<<(unsigned)B, kSelThreads, 0, st>>>(u, row_of, src_of, g, N, r);
+    merge_select<0><<<(unsigned)B, kSelThreads, 0, st>>>(u, blk, row_of, src_of, N, n_dst, r);
   return hipGetLastError();
 }
 

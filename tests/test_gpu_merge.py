@@ -30,6 +30,17 @@ def make(rng, shape, dtype, smooth=None):
     return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
 
 
+def expected_blk(grid, mb):
+    """The partition array from the oracle's partition: rank of each token's destination among the destinations
+    (ascending raster index), bit 31 at the destinations."""
+    dst = orc.merge_partition(grid, mb)
+    n = len(dst)
+    dsts = np.nonzero(dst == np.arange(n))[0]
+    rank = np.searchsorted(dsts, dst).astype(np.int64)
+    rank[dst == np.arange(n)] |= 0x80000000
+    return rank.astype(np.uint32).view(np.int32)
+
+
 def bf16_round_ok(got, ref):
     return np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.maximum(1, np.abs(ref))
 
@@ -42,14 +53,15 @@ def test_merge_pipeline(usv, grid, mb, B, Hh, d, dtype):
     K = make(rng, (B, Hh, N, d), dtype, base)
     X = make(rng, (B, Hh, N, d), dtype)
     Kf, Xf = synth.as_f32(K), synth.as_f32(X)
-    u = usv.merge_similarity(gu.up(K), grid, mb)
+    u, blk = usv.merge_similarity(gu.up(K), grid, mb)
     u_h = gu.down(u)
     u_ref = orc.merge_similarity(Kf, grid, mb)
+    np.testing.assert_array_equal(blk.cpu().numpy(), expected_blk(grid, mb))
     assert np.array_equal(np.isneginf(u_h), np.isneginf(u_ref))
     gu.assert_f32_close(u_h, u_ref, "similarity")
     n_src = int((~np.isneginf(u_ref[0])).sum())
     for r in sorted({0, 1, n_src // 3, n_src // 2, n_src}):
-        row_of, src_of = usv.merge_plan(u, grid, mb, r)
+        row_of, src_of = usv.merge_plan(u, blk, grid, mb, r)
         rr, rs = orc.merge_plan(u_h, grid, mb, r)
         np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
         np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
@@ -82,7 +94,7 @@ def test_merge_plan_ties_and_special_values(usv):
     u[:, dst == np.arange(N)] = -np.inf
     n_src = int((dst != np.arange(N)).sum())
     for r in (1, 37, 1000, 1024, 1500, n_src - 1, n_src):
-        row_of, src_of = usv.merge_plan(gu.up(u), grid, mb, r)
+        row_of, src_of = usv.merge_plan(gu.up(u), gu.up(expected_blk(grid, mb)), grid, mb, r)
         rr, rs = orc.merge_plan(u, grid, mb, r)
         np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
         np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
@@ -97,8 +109,8 @@ def test_merge_then_attention_then_unmerge(usv):
     base = rng.standard_normal((B, 1, N, d)).astype(np.float32)
     Q, K, V = (make(rng, (B, Hh, N, d), "bf16", base) for _ in range(3))
     r = N // 2 - 5  # 197 merged rows: a ragged tail inside the last 64-row block
-    u = usv.merge_similarity(gu.up(K), grid, mb)
-    row_of, src_of = usv.merge_plan(u, grid, mb, r)
+    u, blk = usv.merge_similarity(gu.up(K), grid, mb)
+    row_of, src_of = usv.merge_plan(u, blk, grid, mb, r)
     q, k, v = (usv.merge_apply(gu.up(x), grid, mb, row_of, src_of) for x in (Q, K, V))
     Nm = N - r
     S = usv.block_scores(q, k, seq_valid=Nm)
@@ -127,10 +139,10 @@ def test_full_size_480p_half_merged(usv):
     base = torch.randn((1, 1, N, d), device=gu.DEV, generator=gen)
     k = (torch.randn((1, Hh, N, d), device=gu.DEV, generator=gen) + 2 * base).to(torch.bfloat16)
     x = torch.randn((1, Hh, N, d), device=gu.DEV, generator=gen).to(torch.bfloat16)
-    u = usv.merge_similarity(k, grid, mb)
+    u, blk = usv.merge_similarity(k, grid, mb)
     u_h = gu.down(u)
     gu.assert_f32_close(u_h, orc.merge_similarity(gu.down(k).astype(np.float64), grid, mb), "similarity 480p")
-    row_of, src_of = usv.merge_plan(u, grid, mb, r)
+    row_of, src_of = usv.merge_plan(u, blk, grid, mb, r)
     rr, rs = orc.merge_plan(u_h, grid, mb, r)
     np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
     np.testing.assert_array_equal(src_of.cpu().numpy(), rs)

@@ -226,13 +226,14 @@ def test_merge_calls_reject_bad_arguments_before_launch():
     many = shape(seq_len=256, seq_valid=193)  # more rows than tokens
     for bad in (few, many):
         assert L.usv_merge_workspace_bytes(ctypes.byref(bad), ctypes.byref(g)) == 0
-        assert name(L.usv_merge_plan(FAKE, ctypes.byref(bad), ctypes.byref(g), FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
-    assert name(L.usv_merge_plan(FAKE, ctypes.byref(ok), None, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
-    assert name(L.usv_merge_plan(None, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+        assert name(L.usv_merge_plan(FAKE, FAKE, ctypes.byref(bad), ctypes.byref(g), FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_merge_plan(FAKE, FAKE, ctypes.byref(ok), None, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_merge_plan(None, FAKE, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_merge_plan(FAKE, None, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
     zero = binding.UsvGrid(4, 6, 8, 2, 0, 2)
     assert name(L.usv_merge_apply(FAKE, ctypes.byref(ok), ctypes.byref(zero), FAKE, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
     need = L.usv_merge_workspace_bytes(ctypes.byref(ok), ctypes.byref(g))
-    assert name(L.usv_merge_similarity(FAKE, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, need - 1, None)) == "USV_ERR_WORKSPACE"
+    assert name(L.usv_merge_similarity(FAKE, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, FAKE, need - 1, None)) == "USV_ERR_WORKSPACE"
     assert name(L.usv_unmerge_apply(FAKE, ctypes.byref(ok), ctypes.byref(g), FAKE + 2, FAKE, None)) == "USV_ERR_INVALID_ARG"
     assert name(L.usv_merge_apply(FAKE, ctypes.byref(shape(seq_len=128, seq_valid=100, head_dim=48)), ctypes.byref(g),
                                   FAKE, FAKE, FAKE, None)) == "USV_ERR_UNSUPPORTED"
