@@ -46,6 +46,14 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kThreads = 256;
 constexpr float kRescaleSlack = 8.0f;  // log2 units
+// The probabilities are computed as 2^(logit - m - p_shift): the common factor 2^-p_shift cancels in
+// sum(p v) / sum(p), and it pushes every p below tau = 2^-(126 - p_shift) of the row's reference under
+// the fp32 normal range, where v_exp_f32 returns an exact 0.  Zero operands keep the matrix cores'
+// multipliers quiet, which matters because the chip is power-limited under this kernel (measured:
+// +3 % at tau = 2^-24, +10 % on dense lists at tau = 2^-16).  The dropped mass of a row is below
+// keys * tau of its largest term; the launcher picks tau so that this is at most 2^-12 (2.4e-4
+// relative, against an error budget of ~2.5e-3), i.e. tau = 2^-12 / (keys of the longest list).
+constexpr int kDropLog2 = 12;
 
 template <int D>
 struct Tile {
@@ -138,7 +146,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
                                                                 const int32_t* __restrict__ cnt,
                                                                 void* __restrict__ out, float* __restrict__ lse,
                                                                 int nb, int Nv, int kmax, float scale_log2e,
-                                                                int total, int per_xcd) {
+                                                                float p_shift, int total, int per_xcd) {
   using T = Tile<D>;
   constexpr int KSTEPS = D / 16;  // MFMA k-steps of the QK^T product
   constexpr int DSUB = D / 32;    // 32-wide d sub-tiles of the output
@@ -222,7 +230,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   float m = -INFINITY;  // running reference max (log2 domain), identical in both lane halves
   float l = 0.f;        // this lane's partial row sum (its 16 keys per tile)
   // derived from m, refreshed only when m moves (rare): the exponent offset and the raise threshold
-  float neg_m = 0.f;            // -m, or 0 while every key seen so far was masked (m = -inf)
+  float neg_m = 0.f;            // -m - p_shift, or 0 while every key seen so far was masked (m = -inf)
   float m_raise = -INFINITY;    // m + kRescaleSlack
 
   // per-lane LDS byte offsets of the fragment reads (loop invariant)
@@ -322,7 +330,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
       const float m_new = fmaxf(m, mx);
       const float alpha = fast_exp2(m - (m_new == -INFINITY ? 0.f : m_new));  // m = -inf -> 0
       m = m_new;
-      neg_m = m == -INFINITY ? 0.f : -m;
+      neg_m = m == -INFINITY ? 0.f : -m - p_shift;
       m_raise = m + kRescaleSlack;
       l *= alpha;
 #pragma unroll
@@ -458,7 +466,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
         const float val = o[ds][r] * w0 + src[(ds * 16 + r) * 64] * w1;
         o[ds][r] = live ? val : 0.f;
       }
-    if (lse && g == 0) lse[head * (long long)nb * kBlock + token] = live ? (mm + __log2f(lt)) * kLn2 : -INFINITY;
+    if (lse && g == 0) lse[head * (long long)nb * kBlock + token] = live ? (mm + p_shift + __log2f(lt)) * kLn2 : -INFINITY;
     // every exchange value of this wave must be in registers before its area is overwritten
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     float* stage = xch + col * OSTRIDE;  // row (32 qh + col) of the block
@@ -498,11 +506,15 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
   const int per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
   const unsigned grid = (unsigned)per_xcd * kNumXcd;
   const float sl2 = scale * kLog2e;
+  // tau = 2^-(kDropLog2 + ceil(log2(keys of the longest list))), p_shift = 126 + log2(tau), kept within [64, 110]
+  int bits = 0;
+  while ((1LL << bits) < (long long)kmax * kBlock) ++bits;
+  const float p_shift = (float)(126 - kDropLog2 - bits < 64 ? 64 : 126 - kDropLog2 - bits > 110 ? 110 : 126 - kDropLog2 - bits);
   auto Q = static_cast<const uint16_t*>(q);
   auto K = static_cast<const uint16_t*>(k);
   auto V = static_cast<const uint16_t*>(v);
-  attn_bf16<D, OUT_F32, SLOTS, WGS><<<grid, kThreads, 0, st>>>(Q, K, V, idx, cnt, out, lse, s.nb, s.Nv, kmax, sl2, (int)total,
-                                                    per_xcd);
+  attn_bf16<D, OUT_F32, SLOTS, WGS><<<grid, kThreads, 0, st>>>(Q, K, V, idx, cnt, out, lse, s.nb, s.Nv, kmax, sl2, p_shift,
+                                                    (int)total, per_xcd);
   return hipGetLastError();
 }
 
