@@ -49,7 +49,7 @@ Every function is pinned by tests/test_oracle_pins.py against something other
 than itself (closed forms, torch's scaled_dot_product_attention in fp64,
 pure-Python brute force, invariants).  No function here is "parity unpinned".
 
-Readings taken where the paper is silent (also listed in the design notes):
+Readings taken where the paper is silent:
   * score = mean(Q_cube) . mean(K_cube) / sqrt(d); means over valid tokens only;
     a cube with no valid token scores -inf; result rounded once to fp32.
   * selection is per (batch, head, query cube); candidates are the cubes that
