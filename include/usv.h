@@ -335,6 +335,21 @@ usv_status usv_merge_apply(const void* x, const usv_shape* shape, const usv_grid
 usv_status usv_unmerge_apply(const void* y, const usv_shape* shape, const usv_grid* grid,
                              const int32_t* row_of, void* out, void* stream);
 
+/*
+ * usv_block_sparse_attn with the second branch folded into its store, so that the
+ * attention output never makes a round trip through memory:
+ *   out = gate_fine * attention + gate_coarse * coarse[b,h,token/64,:]
+ * exactly as usv_block_sparse_attn followed by usv_fuse_outputs with an fp32
+ * intermediate.  coarse = NULL (then both gates must be NULL) is plain
+ * usv_block_sparse_attn.  coarse: [B, Hh, nb, d] fp32; gates: NULL (= 1) or
+ * [B, Hh, N, d] of shape->dtype.  lse, if requested, is the attention's.
+ */
+usv_status usv_block_sparse_attn_fused(const void* q, const void* k, const void* v,
+                                       const usv_shape* shape, const int32_t* idx, const int32_t* cnt,
+                                       int32_t kmax, float scale, const float* coarse,
+                                       const void* gate_fine, const void* gate_coarse,
+                                       int32_t out_dtype, void* out, float* lse, void* stream);
+
 /* Static string for a status code. */
 const char* usv_status_string(int32_t status);
 

@@ -27,6 +27,7 @@ EXPORTED_SYMBOLS = (
     "usv_attn_entropy",
     "usv_entropy_allocate",
     "usv_block_sparse_attn",
+    "usv_block_sparse_attn_fused",
     "usv_merge_workspace_bytes",
     "usv_merge_similarity",
     "usv_merge_plan",
@@ -95,6 +96,8 @@ def lib() -> ctypes.CDLL:
     L.usv_coarse_workspace_bytes.restype, L.usv_coarse_workspace_bytes.argtypes = sz, [sp]
     L.usv_coarse_attn.restype, L.usv_coarse_attn.argtypes = i32, [vp, vp, sp, vp, vp, sz, vp]
     L.usv_fuse_outputs.restype, L.usv_fuse_outputs.argtypes = i32, [vp, i32, vp, vp, vp, sp, i32, vp, vp]
+    L.usv_block_sparse_attn_fused.restype = i32
+    L.usv_block_sparse_attn_fused.argtypes = [vp, vp, vp, sp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, vp]
     L.usv_entropy_workspace_bytes.restype, L.usv_entropy_workspace_bytes.argtypes = sz, [sp]
     L.usv_attn_entropy.restype, L.usv_attn_entropy.argtypes = i32, [vp, sp, vp, vp, sz, vp]
     L.usv_entropy_allocate.restype = i32
@@ -204,10 +207,11 @@ def select_topk(scores, k=0, seq_valid=None, budgets=None, kmax=None, idx=None, 
 
 
 def block_sparse_attn(q, k, v, idx, cnt, seq_valid=None, scale=0.0, out=None, lse=None, return_lse=False,
-                      out_dtype=None):
-    """usv_block_sparse_attn: attention over the listed K/V blocks.  Returns out (and lse if asked).
+                      out_dtype=None, coarse=None, gate_fine=None, gate_coarse=None):
+    """usv_block_sparse_attn(_fused): attention over the listed K/V blocks.  Returns out (and lse if asked).
 
-    out_dtype: dtype of the result; defaults to q's dtype, torch.float32 is also allowed for bf16 inputs."""
+    out_dtype: dtype of the result; defaults to q's dtype, torch.float32 is also allowed for bf16 inputs.
+    coarse (+ optional gates): usv_block_sparse_attn_fused, out = gate_fine * attention + gate_coarse * coarse[cube]."""
     sh = _shape_of(q, seq_valid)
     for name, t in (("k", k), ("v", v)):
         if t.shape != q.shape or t.dtype != q.dtype:
@@ -227,13 +231,19 @@ def block_sparse_attn(q, k, v, idx, cnt, seq_valid=None, scale=0.0, out=None, ls
     odt = USV_F32 if out.dtype == torch.float32 else USV_BF16
     if lse is None and return_lse:
         lse = torch.empty((sh.batch, sh.heads, sh.seq_len), dtype=torch.float32, device=q.device)
-    _check(
-        lib().usv_block_sparse_attn(
-            _dev(q, "q"), _dev(k, "k"), _dev(v, "v"), ctypes.byref(sh),
-            _dev(idx, "idx", torch.int32), _dev(cnt, "cnt", torch.int32), int(kmax), float(scale),
-            odt, _dev(out, "out"), None if lse is None else _dev(lse, "lse", torch.float32), _stream(),
-        )
-    )
+    head = (_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), ctypes.byref(sh), _dev(idx, "idx", torch.int32),
+            _dev(cnt, "cnt", torch.int32), int(kmax), float(scale))
+    tail = (odt, _dev(out, "out"), None if lse is None else _dev(lse, "lse", torch.float32), _stream())
+    if coarse is None and gate_fine is None and gate_coarse is None:
+        _check(lib().usv_block_sparse_attn(*head, *tail))
+    else:
+        for name, g in (("gate_fine", gate_fine), ("gate_coarse", gate_coarse)):
+            if g is not None and (g.shape != q.shape or g.dtype != q.dtype):
+                raise ValueError(f"{name} must match q in shape and dtype")
+        _check(lib().usv_block_sparse_attn_fused(
+            *head, None if coarse is None else _dev(coarse, "coarse", torch.float32),
+            None if gate_fine is None else _dev(gate_fine, "gate_fine"),
+            None if gate_coarse is None else _dev(gate_coarse, "gate_coarse"), *tail))
     return (out, lse) if return_lse else out
 
 

@@ -180,6 +180,14 @@ usv_status usv_select_topk_ex(const float* scores, const usv_shape* shape, int32
 usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v, const usv_shape* shape,
                                  const int32_t* idx, const int32_t* cnt, int32_t kmax, float scale,
                                  int32_t out_dtype, void* out, float* lse, void* stream) {
+  return usv_block_sparse_attn_fused(q, k, v, shape, idx, cnt, kmax, scale, nullptr, nullptr, nullptr, out_dtype, out,
+                                     lse, stream);
+}
+
+usv_status usv_block_sparse_attn_fused(const void* q, const void* k, const void* v, const usv_shape* shape,
+                                       const int32_t* idx, const int32_t* cnt, int32_t kmax, float scale,
+                                       const float* coarse, const void* gate_fine, const void* gate_coarse,
+                                       int32_t out_dtype, void* out, float* lse, void* stream) {
   usv::Dims s;
   USV_TRY(check_shape(shape, true, &s));
   USV_TRY(check_ptr(q, "q"));
@@ -193,13 +201,23 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v, co
   if (out_dtype != shape->dtype && !(s.bf16 && out_dtype == USV_F32))
     return fail(USV_ERR_UNSUPPORTED, "out_dtype must equal the input dtype, or be USV_F32 for bf16 inputs");
   if (std::isnan(scale) || std::isinf(scale)) return fail(USV_ERR_INVALID_ARG, "scale must be finite");
+  if (!coarse && (gate_fine || gate_coarse)) return fail(USV_ERR_INVALID_ARG, "gates without coarse");
+  if (coarse && !aligned16(coarse)) return fail(USV_ERR_INVALID_ARG, "coarse is not 16-byte aligned");
+  if (gate_fine && !aligned16(gate_fine)) return fail(USV_ERR_INVALID_ARG, "gate_fine is not 16-byte aligned");
+  if (gate_coarse && !aligned16(gate_coarse)) return fail(USV_ERR_INVALID_ARG, "gate_coarse is not 16-byte aligned");
   if (scale <= 0.f) scale = 1.0f / std::sqrt((float)s.d);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const hipError_t e =
-      s.bf16 ? usv::launch_attn_bf16(q, k, v, s, idx, cnt, kmax, scale, out, out_dtype == USV_F32, lse, st)
-             : usv::launch_attn_f32(static_cast<const float*>(q), static_cast<const float*>(k),
-                                    static_cast<const float*>(v), s, idx, cnt, kmax, scale, static_cast<float*>(out),
-                                    lse, st);
+  if (s.bf16) {
+    const usv::FuseArgs fuse{coarse, static_cast<const uint16_t*>(gate_fine), static_cast<const uint16_t*>(gate_coarse)};
+    return hip_result(usv::launch_attn_bf16(q, k, v, s, idx, cnt, kmax, scale, out, out_dtype == USV_F32, lse, fuse, st),
+                      "usv_block_sparse_attn launch");
+  }
+  // fp32 inputs (the accuracy path): attention, then the fusion kernel in place
+  hipError_t e = usv::launch_attn_f32(static_cast<const float*>(q), static_cast<const float*>(k),
+                                      static_cast<const float*>(v), s, idx, cnt, kmax, scale, static_cast<float*>(out),
+                                      lse, st);
+  if (e == hipSuccess && coarse)
+    e = usv::launch_fuse_outputs(out, true, coarse, gate_fine, gate_coarse, true, out, true, s, st);
   return hip_result(e, "usv_block_sparse_attn launch");
 }
 

@@ -72,6 +72,12 @@ struct Tile {
   __device__ static int v_off(int row, int chunk) { return row * kRowBytes + ((chunk ^ v_swz(row)) << 4); }
 };
 
+__device__ __forceinline__ float4 load_bf16x4(const uint16_t* p) {
+  const uint2 w = *reinterpret_cast<const uint2*>(p);
+  return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                     __uint_as_float(w.y & 0xffff0000u));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Lanes l and l ^ 32 hold the two key halves of one query.  v_permlane32_swap on two copies of x
@@ -146,7 +152,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
                                                                 const int32_t* __restrict__ cnt,
                                                                 void* __restrict__ out, float* __restrict__ lse,
                                                                 int nb, int Nv, int kmax, float scale_log2e,
-                                                                float p_shift, int total, int per_xcd) {
+                                                                float p_shift, int total, int per_xcd, FuseArgs fuse) {
   using T = Tile<D>;
   constexpr int KSTEPS = D / 16;  // MFMA k-steps of the QK^T product
   constexpr int DSUB = D / 32;    // 32-wide d sub-tiles of the output
@@ -487,7 +493,18 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     for (int it = 0; it < PIECES / kThreads; ++it) {
       const int id = it * kThreads + tid;
       const int row = id / (D / 4), c4 = (id % (D / 4)) * 4;
-      const float4 val = *reinterpret_cast<const float4*>(stage + row * OSTRIDE + c4);
+      float4 val = *reinterpret_cast<const float4*>(stage + row * OSTRIDE + c4);
+      if (fuse.coarse && i * kBlock + row < Nv) {
+        // second branch folded into the store: out = gate_fine * attention + gate_coarse * cube-level row of this cube
+        const float4 cz = *reinterpret_cast<const float4*>(fuse.coarse + (head * nb + i) * (long long)D + c4);
+        float4 gf = make_float4(1.f, 1.f, 1.f, 1.f), gc = gf;
+        if (fuse.gate_fine) gf = load_bf16x4(fuse.gate_fine + blk_off + row * D + c4);
+        if (fuse.gate_coarse) gc = load_bf16x4(fuse.gate_coarse + blk_off + row * D + c4);
+        val.x = fmaf(gf.x, val.x, gc.x * cz.x);
+        val.y = fmaf(gf.y, val.y, gc.y * cz.y);
+        val.z = fmaf(gf.z, val.z, gc.z * cz.z);
+        val.w = fmaf(gf.w, val.w, gc.w * cz.w);
+      }
       if (OUT_F32) {
         *reinterpret_cast<float4*>(static_cast<float*>(out) + blk_off + row * D + c4) = val;
       } else {
@@ -501,7 +518,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
 
 template <int D, bool OUT_F32, int SLOTS, int WGS>
 hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx, const int32_t* cnt,
-               int kmax, float scale, void* out, float* lse, hipStream_t st) {
+               int kmax, float scale, void* out, float* lse, const FuseArgs& fuse, hipStream_t st) {
   const long long total = s.bh() * s.nb;
   const int per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
   const unsigned grid = (unsigned)per_xcd * kNumXcd;
@@ -514,7 +531,7 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
   auto K = static_cast<const uint16_t*>(k);
   auto V = static_cast<const uint16_t*>(v);
   attn_bf16<D, OUT_F32, SLOTS, WGS><<<grid, kThreads, 0, st>>>(Q, K, V, idx, cnt, out, lse, s.nb, s.Nv, kmax, sl2, p_shift,
-                                                    (int)total, per_xcd);
+                                                    (int)total, per_xcd, fuse);
   return hipGetLastError();
 }
 
@@ -522,7 +539,7 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
 
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
-                            hipStream_t st) {
+                            const FuseArgs& fuse, hipStream_t st) {
   // Two launch shapes (measured at the 480p shape, 51 of 512 blocks kept):
   //   sparse lists: 5-slot ring, 2 workgroups per CU.  Independent lists miss the 4 MiB L2 about half
   //     the time, and what then limits the tile feed is the number of bytes in flight per CU;
@@ -530,8 +547,8 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const D
   //     tiles and L2 serves them): 3-slot ring, 3 workgroups per CU, for the extra wave per SIMD.
   const bool dense_like = 2 * (long long)kmax >= s.nb;
 #define USV_ATTN_CASE(DD, F32)                                                                         \
-  return dense_like ? run<DD, F32, 3, 3>(q, k, v, s, idx, cnt, kmax, scale, out, lse, st)              \
-                    : run<DD, F32, 5, 2>(q, k, v, s, idx, cnt, kmax, scale, out, lse, st)
+  return dense_like ? run<DD, F32, 3, 3>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st)        \
+                    : run<DD, F32, 5, 2>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st)
   if (s.d == 128) {
     if (out_f32) USV_ATTN_CASE(128, true);
     USV_ATTN_CASE(128, false);

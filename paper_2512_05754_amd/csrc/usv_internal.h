@@ -52,9 +52,16 @@ hipError_t launch_fuse_outputs(const void* fine, bool fine_f32, const float* coa
                                hipStream_t st);
 hipError_t launch_attn_f32(const float* q, const float* k, const float* v, const Dims& s, const int32_t* idx,
                            const int32_t* cnt, int kmax, float scale, float* out, float* lse, hipStream_t st);
+// Optional second branch folded into the attention kernel's store (all NULL: plain attention):
+// out = gate_fine * attention + gate_coarse * coarse[cube]; a NULL gate is 1.  Gates are bf16 [B,Hh,N,d].
+struct FuseArgs {
+  const float* coarse;
+  const uint16_t* gate_fine;
+  const uint16_t* gate_coarse;
+};
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
-                            hipStream_t st);
+                            const FuseArgs& fuse, hipStream_t st);
 
 // gather: raster -> cube-major (+ zeroed padding); else cube-major -> raster.  Strides of the raster tensor in BYTES.
 hipError_t launch_cube_move(bool gather, const void* src, void* dst, const CubeGrid& g, const Dims& s, long long sb,

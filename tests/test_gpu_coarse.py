@@ -153,3 +153,48 @@ def test_full_size_480p_two_branch(usv):
             ref = gu.down(gf[0, h, sl]).astype(np.float64) * fine_ref[i][0] + gu.down(gc[0, h, sl]).astype(np.float64) * C_ref[0, h, i]
             ref[nv:] = 0.0
             gu.assert_attn_close(gu.down(out[0, h, sl]), ref, "bf16", False, f"fused head {h} cube {i}")
+
+
+@pytest.mark.parametrize("out_dt", ["f32", "bf16"])
+@pytest.mark.parametrize("w", [
+    Workload("fused_bf16_d128", 2, 2, 9 * 64 - 9, 128, "bf16", 2.0, 4, seed=46),
+    Workload("fused_bf16_d64_dense", 1, 2, 6 * 64 - 40, 64, "bf16", 1.0, 5, seed=47),
+    Workload("fused_f32_d64", 1, 2, 5 * 64 - 17, 64, "f32", 2.0, 2, seed=48),
+], ids=lambda w: w.name)
+def test_attention_with_fused_second_branch(usv, w, out_dt):
+    """usv_block_sparse_attn_fused against the oracle's attention + fusion, with both gates, one gate, none."""
+    if w.dtype == "f32" and out_dt == "bf16":
+        pytest.skip("fp32 inputs store fp32")
+    Q, K, V = synth.gen_qkv(w)
+    rng = np.random.default_rng(w.seed)
+    gf, gc = (storage(rng, Q.shape, w.dtype) for _ in range(2))
+    q, k, v = gu.up(Q), gu.up(K), gu.up(V)
+    S = usv.block_scores(q, k, seq_valid=w.seq_valid)
+    idx, cnt = usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, force_local=True)
+    C = usv.coarse_attn(S, v, seq_valid=w.seq_valid)
+    odt = torch.float32 if out_dt == "f32" else torch.bfloat16
+    Qf, Kf, Vf = synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V)
+    fine_ref = orc.block_sparse_attn(Qf, Kf, Vf, gu.down(idx), gu.down(cnt), w.seq_valid)[0]
+    C_ref = orc.coarse_attn(gu.down(S), Vf, w.seq_valid)
+    for a, b in ((gf, gc), (None, gc), (gf, None), (None, None)):
+        out, lse = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out_dtype=odt, coarse=C,
+                                         gate_fine=None if a is None else gu.up(a),
+                                         gate_coarse=None if b is None else gu.up(b), return_lse=True)
+        ref = orc.fuse_outputs(fine_ref, C_ref, w.seq_valid, None if a is None else synth.as_f32(a),
+                               None if b is None else synth.as_f32(b))
+        got = gu.down(out)
+        assert not got[:, :, w.seq_valid:].any()
+        # the gates scale the attention error: |gate| <= ~4 for N(0,1) gates, so compare the gated parts separately
+        scale_f = 1.0 if a is None else np.abs(synth.as_f32(a)).astype(np.float64)
+        err = np.abs(got - ref)
+        if w.dtype == "f32":
+            gu.assert_f32_close(got, ref, w.name)
+        else:
+            bound = gu.BF16_MAX_ABS * np.maximum(1.0, scale_f) + (2.0 ** -8 * np.abs(ref) if out_dt == "bf16" else 0.0)
+            assert (err <= bound).all(), f"{w.name}: {(err > bound).sum()} beyond bound, worst {err.max():.3e}"
+    # the unfused pair of calls gives the same result up to the rounding of its intermediate
+    fine = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32)
+    sep = gu.down(usv.fuse_outputs(fine, C, gu.up(gf), gu.up(gc), seq_valid=w.seq_valid, out_dtype=torch.float32))
+    one = gu.down(usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32, coarse=C,
+                                        gate_fine=gu.up(gf), gate_coarse=gu.up(gc)))
+    np.testing.assert_allclose(one, sep, rtol=1e-6, atol=1e-6)

@@ -237,3 +237,13 @@ def test_merge_calls_reject_bad_arguments_before_launch():
     assert name(L.usv_unmerge_apply(FAKE, ctypes.byref(ok), ctypes.byref(g), FAKE + 2, FAKE, None)) == "USV_ERR_INVALID_ARG"
     assert name(L.usv_merge_apply(FAKE, ctypes.byref(shape(seq_len=128, seq_valid=100, head_dim=48)), ctypes.byref(g),
                                   FAKE, FAKE, FAKE, None)) == "USV_ERR_UNSUPPORTED"
+
+
+def test_fused_attention_rejects_gates_without_coarse():
+    L = binding.lib()
+    sh = shape(dtype=binding.USV_BF16)
+    args = (FAKE, FAKE, FAKE, ctypes.byref(sh), FAKE, FAKE, 4, ctypes.c_float(0.0))
+    rc = L.usv_block_sparse_attn_fused(*args, None, FAKE, None, binding.USV_BF16, FAKE, None, None)
+    assert L.usv_status_string(rc).decode() == "USV_ERR_INVALID_ARG" and b"coarse" in L.usv_last_error()
+    rc = L.usv_block_sparse_attn_fused(*args, FAKE + 8, None, None, binding.USV_BF16, FAKE, None, None)
+    assert L.usv_status_string(rc).decode() == "USV_ERR_INVALID_ARG"
