@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="wan13_480p",
                     choices=["wan13_480p", "wan14_720p", "merged_ragged", "tiny",
                              "sweep100", "sweep50", "sweep25", "sweep10", "sweep5"])

@@ -292,12 +292,20 @@ __global__ __launch_bounds__(kSelThreads) void merge_select(const float* __restr
   int need_eq = 0;
   if (r > 0) {  // uniform
     thr = 0u;
+    int last_buf = 1;
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = thr | (1u << bit);
-      if (count_ge(cand, bit & 1) >= r) thr = cand;
+      const int c = count_ge(cand, bit & 1);
+      last_buf = bit & 1;
+      if (c >= r) thr = cand;
+      if (c == r) {  // uniform: exactly r keys are >= cand, they are the answer whatever the lower bits are
+        thr = cand - 1u;
+        break;
+      }
     }
-    // thr is the r-th largest key; thr + 1 counts the keys above it (thr < 0xffffffff: no key is that large)
-    need_eq = r - count_ge(thr + 1u, 0);
+    // thr is the r-th largest key (or just below the r selected ones); thr + 1 counts the keys above it
+    // (thr < 0xffffffff: no key is that large)
+    need_eq = r - count_ge(thr + 1u, last_buf ^ 1);
     __syncthreads();
   }
 

@@ -52,19 +52,34 @@ __global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __re
       // returns 0xffffffff), so it is kept first and the rest of the budget goes to the best others
       if (force_local && j == i) key[e] = 0xffffffffu;
     }
-    // threshold = the want-th largest key among the valid slots
+    // threshold = the want-th largest key among the valid slots.  The search stops as soon as a
+    // candidate splits off exactly `want` keys: they are the answer whatever the lower bits are
+    // (with distinct scores that happens after a dozen bits or so, not 32).
     uint32_t thr = 0u;
+    bool exact = false;
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = thr | (1u << bit);
       int c = 0;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) c += wave_count(e * 64 + lane < nb_valid && key[e] >= cand);
       if (c >= want) thr = cand;
+      if (c == want) {  // wave-uniform
+        exact = true;
+        break;
+      }
     }
-    int greater = 0;
+    int need_eq;
+    if (exact) {
+      // every key >= thr is taken: treat them all as "equal to the threshold" takers by lowering thr's
+      // role to a pure lower bound (thr - 1 is below all of them, and no other key is >= thr)
+      need_eq = 0;
+      thr -= 1u;  // thr >= 1 here: c == want >= 1 keys are >= cand, and cand > 0
+    } else {
+      int greater = 0;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) greater += wave_count(e * 64 + lane < nb_valid && key[e] > thr);
-    const int need_eq = want - greater;  // >= 1 by construction
+      for (int e = 0; e < EPL; ++e) greater += wave_count(e * 64 + lane < nb_valid && key[e] > thr);
+      need_eq = want - greater;  // >= 1 by construction
+    }
 
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int out_base = 0, eq_base = 0;
