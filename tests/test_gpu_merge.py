@@ -155,3 +155,23 @@ def test_full_size_480p_half_merged(usv):
     z = usv.unmerge_apply(y, grid, mb, row_of, N - r)
     idx = torch.from_numpy(rr[0].astype(np.int64)).to(gu.DEV)
     assert torch.equal(z.view(torch.int16), y[:, :, idx, :].view(torch.int16))
+
+
+@pytest.mark.parametrize("grid,mb", [((21, 45, 80), (2, 2, 2)), ((24, 60, 64), (1, 2, 2)), ((9, 100, 111), (4, 4, 4))],
+                         ids=["720p_75600_tokens", "92160_tokens", "99900_tokens_cut_blocks"])
+def test_merge_plan_large_token_counts(usv, grid, mb):
+    """Token counts beyond 32768 (keys in 80 registers per thread) and beyond 81920 (keys re-read from memory
+    in every pass): plan bit-exact on engineered similarities with ties, two batch elements."""
+    N = grid[0] * grid[1] * grid[2]
+    rng = np.random.default_rng([9, N])
+    dst = orc.merge_partition(grid, mb)
+    blk = expected_blk(grid, mb)
+    u = (np.round(rng.standard_normal((2, N)) * 64) / 256).astype(np.float32)  # ~600 distinct values: ties everywhere
+    u[1] = rng.standard_normal(N).astype(np.float32)                             # and a row without ties
+    u[:, dst == np.arange(N)] = -np.inf
+    n_src = int((dst != np.arange(N)).sum())
+    for r in (N // 2 if N // 2 <= n_src else n_src, 4097, n_src):
+        row_of, src_of = usv.merge_plan(gu.up(u), gu.up(blk), grid, mb, r)
+        rr, rs = orc.merge_plan(u, grid, mb, r)
+        np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
+        np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
