@@ -276,6 +276,41 @@ usv_status usv_cube_scatter(const void* cube, const usv_shape* shape, const usv_
                             void* raster, const usv_strides* strides, void* stream);
 
 /*
+ * The three stages on RASTER-order tensors, with no reordered copy of anything:
+ * the kernels look every token row up through the order table while they load
+ * and store (the tile requests of the attention kernel carry per-lane global
+ * addresses anyway).  Same results as usv_cube_gather -> stage -> usv_cube_scatter.
+ *   usv_cube_order                the table on the device: order[p] = raster index
+ *                                 of cube-major position p, p < seq_valid; the
+ *                                 padding positions hold 0
+ *   usv_block_scores_raster       usv_block_scores on raster Q, K
+ *   usv_select_topk               unchanged (it only sees the scores)
+ *   usv_block_sparse_attn_raster  usv_block_sparse_attn on raster Q, K, V, writing
+ *                                 out (and lse, [B, Hh, seq_valid]) in raster order
+ */
+typedef struct {
+  const int32_t* order;    /* device, [seq_len] int32, from usv_cube_order (any permutation works) */
+  usv_strides in_strides;  /* element strides of q, k, v; token == 0 means contiguous [B, Hh, Nv, d] */
+  usv_strides out_strides; /* element strides of out; token == 0 means contiguous [B, Hh, Nv, d] */
+} usv_raster;
+
+usv_status usv_cube_order(const usv_shape* shape, const usv_grid* grid, int32_t* order, void* stream);
+
+/* Arguments as usv_block_scores; q, k laid out by view->in_strides. */
+usv_status usv_block_scores_raster(const void* q, const void* k, const usv_shape* shape,
+                                   const usv_raster* view, float* scores, void* ws, size_t ws_bytes,
+                                   void* stream);
+
+/* Arguments as usv_block_sparse_attn; bf16 inputs only (USV_ERR_UNSUPPORTED
+ * otherwise); seq_valid * token stride must stay below 2 GiB.  out has seq_valid
+ * rows per head (no padding rows), laid out by view->out_strides. */
+usv_status usv_block_sparse_attn_raster(const void* q, const void* k, const void* v,
+                                        const usv_shape* shape, const usv_raster* view,
+                                        const int32_t* idx, const int32_t* cnt, int32_t kmax,
+                                        float scale, int32_t out_dtype, void* out, float* lse,
+                                        void* stream);
+
+/*
  * Token merging (Section 3.3, "Token merging for video").  Tokens are in RASTER
  * order of the T x H x W grid.  The grid is tiled from the origin by merge blocks
  * of s_t x s_h x s_w tokens (usv_grid.ct/ch/cw; cut at the boundary).  The first

@@ -16,6 +16,9 @@ _BINDING_NAMES = (
     "entropy_allocate",
     "coarse_attn",
     "fuse_outputs",
+    "cube_order",
+    "block_scores_raster",
+    "block_sparse_attn_raster",
     "cube_token_order",
     "cube_gather",
     "cube_scatter",

@@ -33,6 +33,9 @@ EXPORTED_SYMBOLS = (
     "usv_merge_plan",
     "usv_merge_apply",
     "usv_unmerge_apply",
+    "usv_cube_order",
+    "usv_block_scores_raster",
+    "usv_block_sparse_attn_raster",
     "usv_cube_token_order",
     "usv_cube_gather",
     "usv_cube_scatter",
@@ -66,6 +69,10 @@ class UsvGrid(ctypes.Structure):
 
 class UsvStrides(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("batch", "head", "token")]
+
+
+class UsvRaster(ctypes.Structure):
+    _fields_ = [("order", ctypes.c_void_p), ("in_strides", UsvStrides), ("out_strides", UsvStrides)]
 
 
 def lib_path() -> str:
@@ -113,6 +120,11 @@ def lib() -> ctypes.CDLL:
     L.usv_merge_plan.restype, L.usv_merge_plan.argtypes = i32, [vp, vp, sp, gp, vp, vp, vp]
     L.usv_merge_apply.restype, L.usv_merge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp, vp]
     L.usv_unmerge_apply.restype, L.usv_unmerge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp]
+    rp = ctypes.POINTER(UsvRaster)
+    L.usv_cube_order.restype, L.usv_cube_order.argtypes = i32, [sp, gp, vp, vp]
+    L.usv_block_scores_raster.restype, L.usv_block_scores_raster.argtypes = i32, [vp, vp, sp, rp, vp, vp, sz, vp]
+    L.usv_block_sparse_attn_raster.restype = i32
+    L.usv_block_sparse_attn_raster.argtypes = [vp, vp, vp, sp, rp, vp, vp, i32, f32, i32, vp, vp, vp]
     L.usv_status_string.restype, L.usv_status_string.argtypes = ctypes.c_char_p, [i32]
     L.usv_last_error.restype, L.usv_last_error.argtypes = ctypes.c_char_p, []
     _lib = L
@@ -439,3 +451,63 @@ def unmerge_apply(y, grid, mblock, row_of, n_merged_rows, out=None):
     _check(lib().usv_unmerge_apply(_dev(y, "y"), ctypes.byref(sh), ctypes.byref(g), _dev(row_of, "row_of", torch.int32),
                                    _dev(out, "out"), _stream()))
     return out
+
+
+def cube_order(grid, cube=(4, 4, 4), seq_len=None, device="cuda:0", out=None):
+    """usv_cube_order: the order table on the device, int32 [seq_len] (padding positions hold 0)."""
+    Nv = int(grid[0]) * int(grid[1]) * int(grid[2])
+    if seq_len is None:
+        seq_len = -(-Nv // BLOCK) * BLOCK
+    if out is None:
+        out = torch.empty((seq_len,), dtype=torch.int32, device=device)
+    sh = UsvShape(1, 1, int(seq_len), Nv, 0, BLOCK, USV_F32)
+    g = _grid(grid, cube)
+    _check(lib().usv_cube_order(ctypes.byref(sh), ctypes.byref(g), _dev(out, "order", torch.int32), _stream()))
+    return out
+
+
+def _raster_shape(x, order):
+    B, Hh, Nv, d = x.shape
+    return UsvShape(B, Hh, order.numel(), Nv, d, BLOCK, USV_BF16 if x.dtype == torch.bfloat16 else USV_F32)
+
+
+def block_scores_raster(q, k, order, out=None, workspace=None):
+    """usv_block_scores_raster: q, k raster-ordered [B, Hh, Nv, d] (strided views allowed) -> scores [B, Hh, nb, nb]."""
+    sh = _raster_shape(q, order)
+    qp, st = _raster(q, "q")
+    kp, st_k = _raster(k, "k")
+    if (st_k.batch, st_k.head, st_k.token) != (st.batch, st.head, st.token) or k.dtype != q.dtype:
+        raise ValueError("k must match q in strides and dtype")
+    nb = sh.seq_len // BLOCK
+    if out is None:
+        out = torch.empty((sh.batch, sh.heads, nb, nb), dtype=torch.float32, device=q.device)
+    need = int(lib().usv_workspace_bytes(ctypes.byref(sh)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    view = UsvRaster(_dev(order, "order", torch.int32), st, UsvStrides(0, 0, 0))
+    _check(lib().usv_block_scores_raster(qp, kp, ctypes.byref(sh), ctypes.byref(view), _dev(out, "scores", torch.float32),
+                                         _dev(workspace, "workspace"), workspace.numel(), _stream()))
+    return out
+
+
+def block_sparse_attn_raster(q, k, v, order, idx, cnt, scale=0.0, out=None, out_dtype=None, return_lse=False):
+    """usv_block_sparse_attn_raster: raster-ordered q, k, v [B, Hh, Nv, d] -> out [B, Hh, Nv, d] in raster order."""
+    sh = _raster_shape(q, order)
+    ptrs = []
+    st = None
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        p, s_t = _raster(t, name)
+        if st is None:
+            st = s_t
+        elif (s_t.batch, s_t.head, s_t.token) != (st.batch, st.head, st.token) or t.dtype != q.dtype:
+            raise ValueError(f"{name} must match q in strides and dtype")
+        ptrs.append(p)
+    if out is None:
+        out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
+    op, ost = _raster(out, "out")
+    lse = torch.empty((sh.batch, sh.heads, sh.seq_valid), dtype=torch.float32, device=q.device) if return_lse else None
+    view = UsvRaster(_dev(order, "order", torch.int32), st, ost)
+    _check(lib().usv_block_sparse_attn_raster(*ptrs, ctypes.byref(sh), ctypes.byref(view), _dev(idx, "idx", torch.int32),
+                                              _dev(cnt, "cnt", torch.int32), int(idx.shape[3]), float(scale), _dt(out), op,
+                                              None if lse is None else _dev(lse, "lse", torch.float32), _stream()))
+    return (out, lse) if return_lse else out

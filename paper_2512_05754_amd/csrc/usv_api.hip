@@ -82,8 +82,8 @@ usv_status check_grid(const usv_grid* g, const usv_shape* sh, usv::CubeGrid* out
 }
 
 // Raster strides in bytes (contiguous [B, Hh, Nv, d] when `st` is NULL), checked for 16-byte rows that do not overlap.
-usv_status check_strides(const usv_strides* st, const usv::Dims& s, long long out_bytes[3]) {
-  const long long esz = s.bf16 ? 2 : 4;
+usv_status check_strides(const usv_strides* st, const usv::Dims& s, long long out_bytes[3], long long esz = 0) {
+  if (esz == 0) esz = s.bf16 ? 2 : 4;
   long long e[3] = {(long long)s.Hh * s.Nv * s.d, (long long)s.Nv * s.d, (long long)s.d};
   if (st) {
     e[0] = st->batch;
@@ -368,6 +368,69 @@ usv_status usv_unmerge_apply(const void* y, const usv_shape* shape, const usv_gr
   USV_TRY(check_ptr(out, "out"));
   return hip_result(usv::launch_unmerge_rows(y, s, N, row_of, out, static_cast<hipStream_t>(stream)),
                     "usv_unmerge_apply launch");
+}
+
+// Fills RasterArgs from a usv_raster view (strides in elements -> bytes).
+usv_status check_raster(const usv_raster* view, const usv::Dims& s, long long out_esz, usv::RasterArgs* ras) {
+  if (!view) return fail(USV_ERR_INVALID_ARG, "raster view is NULL");
+  USV_TRY(check_ptr(view->order, "order"));
+  long long in_b[3], out_b[3];
+  USV_TRY(check_strides(view->in_strides.token ? &view->in_strides : nullptr, s, in_b));
+  USV_TRY(check_strides(view->out_strides.token ? &view->out_strides : nullptr, s, out_b, out_esz));
+  // the tile requests carry the row offset in 32 bits
+  if ((long long)s.Nv * in_b[2] > 0x7fffffffLL - 65536)
+    return fail(USV_ERR_UNSUPPORTED, "seq_valid * token stride must stay below 2 GiB");
+  *ras = usv::RasterArgs{view->order, in_b[2], in_b[1], in_b[0], out_b[2], out_b[1], out_b[0], s.Hh};
+  return USV_OK;
+}
+
+usv_status usv_cube_order(const usv_shape* shape, const usv_grid* grid, int32_t* order, void* stream) {
+  usv::Dims s;
+  usv::CubeGrid g;
+  USV_TRY(check_shape(shape, false, &s));
+  USV_TRY(check_grid(grid, shape, &g));
+  USV_TRY(check_ptr(order, "order"));
+  return hip_result(usv::launch_cube_order(order, g, s.N, s.Nv, static_cast<hipStream_t>(stream)), "usv_cube_order launch");
+}
+
+usv_status usv_block_scores_raster(const void* q, const void* k, const usv_shape* shape, const usv_raster* view,
+                                   float* scores, void* ws, size_t ws_bytes, void* stream) {
+  usv::Dims s;
+  usv::RasterArgs ras;
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_raster(view, s, s.bf16 ? 2 : 4, &ras));
+  USV_TRY(check_ptr(q, "q"));
+  USV_TRY(check_ptr(k, "k"));
+  USV_TRY(check_ptr(scores, "scores"));
+  const size_t need = usv_workspace_bytes(shape);
+  if (!ws || !aligned16(ws) || ws_bytes < need)
+    return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
+  return hip_result(usv::launch_block_scores(q, k, s, scores, static_cast<float*>(ws), static_cast<hipStream_t>(stream), &ras),
+                    "usv_block_scores_raster launch");
+}
+
+usv_status usv_block_sparse_attn_raster(const void* q, const void* k, const void* v, const usv_shape* shape,
+                                        const usv_raster* view, const int32_t* idx, const int32_t* cnt, int32_t kmax,
+                                        float scale, int32_t out_dtype, void* out, float* lse, void* stream) {
+  usv::Dims s;
+  usv::RasterArgs ras;
+  USV_TRY(check_shape(shape, true, &s));
+  if (!s.bf16) return fail(USV_ERR_UNSUPPORTED, "the raster-order attention takes bf16 inputs");
+  if (out_dtype != USV_BF16 && out_dtype != USV_F32) return fail(USV_ERR_UNSUPPORTED, "out_dtype must be USV_BF16 or USV_F32");
+  USV_TRY(check_raster(view, s, out_dtype == USV_F32 ? 4 : 2, &ras));
+  USV_TRY(check_ptr(q, "q"));
+  USV_TRY(check_ptr(k, "k"));
+  USV_TRY(check_ptr(v, "v"));
+  USV_TRY(check_ptr(idx, "idx"));
+  USV_TRY(check_ptr(cnt, "cnt"));
+  USV_TRY(check_ptr(out, "out"));
+  if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(USV_ERR_INVALID_ARG, "lse is not 4-byte aligned");
+  if (kmax < 1 || kmax > s.nb) return fail(USV_ERR_INVALID_ARG, "kmax (%d) must be in [1, blocks = %d]", kmax, s.nb);
+  if (std::isnan(scale) || std::isinf(scale)) return fail(USV_ERR_INVALID_ARG, "scale must be finite");
+  if (scale <= 0.f) scale = 1.0f / std::sqrt((float)s.d);
+  return hip_result(usv::launch_attn_bf16_raster(q, k, v, s, ras, idx, cnt, kmax, scale, out, out_dtype == USV_F32, lse,
+                                                 static_cast<hipStream_t>(stream)),
+                    "usv_block_sparse_attn_raster launch");
 }
 
 usv_status usv_cube_token_order(const usv_grid* grid, int32_t* order) {

@@ -144,7 +144,12 @@ __device__ __forceinline__ void dma_tile<2>(const void* gbase, const int (&voff)
 
 // SLOTS (odd) = tile slots of the LDS ring; a tile is requested LEAD = (SLOTS-1)/2 tiles before it
 // is used.  WGS = workgroups (= waves per SIMD) the register and LDS budget is sized for.
-template <int D, bool OUT_F32, int SLOTS, int WGS>
+// RASTER: Q, K, V and the output are in raster token order (any strides); `ras.order[p]` gives the
+// raster index of cube-major position p.  Every wave fetches the 16 order entries of the rows it
+// requests ahead of the tile (one more 4-byte-per-lane DMA per tile, into a small LDS ring that only
+// this wave reads), turns them into the per-lane global offsets of its DMA instructions, and the
+// epilogue stores each row at its raster position: no reordered copy of any tensor exists.
+template <int D, bool OUT_F32, int SLOTS, int WGS, bool RASTER>
 __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __restrict__ q,
                                                                 const uint16_t* __restrict__ k,
                                                                 const uint16_t* __restrict__ v,
@@ -152,7 +157,8 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
                                                                 const int32_t* __restrict__ cnt,
                                                                 void* __restrict__ out, float* __restrict__ lse,
                                                                 int nb, int Nv, int kmax, float scale_log2e,
-                                                                float p_shift, int total, int per_xcd, FuseArgs fuse) {
+                                                                float p_shift, int total, int per_xcd, FuseArgs fuse,
+                                                                RasterArgs ras) {
   using T = Tile<D>;
   constexpr int KSTEPS = D / 16;  // MFMA k-steps of the QK^T product
   constexpr int DSUB = D / 32;    // 32-wide d sub-tiles of the output
@@ -166,6 +172,10 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   constexpr int kEpilogueBytes = 2 * XROWS * 64 * 4;
   constexpr int kSmem = kSlots * T::kBytes > kEpilogueBytes ? kSlots * T::kBytes : kEpilogueBytes;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kSmem];
+  constexpr int kOrdSlots = 4;                       // order entries of tile e live in slot e % 4
+  constexpr int QD = LEAD + (RASTER ? 2 : 0);        // block ids are queued this many tiles ahead
+  constexpr int kBias = 1024 * (kDma - 1);           // keeps the per-lane global offsets of the DMA non-negative
+  __shared__ __attribute__((aligned(256))) int ord_ring[RASTER ? kOrdSlots * kBlock : 1];
 
   const int work = xcd_contiguous_id(blockIdx.x, per_xcd);
   if (work >= total) return;  // whole workgroup leaves before any barrier
@@ -181,6 +191,15 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   const int32_t* list = idx + (long long)work * kmax;
   const uint16_t* kbase = k + head_off;
   const uint16_t* vbase = v + head_off;
+  // raster mode: byte bases of this (batch, head); the K/V ones are lowered by kBias (see kc/vc below)
+  long long ras_off = 0, ras_out = 0;
+  if constexpr (RASTER) {
+    const long long b = head / ras.Hh, h = head - b * ras.Hh;
+    ras_off = b * ras.batch + h * ras.head;
+    ras_out = b * ras.o_batch + h * ras.o_head;
+  }
+  const unsigned char* kbase_r = reinterpret_cast<const unsigned char*>(k) + ras_off - kBias;
+  const unsigned char* vbase_r = reinterpret_cast<const unsigned char*>(v) + ras_off - kBias;
 
   // DMA plan of this wave: instruction `it` fills LDS bytes [a*1024, a*1024+1024) of a tile slot,
   // a = wave*kDma + it; lane -> (row, stored chunk position p); it fetches global chunk
@@ -194,11 +213,56 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     vofs[it] = (row * D + ((p ^ T::v_swz(row)) << 3)) * 2 - 1024 * it;
   }
   const unsigned wave_lds = lds_address(smem) + wave * kDma * 1024;
+  // raster mode: per-lane constants of the DMA offsets (chunk within the row, the bias, the 1024*it that the
+  // instruction offset adds); the row part comes from the order entries of the tile
+  int kc[kDma], vc[kDma], rowoff[kDma];
+  if constexpr (RASTER) {
+#pragma unroll
+    for (int it = 0; it < kDma; ++it) {
+      const int row = (wave * kDma + it) * T::kRowsPerDma + lane / T::kChunks, p = lane % T::kChunks;
+      kc[it] = ((p ^ T::k_swz(row)) << 4) + kBias - 1024 * it;
+      vc[it] = ((p ^ T::v_swz(row)) << 4) + kBias - 1024 * it;
+      rowoff[it] = 0;
+    }
+  }
+  // this wave's 16 order entries of tile `e` (block j) -> its part of ord_ring slot e % 4
+  auto issue_ord = [&](int j, int e) {
+    if constexpr (RASTER) {
+      if (lane < 16) {
+        const unsigned dst = lds_address(ord_ring) + ((e % kOrdSlots) * kBlock + wave * 16) * 4;
+        const int32_t* src = ras.order + (long long)j * kBlock + wave * 16;
+        const int voff = lane * 4;
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(voff), "s"(src) : "memory");
+      }
+    }
+  };
+  // rowoff[it] = byte offset of the token row that DMA instruction `it` of this lane fetches for tile e
+  auto read_ord = [&](int e) {
+    if constexpr (RASTER) {
+      const int* slot = ord_ring + (e % kOrdSlots) * kBlock + wave * 16 + lane / T::kChunks;
+#pragma unroll
+      for (int it = 0; it < kDma; ++it) rowoff[it] = slot[it * T::kRowsPerDma] * (int)ras.tok;
+    }
+  };
   auto issue_k = [&](int j, int slot) {
-    dma_tile<kDma>(kbase + (long long)j * kBlock * D, kofs, wave_lds + slot * T::kBytes);
+    if constexpr (RASTER) {
+      int off[kDma];
+#pragma unroll
+      for (int it = 0; it < kDma; ++it) off[it] = rowoff[it] + kc[it];
+      dma_tile<kDma>(kbase_r, off, wave_lds + slot * T::kBytes);
+    } else {
+      dma_tile<kDma>(kbase + (long long)j * kBlock * D, kofs, wave_lds + slot * T::kBytes);
+    }
   };
   auto issue_v = [&](int j, int slot) {
-    dma_tile<kDma>(vbase + (long long)j * kBlock * D, vofs, wave_lds + slot * T::kBytes);
+    if constexpr (RASTER) {
+      int off[kDma];
+#pragma unroll
+      for (int it = 0; it < kDma; ++it) off[it] = rowoff[it] + vc[it];
+      dma_tile<kDma>(vbase_r, off, wave_lds + slot * T::kBytes);
+    } else {
+      dma_tile<kDma>(vbase + (long long)j * kBlock * D, vofs, wave_lds + slot * T::kBytes);
+    }
   };
 
   // The index list lives in a VGPR, 64 entries at a time (lane t holds entry 64*chunk + t), and is
@@ -209,23 +273,44 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
 
   // ring item 2n = K(list[n]) -> slot (2n) % SLOTS, item 2n+1 = V(list[n]) -> slot (2n+1) % SLOTS;
   // the first LEAD tiles are requested here
+  if constexpr (RASTER) {
+    // the order entries of the first LEAD + 2 tiles; the loop requests those of tile n + LEAD + 2
+#pragma unroll
+    for (int t = 0; t < LEAD + 2; ++t)
+      if (t < n_list) issue_ord(list_at(t), t);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0); each wave reads only what it requested itself
+  }
 #pragma unroll
   for (int t = 0; t < LEAD; ++t)
     if (t < n_list) {
       const int j = list_at(t);
+      read_ord(t);
       issue_k(j, (2 * t) % kSlots);
       issue_v(j, (2 * t + 1) % kSlots);
     }
-  int jq[LEAD + 1];  // block ids of tiles n .. n+LEAD (entries beyond the list read as block 0, unused)
+  int jq[QD + 1];  // block ids of tiles n .. n+QD (entries beyond the list read as block 0, unused)
 #pragma unroll
-  for (int t = 0; t <= LEAD; ++t) jq[t] = list_at(t);
+  for (int t = 0; t <= QD; ++t) jq[t] = list_at(t);
 
   // Q fragments: lane holds query row 32*qh + col, channels 16 t + 8 g .. + 8 for every k-step t
   bf16x8 qf[KSTEPS];
   {
     const uint16_t* qp = q + head_off + (long long)(i * kBlock + qh * 32 + col) * D + g * 8;
+    if constexpr (RASTER)
+      qp = reinterpret_cast<const uint16_t*>(reinterpret_cast<const unsigned char*>(q) + ras_off +
+                                             (long long)ras.order[i * kBlock + qh * 32 + col] * ras.tok) + g * 8;
 #pragma unroll
     for (int t = 0; t < KSTEPS; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(qp + t * 16);
+    if constexpr (RASTER) {
+      // padding positions have no token: their query rows are zero, as in a gathered copy (their lanes
+      // take part in the wave-wide rescale decisions, so what they hold is not quite without effect)
+      if (i * kBlock + qh * 32 + col >= Nv) {
+#pragma unroll
+        for (int t = 0; t < KSTEPS; ++t)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)0.0f;
+      }
+    }
   }
 
   f32x16 o[DSUB];
@@ -275,6 +360,11 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     const int j = jq[0];
     const int j_pre = jq[LEAD];
     const bool steady = decltype(steady_c)::value || n + LEAD < n_list;
+    if constexpr (RASTER) {
+      // per tile and wave: one order request (tile n+LEAD+2), then K (kDma), then V (kDma)
+      if (decltype(steady_c)::value || n + LEAD + 2 < n_list) issue_ord(jq[QD], n + LEAD + 2);
+      if (steady) read_ord(n + LEAD);
+    }
     if (steady) issue_k(j_pre, freed_v);  // item 2n-1+SLOTS = K(n+LEAD)
 
     // ---- S^T = K Q^T over this wave's 32 keys --------------------------------------------
@@ -301,21 +391,24 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     }
     // V(n) has landed; only the SLOTS-2 items requested after it may still be in flight (near the
     // end of the list fewer are, so the last LEAD tiles simply wait for everything)
-    if (steady)
-      __builtin_amdgcn_s_waitcnt(0x0f70 | ((kSlots - 2) * kDma));
+    // (raster mode: what this wave requested after V(n) is LEAD-1 whole tiles' worth of 2 kDma + 1
+    // requests plus this tile's order and K requests)
+    constexpr int kMidWait = RASTER ? (LEAD - 1) * (2 * kDma + 1) + kDma + 1 : (kSlots - 2) * kDma;
+    if (RASTER ? decltype(steady_c)::value : steady)  // raster: the request counts only hold in whole rounds
+      __builtin_amdgcn_s_waitcnt(0x0f70 | kMidWait);
     else
       __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();  // ... for every wave; and nobody reads K(n) any more
     if (steady) issue_v(j_pre, kslot);  // item 2n+SLOTS = V(n+LEAD) takes K(n)'s slot
     // block ids for the next iteration: shift the queue and append tile n+1+LEAD
 #pragma unroll
-    for (int t = 0; t < LEAD; ++t) jq[t] = jq[t + 1];
-    if (((n + 1 + LEAD) & 63) == 0) {  // next 64 entries; awaited right here (once per 64 tiles) so that
-      list_v = n + 1 + LEAD + lane < n_list ? list[n + 1 + LEAD + lane] : 0;  // the hot path carries no
-      __builtin_amdgcn_s_waitcnt(0x0f70);                                      // vector-memory wait
+    for (int t = 0; t < QD; ++t) jq[t] = jq[t + 1];
+    if (((n + 1 + QD) & 63) == 0) {  // next 64 entries; awaited right here (once per 64 tiles) so that
+      list_v = n + 1 + QD + lane < n_list ? list[n + 1 + QD + lane] : 0;  // the hot path carries no
+      __builtin_amdgcn_s_waitcnt(0x0f70);                                  // vector-memory wait
       asm volatile("" ::"v"(list_v));
     }
-    jq[LEAD] = list_at(n + 1 + LEAD);
+    jq[QD] = list_at(n + 1 + QD);
 
     // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
     if (j == partial_j) {
@@ -400,8 +493,9 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     }
 
     // K(n+1) has landed; again at most SLOTS-2 younger items are in flight
-    if (steady)
-      __builtin_amdgcn_s_waitcnt(0x0f70 | ((kSlots - 2) * kDma));
+    constexpr int kEndWait = RASTER ? (LEAD - 1) * (2 * kDma + 1) + kDma : (kSlots - 2) * kDma;
+    if (RASTER ? decltype(steady_c)::value : steady)
+      __builtin_amdgcn_s_waitcnt(0x0f70 | kEndWait);
     else
       __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();  // ... for every wave; and nobody reads V(n) any more
@@ -472,7 +566,14 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
         const float val = o[ds][r] * w0 + src[(ds * 16 + r) * 64] * w1;
         o[ds][r] = live ? val : 0.f;
       }
-    if (lse && g == 0) lse[head * (long long)nb * kBlock + token] = live ? (mm + p_shift + __log2f(lt)) * kLn2 : -INFINITY;
+    if (lse && g == 0) {
+      const float val = live ? (mm + p_shift + __log2f(lt)) * kLn2 : -INFINITY;
+      if constexpr (RASTER) {  // [B, Hh, Nv] in raster order; padded rows have no place there
+        if (token < Nv) lse[head * (long long)Nv + ras.order[token]] = val;
+      } else {
+        lse[head * (long long)nb * kBlock + token] = val;
+      }
+    }
     // every exchange value of this wave must be in registers before its area is overwritten
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     float* stage = xch + col * OSTRIDE;  // row (32 qh + col) of the block
@@ -505,20 +606,30 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
         val.z = fmaf(gf.z, val.z, gc.z * cz.z);
         val.w = fmaf(gf.w, val.w, gc.w * cz.w);
       }
+      void* dst;
+      if constexpr (RASTER) {
+        if (i * kBlock + row >= Nv) continue;  // the raster tensor has no padded rows
+        dst = static_cast<unsigned char*>(out) + ras_out + (long long)ras.order[i * kBlock + row] * ras.o_tok +
+              c4 * (OUT_F32 ? 4 : 2);
+      } else {
+        dst = OUT_F32 ? static_cast<void*>(static_cast<float*>(out) + blk_off + row * D + c4)
+                      : static_cast<void*>(static_cast<uint16_t*>(out) + blk_off + row * D + c4);
+      }
       if (OUT_F32) {
-        *reinterpret_cast<float4*>(static_cast<float*>(out) + blk_off + row * D + c4) = val;
+        *reinterpret_cast<float4*>(dst) = val;
       } else {
         bf16x4 pk;
         pk[0] = (__bf16)val.x; pk[1] = (__bf16)val.y; pk[2] = (__bf16)val.z; pk[3] = (__bf16)val.w;
-        *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(out) + blk_off + row * D + c4) = pk;
+        *reinterpret_cast<bf16x4*>(dst) = pk;
       }
     }
   }
 }
 
-template <int D, bool OUT_F32, int SLOTS, int WGS>
+template <int D, bool OUT_F32, int SLOTS, int WGS, bool RASTER = false>
 hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx, const int32_t* cnt,
-               int kmax, float scale, void* out, float* lse, const FuseArgs& fuse, hipStream_t st) {
+               int kmax, float scale, void* out, float* lse, const FuseArgs& fuse, hipStream_t st,
+               const RasterArgs& ras = RasterArgs{}) {
   const long long total = s.bh() * s.nb;
   const int per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
   const unsigned grid = (unsigned)per_xcd * kNumXcd;
@@ -530,8 +641,8 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
   auto Q = static_cast<const uint16_t*>(q);
   auto K = static_cast<const uint16_t*>(k);
   auto V = static_cast<const uint16_t*>(v);
-  attn_bf16<D, OUT_F32, SLOTS, WGS><<<grid, kThreads, 0, st>>>(Q, K, V, idx, cnt, out, lse, s.nb, s.Nv, kmax, sl2, p_shift,
-                                                    (int)total, per_xcd, fuse);
+  attn_bf16<D, OUT_F32, SLOTS, WGS, RASTER><<<grid, kThreads, 0, st>>>(Q, K, V, idx, cnt, out, lse, s.nb, s.Nv, kmax, sl2,
+                                                                     p_shift, (int)total, per_xcd, fuse, ras);
   return hipGetLastError();
 }
 
@@ -556,6 +667,22 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const D
   if (out_f32) USV_ATTN_CASE(64, true);
   USV_ATTN_CASE(64, false);
 #undef USV_ATTN_CASE
+}
+
+// Raster-order tensors: 3-slot ring, 2 workgroups per CU (the order ring takes the LDS that a 5-slot ring
+// would need for a second workgroup; the two shapes measured the same on cube-major inputs).
+hipError_t launch_attn_bf16_raster(const void* q, const void* k, const void* v, const Dims& s, const RasterArgs& ras,
+                                   const int32_t* idx, const int32_t* cnt, int kmax, float scale, void* out,
+                                   bool out_f32, float* lse, hipStream_t st) {
+  const FuseArgs none{nullptr, nullptr, nullptr};
+#define USV_RASTER_CASE(DD, F32) return run<DD, F32, 3, 2, true>(q, k, v, s, idx, cnt, kmax, scale, out, lse, none, st, ras)
+  if (s.d == 128) {
+    if (out_f32) USV_RASTER_CASE(128, true);
+    USV_RASTER_CASE(128, false);
+  }
+  if (out_f32) USV_RASTER_CASE(64, true);
+  USV_RASTER_CASE(64, false);
+#undef USV_RASTER_CASE
 }
 
 }  // namespace usv

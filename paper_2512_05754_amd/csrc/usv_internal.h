@@ -40,8 +40,7 @@ __device__ __forceinline__ int xcd_contiguous_id(int bid, int per_xcd) {
 }
 
 // launchers (each returns the hipError_t of its launches)
-hipError_t launch_block_scores(const void* q, const void* k, const Dims& s, float* scores, float* ws,
-                               hipStream_t st);
+
 hipError_t launch_select_topk(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax,
                               bool force_local, int32_t* idx, int32_t* cnt, hipStream_t st);
 hipError_t launch_pool_means(const void* x, const Dims& s, float* means, hipStream_t st);
@@ -59,11 +58,26 @@ struct FuseArgs {
   const uint16_t* gate_fine;
   const uint16_t* gate_coarse;
 };
+// Raster-order tensors for the attention and pooling kernels: order[p] = raster index of cube-major position p
+// (entries p >= Nv hold any valid index); strides in BYTES; the output has its own strides.
+struct RasterArgs {
+  const int32_t* order;
+  long long tok, head, batch;
+  long long o_tok, o_head, o_batch;
+  int Hh;
+};
+// ras == nullptr: cube-major Q, K
+hipError_t launch_block_scores(const void* q, const void* k, const Dims& s, float* scores, float* ws,
+                               hipStream_t st, const RasterArgs* ras = nullptr);
+hipError_t launch_attn_bf16_raster(const void* q, const void* k, const void* v, const Dims& s, const RasterArgs& ras,
+                                   const int32_t* idx, const int32_t* cnt, int kmax, float scale, void* out,
+                                   bool out_f32, float* lse, hipStream_t st);
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
                             const FuseArgs& fuse, hipStream_t st);
 
 // gather: raster -> cube-major (+ zeroed padding); else cube-major -> raster.  Strides of the raster tensor in BYTES.
+hipError_t launch_cube_order(int32_t* order, const CubeGrid& g, int N, int Nv, hipStream_t stream);
 hipError_t launch_cube_move(bool gather, const void* src, void* dst, const CubeGrid& g, const Dims& s, long long sb,
                             long long sh, long long st, hipStream_t stream);
 

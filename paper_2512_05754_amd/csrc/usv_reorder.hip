@@ -94,6 +94,18 @@ __global__ __launch_bounds__(CHUNKS >= 32 ? 512 : 256) void cube_move(const unsi
   }
 }
 
+// order[p] = raster index of the token at cube-major position p (p < Nv), 0 for the padding positions.
+__global__ __launch_bounds__(256) void cube_order(int32_t* __restrict__ order, CubeGrid g, int N, int Nv) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r < Nv) {
+    const int hw = g.H * g.W;
+    const int t = r / hw, rem = r - t * hw, h = rem / g.W, w = rem - h * g.W;
+    order[cube_position(g, t, h, w)] = r;
+  } else if (r < N) {
+    order[r] = 0;
+  }
+}
+
 template <bool GATHER, int CHUNKS>
 hipError_t run(const void* src, void* dst, const CubeGrid& g, const Dims& s, long long sb, long long sh, long long st,
                hipStream_t stream) {
@@ -117,6 +129,11 @@ hipError_t launch_cube_move(bool gather, const void* src, void* dst, const CubeG
   USV_MOVE_CASE(32);
 #undef USV_MOVE_CASE
   return hipErrorInvalidValue;  // unreachable: the API admits d in {64, 128}, bf16 or fp32
+}
+
+hipError_t launch_cube_order(int32_t* order, const CubeGrid& g, int N, int Nv, hipStream_t stream) {
+  cube_order<<<(unsigned)((N + 255) / 256), 256, 0, stream>>>(order, g, N, Nv);
+  return hipGetLastError();
 }
 
 }  // namespace usv

@@ -36,10 +36,11 @@ struct Vec16<uint16_t> {  // bf16 bit patterns
 };
 
 // grid = (B*Hh*nb, 2); blockIdx.y selects Q (0) or K (1).  One workgroup per cube.
-template <typename T, int D>
+// RASTER: the tensors are in raster token order; row r of cube i is token ras.order[64 i + r].
+template <typename T, int D, bool RASTER = false>
 __global__ __launch_bounds__(kPoolThreads) void pool_means(const T* __restrict__ q, const T* __restrict__ k,
                                                            float* __restrict__ ws, int nb, int Nv,
-                                                           long long mean_elems_per_tensor) {
+                                                           long long mean_elems_per_tensor, RasterArgs ras = RasterArgs{}) {
   constexpr int VEC = Vec16<T>::kElems;
   constexpr int LPR = D / VEC;              // lanes per token row
   constexpr int RPI = kPoolThreads / LPR;   // rows per iteration
@@ -49,6 +50,11 @@ __global__ __launch_bounds__(kPoolThreads) void pool_means(const T* __restrict__
   const long long blk = blockIdx.x;         // (b*Hh + h) * nb + i
   const int i = (int)(blk % nb);
   const T* src = (blockIdx.y == 0 ? q : k) + blk * (long long)kBlock * D;
+  const unsigned char* rbase = nullptr;
+  if constexpr (RASTER) {
+    const long long bh = blk / nb, b = bh / ras.Hh, h = bh - b * ras.Hh;
+    rbase = reinterpret_cast<const unsigned char*>(blockIdx.y == 0 ? q : k) + b * ras.batch + h * ras.head;
+  }
   float* dst = ws + (long long)blockIdx.y * mean_elems_per_tensor + blk * D;
   const int nvalid = min(kBlock, max(0, Nv - i * kBlock));
 
@@ -62,7 +68,10 @@ __global__ __launch_bounds__(kPoolThreads) void pool_means(const T* __restrict__
     const int r = r0 + it * RPI;
     if (r < nvalid) {
       float x[VEC];
-      Vec16<T>::load(src + (long long)r * D + c0, x);
+      if constexpr (RASTER)
+        Vec16<T>::load(reinterpret_cast<const T*>(rbase + (long long)ras.order[i * kBlock + r] * ras.tok) + c0, x);
+      else
+        Vec16<T>::load(src + (long long)r * D + c0, x);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) acc[e] += x[e];
     }
@@ -141,11 +150,16 @@ __global__ __launch_bounds__(256) void score_gemm(const float* __restrict__ qm, 
 }
 
 template <typename T, int D>
-hipError_t run(const void* q, const void* k, const Dims& s, float* scores, float* ws, hipStream_t st) {
+hipError_t run(const void* q, const void* k, const Dims& s, float* scores, float* ws, hipStream_t st,
+               const RasterArgs* ras = nullptr) {
   const long long cubes = s.bh() * s.nb;
   const long long mean_elems = cubes * D;
-  pool_means<T, D><<<dim3((unsigned)cubes, 2), kPoolThreads, 0, st>>>(
-      static_cast<const T*>(q), static_cast<const T*>(k), ws, s.nb, s.Nv, mean_elems);
+  if (ras)
+    pool_means<T, D, true><<<dim3((unsigned)cubes, 2), kPoolThreads, 0, st>>>(
+        static_cast<const T*>(q), static_cast<const T*>(k), ws, s.nb, s.Nv, mean_elems, *ras);
+  else
+    pool_means<T, D><<<dim3((unsigned)cubes, 2), kPoolThreads, 0, st>>>(
+        static_cast<const T*>(q), static_cast<const T*>(k), ws, s.nb, s.Nv, mean_elems);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int tiles = (s.nb + 63) / 64;
@@ -171,9 +185,10 @@ hipError_t launch_pool_means(const void* x, const Dims& s, float* means, hipStre
 }
 
 hipError_t launch_block_scores(const void* q, const void* k, const Dims& s, float* scores, float* ws,
-                               hipStream_t st) {
-  if (s.bf16) return s.d == 128 ? run<uint16_t, 128>(q, k, s, scores, ws, st) : run<uint16_t, 64>(q, k, s, scores, ws, st);
-  return s.d == 128 ? run<float, 128>(q, k, s, scores, ws, st) : run<float, 64>(q, k, s, scores, ws, st);
+                               hipStream_t st, const RasterArgs* ras) {
+  if (s.bf16)
+    return s.d == 128 ? run<uint16_t, 128>(q, k, s, scores, ws, st, ras) : run<uint16_t, 64>(q, k, s, scores, ws, st, ras);
+  return s.d == 128 ? run<float, 128>(q, k, s, scores, ws, st, ras) : run<float, 64>(q, k, s, scores, ws, st, ras);
 }
 
 }  // namespace usv

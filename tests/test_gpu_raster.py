@@ -1,0 +1,95 @@
+"""GPU parity of the raster-order entry points: the three stages on raster tensors must give what
+usv_cube_gather -> stage -> usv_cube_scatter gives (bit for bit: same arithmetic, only the addresses
+differ), and that in turn is checked against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as gu
+from oracle import usv_oracle as orc
+from paper_2512_05754_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def raster_inputs(w, grid, cube):
+    Qc, Kc, Vc = synth.gen_qkv(w)  # cube-major with the block structure; the raster tensors are their scatter
+    return tuple(orc.cube_scatter(x, grid, cube) for x in (Qc, Kc, Vc))
+
+
+CASES = [
+    ((5, 8, 12), (4, 4, 4), 1, 2, 128, 3),     # 480 tokens, cut cubes, ragged tail
+    ((4, 8, 8), (4, 4, 4), 2, 3, 128, 2),      # divisible grid, two batch elements
+    ((7, 9, 10), (4, 4, 4), 1, 2, 64, 4),      # d = 64
+    ((3, 12, 70), (1, 8, 8), 1, 1, 128, 30),   # flat cubes, lists longer than the request look-ahead
+    ((6, 20, 40), (4, 4, 4), 1, 1, 128, 70),   # lists longer than 64 entries (index reload)
+]
+
+
+@pytest.mark.parametrize("grid,cube,B,Hh,d,keep", CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_raster_path_equals_gather_path_and_oracle(usv, grid, cube, B, Hh, d, keep):
+    Nv = grid[0] * grid[1] * grid[2]
+    w = synth.Workload("raster", B, Hh, Nv, d, "bf16", 2.0, keep, seed=81 + d + keep)
+    Qr, Kr, Vr = raster_inputs(w, grid, cube)
+    q, k, v = gu.up(Qr), gu.up(Kr), gu.up(Vr)
+    N = w.seq_len
+    order = usv.cube_order(grid, cube, seq_len=N)
+    np.testing.assert_array_equal(order.cpu().numpy()[:Nv], orc.cube_token_order(grid, cube))
+    assert not order.cpu().numpy()[Nv:].any()
+    # reference path on the GPU: gather, three stages, scatter
+    qc, kc, vc = (usv.cube_gather(x, grid, cube, seq_len=N) for x in (q, k, v))
+    S_ref = usv.block_scores(qc, kc, seq_valid=Nv)
+    S = usv.block_scores_raster(q, k, order)
+    assert torch.equal(S, S_ref)
+    idx, cnt = usv.select_topk(S, k=keep, seq_valid=Nv)
+    for odt in (torch.float32, torch.bfloat16):
+        o_ref, lse_ref = usv.block_sparse_attn(qc, kc, vc, idx, cnt, seq_valid=Nv, out_dtype=odt, return_lse=True)
+        o_ref_r = usv.cube_scatter(o_ref, grid, cube)
+        out, lse = usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out_dtype=odt, return_lse=True)
+        assert torch.equal(out.view(torch.int32 if odt == torch.float32 else torch.int16),
+                           o_ref_r.view(torch.int32 if odt == torch.float32 else torch.int16))
+        lse_r = gu.down(lse_ref)[:, :, :Nv][:, :, np.argsort(orc.cube_token_order(grid, cube))]
+        np.testing.assert_array_equal(gu.down(lse), lse_r)
+    # and against the oracle
+    Qf, Kf, Vf = (orc.cube_gather(synth.as_f32(x), grid, cube, N) for x in (Qr, Kr, Vr))
+    ridx, rcnt = orc.select_topk(gu.down(S), keep, Nv)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
+    ref = orc.cube_scatter(orc.block_sparse_attn(Qf, Kf, Vf, ridx, rcnt, Nv)[0], grid, cube)
+    out = usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out_dtype=torch.float32)
+    gu.assert_attn_close(gu.down(out), ref, "bf16", False, "raster attention")
+
+
+def test_raster_path_on_projection_layout(usv):
+    """Q, K, V as one projection output [B, Nv, 3, Hh, d] (strided views) and the output written as [B, Nv, Hh*d]."""
+    grid, cube, B, Hh, d, keep = (5, 8, 12), (4, 4, 4), 2, 3, 128, 3
+    Nv = 480
+    w = synth.Workload("raster_proj", B, Hh, Nv, d, "bf16", 2.0, keep, seed=91)
+    Qr, Kr, Vr = raster_inputs(w, grid, cube)
+    qkv = torch.stack([gu.up(x) for x in (Qr, Kr, Vr)], dim=0)          # [3, B, Hh, Nv, d]
+    packed = qkv.permute(1, 3, 0, 2, 4).contiguous()                     # [B, Nv, 3, Hh, d]
+    q, k, v = (packed[:, :, t].permute(0, 2, 1, 3) for t in range(3))    # [B, Hh, Nv, d] views, token stride 3*Hh*d
+    order = usv.cube_order(grid, cube)
+    S = usv.block_scores_raster(q, k, order)
+    idx, cnt = usv.select_topk(S, k=keep, seq_valid=Nv)
+    buf = torch.zeros((B, Nv, Hh, d), dtype=torch.bfloat16, device=gu.DEV)
+    usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out=buf.permute(0, 2, 1, 3))
+    ref = usv.block_sparse_attn_raster(gu.up(Qr), gu.up(Kr), gu.up(Vr), order, idx, cnt)
+    assert torch.equal(buf.permute(0, 2, 1, 3).contiguous().view(torch.int16), ref.view(torch.int16))
+    assert torch.equal(S, usv.block_scores_raster(gu.up(Qr), gu.up(Kr), order))
+
+
+def test_raster_path_full_size_480p(usv):
+    """The 480p latent grid with all 12 heads: raster path against the gather path, bit for bit."""
+    grid, cube = (21, 30, 52), (4, 4, 4)
+    w = synth.WAN13_480P
+    Qr, Kr, Vr = raster_inputs(w, grid, cube)
+    q, k, v = gu.up(Qr), gu.up(Kr), gu.up(Vr)
+    order = usv.cube_order(grid, cube)
+    S = usv.block_scores_raster(q, k, order)
+    idx, cnt = usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid)
+    out = usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out_dtype=torch.float32)
+    qc, kc, vc = (usv.cube_gather(x, grid, cube) for x in (q, k, v))
+    assert torch.equal(S, usv.block_scores(qc, kc, seq_valid=w.seq_valid))
+    o_ref = usv.cube_scatter(usv.block_sparse_attn(qc, kc, vc, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32),
+                             grid, cube)
+    assert torch.equal(out.view(torch.int32), o_ref.view(torch.int32))
