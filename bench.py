@@ -41,12 +41,13 @@ def parse():
                     help="also run one plain 256 MiB device copy (untimed) so that a rocprofv3 --pmc run of this "
                          "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
-    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch", "merge"],
+    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch", "merge", "raster"],
                     help="attention: the three-stage hot path (the headline metric); reorder: the raster <-> "
                          "cube-major token reorder either side of it (gather Q, K, V + scatter O); two_branch: the "
                          "hot path with the local cube forced into every list, plus the cube-level branch and the "
                          "gated fusion of the two outputs; merge: token merging (similarity, plan, merge Q/K/V, "
-                         "unmerge O) with half of the tokens merged")
+                         "unmerge O) with half of the tokens merged; raster: the three-stage hot path on RASTER-order Q, K, V "
+                         "(usv_block_scores_raster, usv_select_topk, usv_block_sparse_attn_raster: no reordered copies)")
     ap.add_argument("--no-mfma-peak", action="store_true",
                     help="skip the MFMA-only peak probe (paper_2512_05754_amd/tools/mfma_peak, ~1 s)")
     return ap.parse_args()
@@ -340,6 +341,15 @@ def main():
     q, k, v = up(Q), up(K), up(V)
     budgets = None if w.keep else torch.from_numpy(synth.gen_budgets(w)).to(dev)
     two_branch = args.path == "two_branch"
+    raster = args.path == "raster"
+    if raster:
+        if w.name not in GRIDS:
+            print(f"bench.py: --path raster needs a workload with a latent grid ({sorted(GRIDS)})", file=sys.stderr)
+            sys.exit(2)
+        # the same tokens in raster order of the latent grid (the layout a DiT block's projections leave behind)
+        r_grid, r_cube = GRIDS[w.name], (4, 4, 4)
+        q, k, v = (usv.cube_scatter(x, r_grid, r_cube) for x in (q, k, v))
+        order = usv.cube_order(r_grid, r_cube, seq_len=w.seq_len)
     out_dtype = torch.float32 if (args.out_dtype == "f32" or w.dtype == "f32") else torch.bfloat16
 
     # every buffer is allocated once, outside the timed region
@@ -348,7 +358,7 @@ def main():
     ws = torch.empty(usv.workspace_bytes(B, Hh, N, w.seq_valid, d, w.dtype), dtype=torch.uint8, device=dev)
     idx = torch.empty((B, Hh, nb, kmax), dtype=torch.int32, device=dev)
     cnt = torch.empty((B, Hh, nb), dtype=torch.int32, device=dev)
-    out = torch.empty((B, Hh, N, d), dtype=out_dtype, device=dev)
+    out = torch.empty((B, Hh, w.seq_valid if raster else N, d), dtype=out_dtype, device=dev)
     if two_branch:
         gen = torch.Generator(device=dev).manual_seed(w.seed)
         gates = [torch.rand((B, Hh, N, d), device=dev, generator=gen).to(q.dtype) for _ in range(2)]
@@ -363,7 +373,10 @@ def main():
     def step(events=None):
         if events is not None:
             events[0].record()
-        usv.block_scores(q, k, seq_valid=w.seq_valid, out=S, workspace=ws)
+        if raster:
+            usv.block_scores_raster(q, k, order, out=S, workspace=ws)
+        else:
+            usv.block_scores(q, k, seq_valid=w.seq_valid, out=S, workspace=ws)
         if events is not None:
             events[1].record()
         usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, budgets=budgets, kmax=kmax, idx=idx, cnt=cnt,
@@ -379,6 +392,8 @@ def main():
                                   gate_fine=gates[0], gate_coarse=gates[1])
             if be is not None:
                 be[1].record()
+        elif raster:
+            usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out=out)
         else:
             usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=out)
         if events is not None:
@@ -456,6 +471,12 @@ def main():
             "avg_launch_ms": float(avg[2]),
         },
     }
+    if raster:
+        result["config"]["path"] = "raster"
+        result["config"]["grid"] = list(r_grid)
+        result["config"]["step"] = "usv_block_scores_raster + usv_select_topk + usv_block_sparse_attn_raster"
+        result["roofline"]["kernel"] = "usv_block_sparse_attn_raster (attn_bf16, raster addressing)"
+        result["roofline"]["traffic"] = measured_traffic("raster:" + w.name)
     if two_branch:
         c_ms = float(np.mean([evs[i][2].elapsed_time(branch_events[i][0]) for i in range(args.steps)]))
         a_ms = float(np.mean([branch_events[i][0].elapsed_time(branch_events[i][1]) for i in range(args.steps)]))
