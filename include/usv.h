@@ -125,8 +125,10 @@ usv_status usv_select_topk_ex(const float* scores, const usv_shape* shape, int32
  * q, k, v : [B, Hh, N, d] of shape->dtype (device, read only)
  * idx     : [B, Hh, nb, kmax] int32; row (b,h,i) holds cnt[b,h,i] DISTINCT block
  *           ids in [0, ceil(Nv/64)) in its first slots, in any order (ascending
- *           reads K/V most cache-friendly).  Not validated: an out-of-range id is
- *           undefined behaviour.
+ *           reads K/V most cache-friendly).  Device contents are not validated:
+ *           ids outside [0, nb) and counts outside [0, kmax] are clamped into
+ *           range, so no memory outside the tensors is touched, but the rows of
+ *           such a list hold unspecified values.
  * cnt     : [B, Hh, nb] int32, 0 <= cnt <= kmax
  * scale   : softmax scale; <= 0 selects 1/sqrt(d)
  * out_dtype : usv_dtype of `out`: shape->dtype, or USV_F32 for bf16 inputs (the

@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction; keep it scalar
   const int qh = wave & 1, kh = wave >> 1;
   const int col = lane & 31, g = lane >> 5;
-  const int n_list = cnt[work];
+  const int n_list = min(max(cnt[work], 0), kmax);  // device contents are not trusted with addresses:
   const int32_t* list = idx + (long long)work * kmax;
   const uint16_t* kbase = k + head_off;
   const uint16_t* vbase = v + head_off;
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   // The index list lives in a VGPR, 64 entries at a time (lane t holds entry 64*chunk + t), and is
   // read with v_readlane: one instruction per tile and no scalar-memory wait, which would also be
   // a wait for every LDS read in flight.
-  int list_v = lane < n_list ? list[lane] : 0;
+  int list_v = lane < n_list ? min(max(list[lane], 0), nb - 1) : 0;  // ... ids are clamped into [0, nb)
   auto list_at = [&](int n) { return __builtin_amdgcn_readlane(list_v, n & 63); };
 
   // ring item 2n = K(list[n]) -> slot (2n) % SLOTS, item 2n+1 = V(list[n]) -> slot (2n+1) % SLOTS;
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
 #pragma unroll
     for (int t = 0; t < QD; ++t) jq[t] = jq[t + 1];
     if (((n + 1 + QD) & 63) == 0) {  // next 64 entries; awaited right here (once per 64 tiles) so that
-      list_v = n + 1 + QD + lane < n_list ? list[n + 1 + QD + lane] : 0;  // the hot path carries no
+      list_v = n + 1 + QD + lane < n_list ? min(max(list[n + 1 + QD + lane], 0), nb - 1) : 0;  // the hot path carries no
       __builtin_amdgcn_s_waitcnt(0x0f70);                                  // vector-memory wait
       asm volatile("" ::"v"(list_v));
     }

@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void attn_f32(const float* __restrict__ q, con
   const int tid = threadIdx.x;
   const int r = tid >> 2, part = tid & 3;
   const int token = i * kBlock + r;
-  const int n_list = cnt[blk];
+  const int n_list = min(max(cnt[blk], 0), kmax);  // device contents are not trusted with addresses
 
   float qr[DP], o[DP];
   {
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void attn_f32(const float* __restrict__ q, con
   float m = -INFINITY, l = 0.f;
 
   for (int n = 0; n < n_list; ++n) {
-    const int j = idx[blk * kmax + n];
+    const int j = min(max(idx[blk * kmax + n], 0), nb - 1);
     const int nkeys = min(kBlock, Nv - j * kBlock);  // >= 1 for a listed block
     __syncthreads();                                  // previous tile fully consumed
     const float* kp = k + head_off + (long long)j * kBlock * D;

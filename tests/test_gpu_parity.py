@@ -216,6 +216,29 @@ def test_rows_sum_to_one_and_determinism(usv):
     assert torch.equal(S, S2)
 
 
+@pytest.mark.parametrize("w", [small_workloads()[1], small_workloads()[2]], ids=lambda w: w.name)
+def test_bad_list_contents_are_clamped_not_followed(usv, w):
+    """The kernels clamp block ids into [0, nb) and counts into [0, kmax] before they become addresses: rows
+    with a damaged list hold unspecified (finite or not) values, every other row is exactly what it was."""
+    rng = np.random.default_rng(23)
+    Q, K, V = synth.gen_qkv(w)
+    idx, cnt = arbitrary_lists(w, rng, 4)
+    q, k, v = gu.up(Q), gu.up(K), gu.up(V)
+    good = usv.block_sparse_attn(q, k, v, gu.up(idx), gu.up(cnt), seq_valid=w.seq_valid, out_dtype=torch.float32)
+    bad_idx, bad_cnt = idx.copy(), cnt.copy()
+    bad_idx[0, 0, 0, :] = [-7, w.nb, 1 << 30, -(1 << 31)][:bad_idx.shape[3]]   # ids far outside the tensors
+    bad_cnt[0, 0, 0] = bad_idx.shape[3]
+    bad_cnt[0, 1, 1] = bad_idx.shape[3] + 1000                                   # count beyond the row stride
+    bad_cnt[0, 1, 2] = -5
+    out = usv.block_sparse_attn(q, k, v, gu.up(bad_idx), gu.up(bad_cnt), seq_valid=w.seq_valid, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    keep = torch.ones(good.shape[:3], dtype=torch.bool, device=good.device)
+    keep[0, 0, 0:64] = False
+    keep[0, 1, 64:192] = False
+    assert torch.equal(out[keep], good[keep])
+    assert (out[0, 1, 128:192] == 0).all()  # a negative count is an empty list
+
+
 def test_outputs_do_not_spill_past_their_buffers(usv):
     """Canaries around scores, idx and out stay intact."""
     w = Workload("canary", 1, 2, 5 * 64 - 1, 128, "bf16", 2.0, 3, seed=61)
