@@ -148,6 +148,40 @@ def test_cube_move_rejects_null_and_misaligned_pointers():
     assert L.usv_cube_token_order(ctypes.byref(g), None) == 1
 
 
+def test_raster_entry_points_reject_bad_arguments_before_launch():
+    L = binding.lib()
+    name = lambda rc: L.usv_status_string(rc).decode()
+    sh = shape(seq_len=64, seq_valid=64, head_dim=128, dtype=binding.USV_BF16)
+    g = binding.UsvGrid(4, 4, 4, 4, 4, 4)
+    zero = binding.UsvStrides(0, 0, 0)
+    view = binding.UsvRaster(FAKE, zero, zero)
+    need = L.usv_workspace_bytes(ctypes.byref(sh))
+    bf16, f32 = binding.USV_BF16, binding.USV_F32
+    # usv_cube_order
+    assert name(L.usv_cube_order(ctypes.byref(sh), ctypes.byref(g), None, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_cube_order(ctypes.byref(sh), ctypes.byref(binding.UsvGrid(4, 4, 5, 4, 4, 4)), FAKE, None)) == "USV_ERR_INVALID_ARG"
+    # usv_block_scores_raster
+    assert name(L.usv_block_scores_raster(FAKE, FAKE, ctypes.byref(sh), None, FAKE, FAKE, need, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_block_scores_raster(FAKE, FAKE, ctypes.byref(sh), ctypes.byref(binding.UsvRaster(None, zero, zero)),
+                                          FAKE, FAKE, need, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_block_scores_raster(FAKE, FAKE, ctypes.byref(sh), ctypes.byref(view), FAKE, FAKE, need - 1, None)) == "USV_ERR_WORKSPACE"
+    short_rows = binding.UsvRaster(FAKE, binding.UsvStrides(2 * 64 * 128, 64 * 128, 64), zero)  # token stride < head_dim
+    assert name(L.usv_block_scores_raster(FAKE, FAKE, ctypes.byref(sh), ctypes.byref(short_rows), FAKE, FAKE, need, None)) == "USV_ERR_INVALID_ARG"
+    # usv_block_sparse_attn_raster
+    args = lambda shp, vw, kmax=1, od=bf16, scale=0.0, out=FAKE: L.usv_block_sparse_attn_raster(
+        FAKE, FAKE, FAKE, ctypes.byref(shp), ctypes.byref(vw), FAKE, FAKE, kmax, ctypes.c_float(scale), od, out, None, None)
+    assert name(args(shape(seq_len=64, seq_valid=64, head_dim=128), view)) == "USV_ERR_UNSUPPORTED"      # fp32 inputs
+    assert name(args(sh, view, od=7)) == "USV_ERR_UNSUPPORTED"
+    assert name(args(sh, view, kmax=0)) == "USV_ERR_INVALID_ARG"
+    assert name(args(sh, view, kmax=2)) == "USV_ERR_INVALID_ARG"                                          # kmax > blocks
+    assert name(args(sh, view, scale=float("inf"))) == "USV_ERR_INVALID_ARG"
+    assert name(args(sh, view, out=None)) == "USV_ERR_INVALID_ARG"
+    big = shape(seq_len=1 << 18, seq_valid=1 << 18, head_dim=128, dtype=bf16)                             # 2^18 tokens x 16 KiB rows
+    wide = binding.UsvRaster(FAKE, binding.UsvStrides(1 << 40, 128, 8192), zero)
+    assert name(args(big, wide)) == "USV_ERR_UNSUPPORTED"
+    assert b"2 GiB" in L.usv_last_error()
+
+
 # --------------------------------------------------------------------------- #
 # cube-level branch, fusion, selection flags
 # --------------------------------------------------------------------------- #
