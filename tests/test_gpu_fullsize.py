@@ -90,3 +90,11 @@ def test_merged_ragged_budgets(usv):
 
 def test_wan14_720p_keep5(usv):
     run_and_check(usv, synth.WAN14_720P, n_samples=36, check_all_topk=False)
+
+
+def test_maximum_supported_block_count(usv):
+    """USV_MAX_BLOCKS = 4096 blocks (262,144 tokens) in one head: the widest selection kernel (64 scores per lane),
+    the largest score matrix and the longest K/V tensors the index arithmetic has to address."""
+    w = synth.Workload("max_blocks", 1, 1, 4096 * 64 - 5, 64, "bf16", 2.0, 8, seed=404)
+    assert w.nb == 4096
+    run_and_check(usv, w, n_samples=6)
