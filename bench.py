@@ -48,6 +48,9 @@ def parse():
                          "gated fusion of the two outputs; merge: token merging (similarity, plan, merge Q/K/V, "
                          "unmerge O) with half of the tokens merged; raster: the three-stage hot path on RASTER-order Q, K, V "
                          "(usv_block_scores_raster, usv_select_topk, usv_block_sparse_attn_raster: no reordered copies)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (the three calls) in a HIP graph and time --steps replays of it; the per-stage "
+                         "times then come from a second, eager pass (attention and raster paths only)")
     ap.add_argument("--no-mfma-peak", action="store_true",
                     help="skip the MFMA-only peak probe (paper_2512_05754_amd/tools/mfma_peak, ~1 s)")
     return ap.parse_args()
@@ -418,11 +421,29 @@ def main():
     # timed region: exactly --steps passes; per-stage events are recorded on the launch stream
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        step(evs[s])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    if args.graph and not two_branch:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        for s in range(args.steps):  # eager pass for the per-stage times only
+            step(evs[s])
+        torch.cuda.synchronize()
+    else:
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            step(evs[s])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
 
     ms_step = wall * 1e3 / args.steps
     st_ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in evs])  # [steps, 3]; two_branch fixes [2] below
@@ -471,6 +492,8 @@ def main():
             "avg_launch_ms": float(avg[2]),
         },
     }
+    if args.graph and not two_branch:
+        result["config"]["launch"] = "hip graph replay (one graph = one step)"
     if raster:
         result["config"]["path"] = "raster"
         result["config"]["grid"] = list(r_grid)

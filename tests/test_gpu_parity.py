@@ -271,3 +271,50 @@ def test_errors_surface_as_exceptions(usv):
         usv.block_scores(torch.zeros(1, 1, 128, 96, device=gu.DEV), torch.zeros(1, 1, 128, 96, device=gu.DEV))
     with pytest.raises(usv.UsvError, match="USV_ERR_WORKSPACE"):
         usv.block_scores(x, x, workspace=torch.zeros(16, dtype=torch.uint8, device=gu.DEV))
+
+
+def test_three_stages_replay_from_a_hip_graph(usv):
+    """The calls only enqueue kernels on the caller's stream (no allocation, no memset, no host sync), so a
+    serving loop can capture them once and replay: every replay, with eager work and synchronisation in
+    between and fresh data in the captured buffers, must equal the eager result bit for bit."""
+    w = Workload("graph", 1, 2, 7 * 64 - 3, 128, "bf16", 2.0, 3, seed=71)
+    nb = w.nb
+    q, k, v = (torch.empty((1, 2, w.seq_len, 128), dtype=torch.bfloat16, device=gu.DEV) for _ in range(3))
+    S = torch.empty((1, 2, nb, nb), dtype=torch.float32, device=gu.DEV)
+    ws = torch.empty(usv.workspace_bytes(1, 2, w.seq_len, w.seq_valid, 128, "bf16"), dtype=torch.uint8, device=gu.DEV)
+    idx = torch.empty((1, 2, nb, 3), dtype=torch.int32, device=gu.DEV)
+    cnt = torch.empty((1, 2, nb), dtype=torch.int32, device=gu.DEV)
+    out = torch.empty((1, 2, w.seq_len, 128), dtype=torch.float32, device=gu.DEV)
+
+    def step():
+        usv.block_scores(q, k, seq_valid=w.seq_valid, out=S, workspace=ws)
+        usv.select_topk(S, k=3, seq_valid=w.seq_valid, idx=idx, cnt=cnt)
+        usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=out)
+
+    def load(seed):
+        Q, K, V = synth.gen_qkv(Workload("graph", 1, 2, w.seq_valid, 128, "bf16", 2.0, 3, seed=seed))
+        for dst, src in ((q, Q), (k, K), (v, V)):
+            dst.copy_(gu.up(src))
+
+    load(71)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up on the capture stream, as torch asks for
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for seed in (72, 73, 74):
+        load(seed)
+        step()                       # eager
+        torch.cuda.synchronize()
+        want = (S.clone(), idx.clone(), cnt.clone(), out.clone())
+        for t in (S, idx, cnt, out):
+            t.fill_(7)               # eager work between the replays; also proves the replay writes everything
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((S, idx, cnt, out), want):
+            assert torch.equal(got.view(torch.int32), ref.view(torch.int32))
