@@ -116,6 +116,32 @@ def test_pipeline_against_oracle(usv, w):
     assert (gu.down(out)[..., w.seq_valid:, :] == 0).all()
 
 
+DEGENERATE = [
+    Workload("one_token_bf16", 1, 1, 1, 128, "bf16", 2.0, 1, seed=31),        # a single valid token in a single block
+    Workload("one_token_f32", 2, 1, 1, 64, "f32", 0.0, 1, seed=32),
+    Workload("block_plus_one_bf16", 1, 2, 65, 64, "bf16", 2.0, 2, seed=33),   # second block holds one token
+    Workload("block_plus_one_f32", 1, 1, 65, 128, "f32", 2.0, 1, seed=34),
+    Workload("one_block_exact_bf16", 1, 1, 64, 128, "bf16", 2.0, 1, seed=35),  # no padding at all, one tile
+]
+
+
+@pytest.mark.parametrize("w", DEGENERATE, ids=lambda w: w.name)
+def test_degenerate_sizes_against_oracle(usv, w):
+    """The smallest shapes the ABI admits: one token, one block, a block with a single valid token."""
+    (Q, K, V), S, idx, cnt, out, lse = run_pipeline(usv, w, out_dtype=torch.float32)
+    Qf, Kf, Vf = (synth.as_f32(x) for x in (Q, K, V))
+    gu.assert_f32_close(S, orc.block_scores(Qf, Kf, w.seq_valid), w.name + " scores")
+    ridx, rcnt = orc.select_topk(S, w.keep, w.seq_valid)
+    assert np.array_equal(idx, ridx) and np.array_equal(cnt, rcnt)
+    O, L = orc.block_sparse_attn(Qf, Kf, Vf, ridx, rcnt, w.seq_valid)
+    gu.assert_attn_close(gu.down(out), O, w.dtype, False, w.name)
+    live = np.isfinite(L)
+    assert np.array_equal(np.isneginf(lse), ~live)
+    assert np.abs(lse[live] - L[live]).max() <= (1e-4 if w.dtype == "f32" else 2e-2)
+    if w.seq_valid == 1:  # softmax over one key: the output row is that key's value row
+        np.testing.assert_allclose(gu.down(out)[:, :, 0], Vf[:, :, 0], rtol=0, atol=1e-6)
+
+
 @pytest.mark.parametrize("w", [x for x in small_workloads() if x.dtype == "bf16"], ids=lambda w: w.name)
 def test_bf16_output_storage(usv, w):
     (Q, K, V), S, idx, cnt, out, _ = run_pipeline(usv, w)
