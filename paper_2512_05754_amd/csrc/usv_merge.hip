@@ -86,12 +86,12 @@ __global__ __launch_bounds__(256) void merge_descriptors(const T* __restrict__ k
     const T* src = k + ((long long)b * Hh * N + row) * D + c0;
     const long long hs = (long long)N * D;
     int h = 0;
-    for (; h + 4 <= Hh; h += 4) {  // four heads in flight
-      float x[4][VEC];
+    for (; h + 6 <= Hh; h += 6) {  // six heads in flight (twelve heads = two trips)
+      float x[6][VEC];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) Row<T>::load(src + (h + u) * hs, x[u]);
+      for (int u = 0; u < 6; ++u) Row<T>::load(src + (h + u) * hs, x[u]);
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 6; ++u)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] += x[u][e];
     }
@@ -377,7 +377,9 @@ __global__ __launch_bounds__(256) void merge_rows(const T* __restrict__ x, const
                                                   const int32_t* __restrict__ src_of, T* __restrict__ out, MergeGrid g,
                                                   int N, int Nm, int Np, int Hh) {
   constexpr int VEC = Row<T>::kElems, LPR = D / VEC, RPW = 256 / LPR;
-  const int b = blockIdx.z, h = blockIdx.y, p = blockIdx.x * RPW + threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * VEC;
+  // workgroups are dealt from the END of the merged sequence: the destination rows live there and cost several
+  // dependent reads each, so they start first and the cheap copy rows fill in behind them
+  const int b = blockIdx.z, h = blockIdx.y, p = (gridDim.x - 1 - blockIdx.x) * RPW + threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * VEC;
   if (p >= Np) return;
   float acc[VEC];
 #pragma unroll
@@ -392,18 +394,41 @@ __global__ __launch_bounds__(256) void merge_rows(const T* __restrict__ x, const
       const int32_t* ro = row_of + (long long)b * N;
       const int et = min(g.st, g.T - c.t), eh = min(g.sh, g.H - c.h), ew = min(g.sw, g.W - c.w);
       int count = 1;
-      for (int lt = 0; lt < et; ++lt)
-        for (int lh = 0; lh < eh; ++lh)
-          for (int lw = 0; lw < ew; ++lw) {
-            const int k = ((c.t + lt) * g.H + c.h + lh) * g.W + c.w + lw;
-            if (k != s && ro[k] == p) {
-              float v[VEC];
-              Row<T>::load(xb + (long long)k * D, v);
+      if (g.st == 2 && g.sh == 2 && g.sw == 2) {
+        // the usual 2x2x2 block: the seven look-ups are in flight together, then the row loads they select
+        // (same order of additions as the general loop)
+        int kk[8], rk[8];
 #pragma unroll
-              for (int e = 0; e < VEC; ++e) acc[e] += v[e];
-              ++count;
-            }
+        for (int q = 1; q < 8; ++q) {
+          const int lw = q & 1, lh = (q >> 1) & 1, lt = q >> 2;
+          kk[q] = ((c.t + lt) * g.H + c.h + lh) * g.W + c.w + lw;
+          rk[q] = (lt < et && lh < eh && lw < ew) ? ro[kk[q]] : -1;
+        }
+        float v[8][VEC];
+#pragma unroll
+        for (int q = 1; q < 8; ++q)
+          if (rk[q] == p) Row<T>::load(xb + (long long)kk[q] * D, v[q]);
+#pragma unroll
+        for (int q = 1; q < 8; ++q)
+          if (rk[q] == p) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += v[q][e];
+            ++count;
           }
+      } else {
+        for (int lt = 0; lt < et; ++lt)
+          for (int lh = 0; lh < eh; ++lh)
+            for (int lw = 0; lw < ew; ++lw) {
+              const int k = ((c.t + lt) * g.H + c.h + lh) * g.W + c.w + lw;
+              if (k != s && ro[k] == p) {
+                float v[VEC];
+                Row<T>::load(xb + (long long)k * D, v);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] += v[e];
+                ++count;
+              }
+            }
+      }
       if (count > 1) {
         const float inv = 1.0f / (float)count;
 #pragma unroll
