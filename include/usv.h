@@ -104,8 +104,8 @@ usv_status usv_select_topk(const float* scores, const usv_shape* shape, int32_t 
                            void* stream);
 
 /* usv_select_topk with options.  flags = 0 is usv_select_topk itself.
- * USV_TOPK_FORCE_LOCAL (Figure 2, right: the budget is split between "local cube
- * attention" and "long-range sparse attention"): a row that keeps anything keeps
+ * USV_TOPK_FORCE_LOCAL (Figure 2, right: the budget is split between attention inside
+ * the local cube and sparse attention to far-away cubes): a row that keeps anything keeps
  * its OWN cube i, and fills the rest of its budget with the best other cubes in
  * the order above.  The paper gives no rule for the split; this reading spends
  * one block of the budget on the local cube. */
@@ -118,8 +118,8 @@ usv_status usv_select_topk_ex(const float* scores, const usv_shape* shape, int32
  * Stage 3 - block-sparse attention: the masked-attention equation of Section 3.2,
  *   out = softmax(Q K^T * scale + log M) V,
  * with M[r, c] = 1 iff block(c) is listed for block(r) and c < seq_valid.
- * Only the listed K/V blocks are read ("dense attention only within selected
- * tiles", Section 2.2).  With every block listed this is the dense-attention
+ * Only the listed K/V blocks are read (Section 2.2: attention is dense inside the
+ * selected tiles and absent elsewhere).  With every block listed this is the dense-attention
  * equation of the same section.
  *
  * q, k, v : [B, Hh, N, d] of shape->dtype (device, read only)
@@ -225,8 +225,8 @@ usv_status usv_entropy_allocate(const float* entropy, int32_t layers, float rho_
 
 /*
  * Either side of the three stages: the token order (Figure 2, right: queries, keys
- * and values are "partitioned into local 3D cubes"; the outputs are "broadcast back
- * to the full token grid").  A model holds tokens in raster order of the latent
+ * and values are split into small 3-D cubes, and the outputs are spread over the whole
+ * token grid again).  A model holds tokens in raster order of the latent
  * grid, index (t*H + h)*W + w; the stages above want cube-major order.
  *
  * Cube-major order of a T x H x W grid tiled by ct x ch x cw cubes (ct*ch*cw = 64):

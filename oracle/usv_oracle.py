@@ -23,9 +23,9 @@ description; Figure 2's "top-k cube selection"):
   dense_attn        softmax(Q K^T / sqrt(d_k)) V, the keep-all limit.
 
   cube_token_order / cube_gather / cube_scatter
-                    the step either side of the path (Figure 2, right: tokens are
-                    "partitioned into local 3D cubes" on the way in and "broadcast
-                    back to the full token grid" on the way out): the permutation
+                    the step either side of the path (Figure 2, right: the tokens are
+                    split into small 3-D cubes on the way in, and the results are
+                    spread over the whole token grid again on the way out): the permutation
                     between raster (t, h, w) token order and cube-major order.
 
   coarse_attn / fuse_outputs
@@ -67,7 +67,7 @@ Readings taken where the paper is silent:
   * coarse branch (the cube level of the coarse-to-fine scheme, Section 2.2): attention
     among the pooled cubes, C_i = sum_j softmax_j(S_ij) mean(V_j) over the cubes that hold
     a valid token, with S the stage-1 scores (they already carry the 1/sqrt(d)).
-  * fusion ("broadcast back to the full token grid, and fused"): every token r of cube i
+  * fusion (Figure 2 only says that the branch outputs are spread over the token grid and combined): every token r of cube i
     receives C_i; out_r = g_fine[r] * O_fine[r] + g_coarse[r] * C_cube(r), elementwise, with
     per-token, per-channel gates supplied by the model (absent gate = 1).
   * attention entropy: the paper takes the marginal of the full N x N attention weights,
@@ -78,8 +78,8 @@ Readings taken where the paper is silent:
   * token merging: tokens are in raster order of the T x H x W grid; the merge blocks
     (s_t, s_h, s_w) tile the grid from the origin and are cut by its boundary; the
     destination of a block is its first token (local coordinates 0,0,0), every other token
-    of the block is a source.  "Sources and destinations are restricted to local 3D blocks":
-    the only candidate destination of a source is the one of its own block, so j*(i) is that
+    of the block is a source.  Section 3.3 confines sources and destinations to the same local 3-D
+    block: the only candidate destination of a source is the one of its own block, so j*(i) is that
     token and u_i their cosine similarity (a zero descriptor gives similarity 0).  The r
     selected sources are the first r in the order (u descending, raster index ascending);
     on canonical values as in the top-k selection (-0 equals +0, NaN ranks lowest); the merged
@@ -153,7 +153,7 @@ def select_topk(S, k, seq_valid, budgets=None, kmax=None, block=BLOCK, force_loc
 
     A row keeps min(budget, kmax, nb_valid) blocks where budget = budgets[b,h,i] if given else k.
     Query blocks with no valid token keep nothing.
-    force_local (Figure 2, right: part of the budget goes to "local cube attention"): a row that
+    force_local (Figure 2, right: part of the budget goes to attention inside the local cube): a row that
     keeps anything keeps its own cube i, and fills the rest of its budget with the best OTHER cubes."""
     B, Hh, nb, _ = S.shape
     nb_valid = (seq_valid + block - 1) // block

@@ -1,5 +1,6 @@
-// Cube-level branch and output fusion (paper Figure 2, right: the outputs are "broadcast back to the
-// full token grid, and fused"; Section 2.2: the coarse level of the coarse-to-fine scheme).
+// Cube-level branch and output fusion (paper Figure 2, right: the cube-level result is spread over the
+// tokens of the grid again and combined with the token-level one; Section 2.2: the coarse level of the
+// coarse-to-fine scheme).
 //
 //   coarse_attn   C[bh, i, :] = sum_j softmax_j(S[bh, i, :])_j * Vm[bh, j, :] over the cubes that hold a
 //                 valid token; S are the stage-1 scores, Vm the pooled fp32 means of V.  Two passes over
