@@ -2,7 +2,8 @@
 //
 // One 64-lane wavefront owns one score row.  The row lives in registers (element e*64+lane in
 // slot e), mapped to order-preserving unsigned keys.  The k-th largest key is found by a
-// bit-by-bit search from the most significant bit (each step is a compare + wave-wide count),
+// bit-by-bit search from the most significant bit (each step is a per-lane compare-and-count plus
+// one wave-wide sum),
 // which makes the result a pure function of the (key, index) total order: bit-exact and free of
 // atomics.  Ties at the threshold are broken towards the lower block index with ballot prefix
 // counts, and the survivors are written in ascending block index in one more pass.
@@ -21,7 +22,22 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-__device__ __forceinline__ int wave_count(bool p) { return __popcll(__ballot(p)); }
+// Sum of a per-lane count over the 64 lanes, as a wave-uniform value: four DPP adds leave every 16-lane row's
+// total in all of its lanes (pairs, quads, then the row rotated by 4 and by 8), and the four row totals are
+// read back with v_readlane.  No LDS, no ballots.
+__device__ __forceinline__ int wave_sum(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x124, 0xf, 0xf, false);  // row_ror:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false);  // row_ror:8
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+         __builtin_amdgcn_readlane(v, 48);
+}
+
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ int lanes_below(unsigned long long mask) {
+  return __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+}
 
 template <int EPL>  // elements per lane: row length <= 64 * EPL
 __global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __restrict__ scores,
@@ -38,30 +54,38 @@ __global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __re
   int want = budgets ? budgets[row] : k_uniform;
   want = max(0, min(want, min(kmax, nb_valid)));
   if (i >= nb_valid) want = 0;
+  want = __builtin_amdgcn_readfirstlane(want);  // the same in every lane; keep the search loop scalar
 
   if (want > 0) {
     const float* src = scores + row * nb;
+    // every load of the row is in flight at once (slots past the row re-read its last score and are
+    // overwritten below)
+    float x[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) x[e] = src[min(e * 64 + lane, nb - 1)];
     uint32_t key[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
       const int j = e * 64 + lane;
       // slots beyond the valid blocks get the lowest key; `want <= nb_valid` and the index
       // tie-break keep them out of the result
-      key[e] = j < nb_valid ? order_key(src[j]) : 0u;
+      key[e] = j < nb_valid ? order_key(x[e]) : 0u;
       // local-cube allocation: the row's own cube gets a key above every score (order_key never
       // returns 0xffffffff), so it is kept first and the rest of the budget goes to the best others
       if (force_local && j == i) key[e] = 0xffffffffu;
     }
-    // threshold = the want-th largest key among the valid slots.  The search stops as soon as a
-    // candidate splits off exactly `want` keys: they are the answer whatever the lower bits are
-    // (with distinct scores that happens after a dozen bits or so, not 32).
+    // threshold = the want-th largest key among the valid slots.  Every candidate is >= 1, so the slots
+    // beyond the valid blocks (key 0) never count.  The search stops as soon as a candidate splits off
+    // exactly `want` keys: they are the answer whatever the lower bits are (with distinct scores that
+    // happens after a dozen bits or so, not 32).
     uint32_t thr = 0u;
     bool exact = false;
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = thr | (1u << bit);
       int c = 0;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) c += wave_count(e * 64 + lane < nb_valid && key[e] >= cand);
+      for (int e = 0; e < EPL; ++e) c += key[e] >= cand ? 1 : 0;
+      c = wave_sum(c);
       if (c >= want) thr = cand;
       if (c == want) {  // wave-uniform
         exact = true;
@@ -77,11 +101,10 @@ __global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __re
     } else {
       int greater = 0;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) greater += wave_count(e * 64 + lane < nb_valid && key[e] > thr);
-      need_eq = want - greater;  // >= 1 by construction
+      for (int e = 0; e < EPL; ++e) greater += (e * 64 + lane < nb_valid && key[e] > thr) ? 1 : 0;
+      need_eq = want - wave_sum(greater);  // >= 1 by construction
     }
 
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int out_base = 0, eq_base = 0;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
@@ -89,10 +112,10 @@ __global__ __launch_bounds__(64 * kRowsPerWg) void select_topk(const float* __re
       const bool valid = j < nb_valid;
       const bool gt = valid && key[e] > thr;
       const bool eq = valid && key[e] == thr;
-      const unsigned long long eq_b = __ballot(eq);
-      const bool take = gt || (eq && eq_base + __popcll(eq_b & lt_mask) < need_eq);
-      const unsigned long long take_b = __ballot(take);
-      if (take) out[out_base + __popcll(take_b & lt_mask)] = j;
+      const unsigned long long eq_b = __builtin_amdgcn_ballot_w64(eq);
+      const bool take = gt || (eq && eq_base + lanes_below(eq_b) < need_eq);
+      const unsigned long long take_b = __builtin_amdgcn_ballot_w64(take);
+      if (take) out[out_base + lanes_below(take_b)] = j;
       out_base += __popcll(take_b);
       eq_base += __popcll(eq_b);
     }
