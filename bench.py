@@ -41,13 +41,14 @@ def parse():
                     help="also run one plain 256 MiB device copy (untimed) so that a rocprofv3 --pmc run of this "
                          "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
-    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch", "merge", "raster"],
+    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch", "merge", "raster", "raster_two_branch"],
                     help="attention: the three-stage hot path (the headline metric); reorder: the raster <-> "
                          "cube-major token reorder either side of it (gather Q, K, V + scatter O); two_branch: the "
                          "hot path with the local cube forced into every list, plus the cube-level branch and the "
                          "gated fusion of the two outputs; merge: token merging (similarity, plan, merge Q/K/V, "
                          "unmerge O) with half of the tokens merged; raster: the three-stage hot path on RASTER-order Q, K, V "
-                         "(usv_block_scores_raster, usv_select_topk, usv_block_sparse_attn_raster: no reordered copies)")
+                         "(usv_block_scores_raster, usv_select_topk, usv_block_sparse_attn_raster: no reordered copies); "
+                         "raster_two_branch: the two_branch path on raster-order tensors")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (the three calls) in a HIP graph and time --steps replays of it; the per-stage "
                          "times then come from a second, eager pass (attention and raster paths only)")
@@ -343,8 +344,8 @@ def main():
 
     q, k, v = up(Q), up(K), up(V)
     budgets = None if w.keep else torch.from_numpy(synth.gen_budgets(w)).to(dev)
-    two_branch = args.path == "two_branch"
-    raster = args.path == "raster"
+    two_branch = args.path in ("two_branch", "raster_two_branch")
+    raster = args.path in ("raster", "raster_two_branch")
     if raster:
         if w.name not in GRIDS:
             print(f"bench.py: --path raster needs a workload with a latent grid ({sorted(GRIDS)})", file=sys.stderr)
@@ -364,10 +365,10 @@ def main():
     out = torch.empty((B, Hh, w.seq_valid if raster else N, d), dtype=out_dtype, device=dev)
     if two_branch:
         gen = torch.Generator(device=dev).manual_seed(w.seed)
-        gates = [torch.rand((B, Hh, N, d), device=dev, generator=gen).to(q.dtype) for _ in range(2)]
+        gates = [torch.rand((B, Hh, w.seq_valid if raster else N, d), device=dev, generator=gen).to(q.dtype) for _ in range(2)]
         coarse = torch.empty((B, Hh, nb, d), dtype=torch.float32, device=dev)
         ws_c = torch.empty(B * Hh * nb * d * 4, dtype=torch.uint8, device=dev)
-        fused = torch.empty((B, Hh, N, d), dtype=q.dtype, device=dev)
+        fused = torch.empty((B, Hh, w.seq_valid if raster else N, d), dtype=q.dtype, device=dev)
         ent = torch.empty((B,), dtype=torch.float32, device=dev)
         ws_e = torch.empty(B * Hh * ((nb + 31) // 32) * nb * 4, dtype=torch.uint8, device=dev)
         branch_events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -388,11 +389,18 @@ def main():
             events[2].record()
         if two_branch:  # the cube-level branch first: the attention kernel folds it and the gates into its store
             be = branch_events[step_no[0]] if events is not None else None
-            usv.coarse_attn(S, v, seq_valid=w.seq_valid, out=coarse, workspace=ws_c)
+            if raster:
+                usv.coarse_attn_raster(S, v, order, out=coarse, workspace=ws_c)
+            else:
+                usv.coarse_attn(S, v, seq_valid=w.seq_valid, out=coarse, workspace=ws_c)
             if be is not None:
                 be[0].record()
-            usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=fused, coarse=coarse,
-                                  gate_fine=gates[0], gate_coarse=gates[1])
+            if raster:
+                usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out=fused, coarse=coarse,
+                                             gate_fine=gates[0], gate_coarse=gates[1])
+            else:
+                usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=fused, coarse=coarse,
+                                      gate_fine=gates[0], gate_coarse=gates[1])
             if be is not None:
                 be[1].record()
         elif raster:
@@ -497,7 +505,9 @@ def main():
     if raster:
         result["config"]["path"] = "raster"
         result["config"]["grid"] = list(r_grid)
-        result["config"]["step"] = "usv_block_scores_raster + usv_select_topk + usv_block_sparse_attn_raster"
+        result["config"]["step"] = ("usv_block_scores_raster + usv_select_topk + usv_block_sparse_attn_raster" if not two_branch else
+                                    "usv_block_scores_raster + usv_select_topk_ex + usv_coarse_attn_raster + "
+                                    "usv_block_sparse_attn_raster_fused + usv_attn_entropy")
         result["roofline"]["kernel"] = "usv_block_sparse_attn_raster (attn_bf16, raster addressing)"
         result["roofline"]["traffic"] = measured_traffic("raster:" + w.name)
     if two_branch:
@@ -514,7 +524,7 @@ def main():
         result["stages_ms"]["attn_entropy"] = e_ms
         result["stage_hbm_gbs"]["attn_entropy"] = B * Hh * nb * nb * 4 / (e_ms * 1e-3) / 1e9
         result["config"]["attn_entropy"] = [float(x) for x in ent.cpu()]
-        result["config"]["path"] = "two_branch"
+        result["config"]["path"] = args.path
         result["stages_ms"]["coarse_attn"] = c_ms
         bytes_coarse = B * Hh * (N * d * esz + 2 * nb * nb * 4 + 3 * nb * d * 4)  # V once, S twice, means + output
         result["stage_hbm_gbs"]["coarse_attn"] = bytes_coarse / (c_ms * 1e-3) / 1e9

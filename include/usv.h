@@ -312,6 +312,23 @@ usv_status usv_block_sparse_attn_raster(const void* q, const void* k, const void
                                         float scale, int32_t out_dtype, void* out, float* lse,
                                         void* stream);
 
+/* The second branch on raster-order tensors.
+ * usv_coarse_attn_raster: usv_coarse_attn with v laid out by view->in_strides (any
+ *   dtype usv_coarse_attn takes); coarse is [B, Hh, nb, d] fp32 as there.
+ * usv_block_sparse_attn_raster_fused: usv_block_sparse_attn_fused on raster tensors
+ *   (bf16 only); gate_fine and gate_coarse, where given, are raster-order bf16
+ *   tensors laid out like q (view->in_strides).  Same results as gathering every
+ *   tensor, calling the cube-major entry point and scattering the output. */
+usv_status usv_coarse_attn_raster(const float* scores, const void* v, const usv_shape* shape,
+                                  const usv_raster* view, float* coarse, void* ws, size_t ws_bytes,
+                                  void* stream);
+usv_status usv_block_sparse_attn_raster_fused(const void* q, const void* k, const void* v,
+                                              const usv_shape* shape, const usv_raster* view,
+                                              const int32_t* idx, const int32_t* cnt, int32_t kmax,
+                                              float scale, const float* coarse, const void* gate_fine,
+                                              const void* gate_coarse, int32_t out_dtype, void* out,
+                                              float* lse, void* stream);
+
 /*
  * Token merging (Section 3.3, "Token merging for video").  Tokens are in RASTER
  * order of the T x H x W grid.  The grid is tiled from the origin by merge blocks

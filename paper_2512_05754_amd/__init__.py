@@ -19,6 +19,7 @@ _BINDING_NAMES = (
     "cube_order",
     "block_scores_raster",
     "block_sparse_attn_raster",
+    "coarse_attn_raster",
     "cube_token_order",
     "cube_gather",
     "cube_scatter",

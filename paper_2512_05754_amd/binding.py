@@ -36,6 +36,8 @@ EXPORTED_SYMBOLS = (
     "usv_cube_order",
     "usv_block_scores_raster",
     "usv_block_sparse_attn_raster",
+    "usv_coarse_attn_raster",
+    "usv_block_sparse_attn_raster_fused",
     "usv_cube_token_order",
     "usv_cube_gather",
     "usv_cube_scatter",
@@ -125,6 +127,9 @@ def lib() -> ctypes.CDLL:
     L.usv_block_scores_raster.restype, L.usv_block_scores_raster.argtypes = i32, [vp, vp, sp, rp, vp, vp, sz, vp]
     L.usv_block_sparse_attn_raster.restype = i32
     L.usv_block_sparse_attn_raster.argtypes = [vp, vp, vp, sp, rp, vp, vp, i32, f32, i32, vp, vp, vp]
+    L.usv_coarse_attn_raster.restype, L.usv_coarse_attn_raster.argtypes = i32, [vp, vp, sp, rp, vp, vp, sz, vp]
+    L.usv_block_sparse_attn_raster_fused.restype = i32
+    L.usv_block_sparse_attn_raster_fused.argtypes = [vp, vp, vp, sp, rp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, vp]
     L.usv_status_string.restype, L.usv_status_string.argtypes = ctypes.c_char_p, [i32]
     L.usv_last_error.restype, L.usv_last_error.argtypes = ctypes.c_char_p, []
     _lib = L
@@ -490,8 +495,30 @@ def block_scores_raster(q, k, order, out=None, workspace=None):
     return out
 
 
-def block_sparse_attn_raster(q, k, v, order, idx, cnt, scale=0.0, out=None, out_dtype=None, return_lse=False):
-    """usv_block_sparse_attn_raster: raster-ordered q, k, v [B, Hh, Nv, d] -> out [B, Hh, Nv, d] in raster order."""
+def coarse_attn_raster(scores, v, order, out=None, workspace=None):
+    """usv_coarse_attn_raster: usv_coarse_attn with v in raster order [B, Hh, Nv, d] (strided views allowed)."""
+    sh = _raster_shape(v, order)
+    vp_, st = _raster(v, "v")
+    nb = sh.seq_len // BLOCK
+    if tuple(scores.shape) != (sh.batch, sh.heads, nb, nb):
+        raise ValueError("scores must be [B, Hh, nb, nb]")
+    if out is None:
+        out = torch.empty((sh.batch, sh.heads, nb, sh.head_dim), dtype=torch.float32, device=v.device)
+    need = int(lib().usv_coarse_workspace_bytes(ctypes.byref(sh)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=v.device)
+    view = UsvRaster(_dev(order, "order", torch.int32), st, UsvStrides(0, 0, 0))
+    _check(lib().usv_coarse_attn_raster(_dev(scores, "scores", torch.float32), vp_, ctypes.byref(sh), ctypes.byref(view),
+                                        _dev(out, "coarse", torch.float32), _dev(workspace, "workspace"),
+                                        workspace.numel() * workspace.element_size(), _stream()))
+    return out
+
+
+def block_sparse_attn_raster(q, k, v, order, idx, cnt, scale=0.0, out=None, out_dtype=None, return_lse=False,
+                             coarse=None, gate_fine=None, gate_coarse=None):
+    """usv_block_sparse_attn_raster(_fused): raster-ordered q, k, v [B, Hh, Nv, d] -> out [B, Hh, Nv, d] in raster order.
+
+    coarse (+ optional raster-order gates laid out like q): out = gate_fine * attention + gate_coarse * coarse[cube]."""
     sh = _raster_shape(q, order)
     ptrs = []
     st = None
@@ -507,7 +534,17 @@ def block_sparse_attn_raster(q, k, v, order, idx, cnt, scale=0.0, out=None, out_
     op, ost = _raster(out, "out")
     lse = torch.empty((sh.batch, sh.heads, sh.seq_valid), dtype=torch.float32, device=q.device) if return_lse else None
     view = UsvRaster(_dev(order, "order", torch.int32), st, ost)
-    _check(lib().usv_block_sparse_attn_raster(*ptrs, ctypes.byref(sh), ctypes.byref(view), _dev(idx, "idx", torch.int32),
-                                              _dev(cnt, "cnt", torch.int32), int(idx.shape[3]), float(scale), _dt(out), op,
-                                              None if lse is None else _dev(lse, "lse", torch.float32), _stream()))
+    gates = []
+    for name, g_ in (("gate_fine", gate_fine), ("gate_coarse", gate_coarse)):
+        if g_ is None:
+            gates.append(None)
+            continue
+        gp_, gst = _raster(g_, name)
+        if (gst.batch, gst.head, gst.token) != (st.batch, st.head, st.token) or g_.dtype != q.dtype or g_.shape != q.shape:
+            raise ValueError(f"{name} must match q in shape, strides and dtype")
+        gates.append(gp_)
+    _check(lib().usv_block_sparse_attn_raster_fused(
+        *ptrs, ctypes.byref(sh), ctypes.byref(view), _dev(idx, "idx", torch.int32), _dev(cnt, "cnt", torch.int32),
+        int(idx.shape[3]), float(scale), None if coarse is None else _dev(coarse, "coarse", torch.float32), gates[0],
+        gates[1], _dt(out), op, None if lse is None else _dev(lse, "lse", torch.float32), _stream()))
     return (out, lse) if return_lse else out

@@ -412,6 +412,33 @@ usv_status usv_block_scores_raster(const void* q, const void* k, const usv_shape
 usv_status usv_block_sparse_attn_raster(const void* q, const void* k, const void* v, const usv_shape* shape,
                                         const usv_raster* view, const int32_t* idx, const int32_t* cnt, int32_t kmax,
                                         float scale, int32_t out_dtype, void* out, float* lse, void* stream) {
+  return usv_block_sparse_attn_raster_fused(q, k, v, shape, view, idx, cnt, kmax, scale, nullptr, nullptr, nullptr,
+                                            out_dtype, out, lse, stream);
+}
+
+usv_status usv_coarse_attn_raster(const float* scores, const void* v, const usv_shape* shape, const usv_raster* view,
+                                  float* coarse, void* ws, size_t ws_bytes, void* stream) {
+  usv::Dims s;
+  usv::RasterArgs ras;
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_raster(view, s, s.bf16 ? 2 : 4, &ras));
+  USV_TRY(check_ptr(scores, "scores"));
+  USV_TRY(check_ptr(v, "v"));
+  USV_TRY(check_ptr(coarse, "coarse"));
+  const size_t need = usv_coarse_workspace_bytes(shape);
+  if (!ws || !aligned16(ws) || ws_bytes < need)
+    return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = usv::launch_pool_means(v, s, static_cast<float*>(ws), st, &ras);
+  if (e == hipSuccess) e = usv::launch_coarse_attn(scores, static_cast<const float*>(ws), s, coarse, st);
+  return hip_result(e, "usv_coarse_attn_raster launch");
+}
+
+usv_status usv_block_sparse_attn_raster_fused(const void* q, const void* k, const void* v, const usv_shape* shape,
+                                              const usv_raster* view, const int32_t* idx, const int32_t* cnt,
+                                              int32_t kmax, float scale, const float* coarse, const void* gate_fine,
+                                              const void* gate_coarse, int32_t out_dtype, void* out, float* lse,
+                                              void* stream) {
   usv::Dims s;
   usv::RasterArgs ras;
   USV_TRY(check_shape(shape, true, &s));
@@ -427,9 +454,14 @@ usv_status usv_block_sparse_attn_raster(const void* q, const void* k, const void
   if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return fail(USV_ERR_INVALID_ARG, "lse is not 4-byte aligned");
   if (kmax < 1 || kmax > s.nb) return fail(USV_ERR_INVALID_ARG, "kmax (%d) must be in [1, blocks = %d]", kmax, s.nb);
   if (std::isnan(scale) || std::isinf(scale)) return fail(USV_ERR_INVALID_ARG, "scale must be finite");
+  if (!coarse && (gate_fine || gate_coarse)) return fail(USV_ERR_INVALID_ARG, "gates without coarse");
+  if (coarse && !aligned16(coarse)) return fail(USV_ERR_INVALID_ARG, "coarse is not 16-byte aligned");
+  if (gate_fine && !aligned16(gate_fine)) return fail(USV_ERR_INVALID_ARG, "gate_fine is not 16-byte aligned");
+  if (gate_coarse && !aligned16(gate_coarse)) return fail(USV_ERR_INVALID_ARG, "gate_coarse is not 16-byte aligned");
   if (scale <= 0.f) scale = 1.0f / std::sqrt((float)s.d);
+  const usv::FuseArgs fuse{coarse, static_cast<const uint16_t*>(gate_fine), static_cast<const uint16_t*>(gate_coarse)};
   return hip_result(usv::launch_attn_bf16_raster(q, k, v, s, ras, idx, cnt, kmax, scale, out, out_dtype == USV_F32, lse,
-                                                 static_cast<hipStream_t>(stream)),
+                                                 fuse, static_cast<hipStream_t>(stream)),
                     "usv_block_sparse_attn_raster launch");
 }
 

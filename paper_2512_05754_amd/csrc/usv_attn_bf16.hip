@@ -599,8 +599,11 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
         // second branch folded into the store: out = gate_fine * attention + gate_coarse * cube-level row of this cube
         const float4 cz = *reinterpret_cast<const float4*>(fuse.coarse + (head * nb + i) * (long long)D + c4);
         float4 gf = make_float4(1.f, 1.f, 1.f, 1.f), gc = gf;
-        if (fuse.gate_fine) gf = load_bf16x4(fuse.gate_fine + blk_off + row * D + c4);
-        if (fuse.gate_coarse) gc = load_bf16x4(fuse.gate_coarse + blk_off + row * D + c4);
+        long long gate_off = blk_off + row * D + c4;  // in elements
+        if constexpr (RASTER)  // the gates are raster tensors laid out like q
+          gate_off = (ras_off + (long long)ras.order[i * kBlock + row] * ras.tok) / 2 + c4;
+        if (fuse.gate_fine) gf = load_bf16x4(fuse.gate_fine + gate_off);
+        if (fuse.gate_coarse) gc = load_bf16x4(fuse.gate_coarse + gate_off);
         val.x = fmaf(gf.x, val.x, gc.x * cz.x);
         val.y = fmaf(gf.y, val.y, gc.y * cz.y);
         val.z = fmaf(gf.z, val.z, gc.z * cz.z);
@@ -673,9 +676,8 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const D
 // would need for a second workgroup; the two shapes measured the same on cube-major inputs).
 hipError_t launch_attn_bf16_raster(const void* q, const void* k, const void* v, const Dims& s, const RasterArgs& ras,
                                    const int32_t* idx, const int32_t* cnt, int kmax, float scale, void* out,
-                                   bool out_f32, float* lse, hipStream_t st) {
-  const FuseArgs none{nullptr, nullptr, nullptr};
-#define USV_RASTER_CASE(DD, F32) return run<DD, F32, 3, 2, true>(q, k, v, s, idx, cnt, kmax, scale, out, lse, none, st, ras)
+                                   bool out_f32, float* lse, const FuseArgs& fuse, hipStream_t st) {
+#define USV_RASTER_CASE(DD, F32) return run<DD, F32, 3, 2, true>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st, ras)
   if (s.d == 128) {
     if (out_f32) USV_RASTER_CASE(128, true);
     USV_RASTER_CASE(128, false);

@@ -43,7 +43,9 @@ __device__ __forceinline__ int xcd_contiguous_id(int bid, int per_xcd) {
 
 hipError_t launch_select_topk(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax,
                               bool force_local, int32_t* idx, int32_t* cnt, hipStream_t st);
-hipError_t launch_pool_means(const void* x, const Dims& s, float* means, hipStream_t st);
+struct RasterArgs;
+hipError_t launch_pool_means(const void* x, const Dims& s, float* means, hipStream_t st,
+                             const RasterArgs* ras = nullptr);  // ras == nullptr: cube-major x
 hipError_t launch_coarse_attn(const float* scores, const float* vmean, const Dims& s, float* coarse, hipStream_t st);
 hipError_t launch_attn_entropy(const float* scores, const Dims& s, float* entropy, float* ws, hipStream_t st);
 hipError_t launch_fuse_outputs(const void* fine, bool fine_f32, const float* coarse, const void* gate_fine,
@@ -71,7 +73,7 @@ hipError_t launch_block_scores(const void* q, const void* k, const Dims& s, floa
                                hipStream_t st, const RasterArgs* ras = nullptr);
 hipError_t launch_attn_bf16_raster(const void* q, const void* k, const void* v, const Dims& s, const RasterArgs& ras,
                                    const int32_t* idx, const int32_t* cnt, int kmax, float scale, void* out,
-                                   bool out_f32, float* lse, hipStream_t st);
+                                   bool out_f32, float* lse, const FuseArgs& fuse, hipStream_t st);
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
                             const FuseArgs& fuse, hipStream_t st);

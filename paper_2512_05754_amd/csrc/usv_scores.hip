@@ -169,19 +169,24 @@ hipError_t run(const void* q, const void* k, const Dims& s, float* scores, float
 }
 
 template <typename T, int D>
-hipError_t run_pool(const void* x, const Dims& s, float* means, hipStream_t st) {
+hipError_t run_pool(const void* x, const Dims& s, float* means, hipStream_t st, const RasterArgs* ras) {
   const long long cubes = s.bh() * s.nb;
-  pool_means<T, D><<<dim3((unsigned)cubes, 1), kPoolThreads, 0, st>>>(static_cast<const T*>(x), static_cast<const T*>(x),
-                                                                      means, s.nb, s.Nv, cubes * D);
+  if (ras)
+    pool_means<T, D, true><<<dim3((unsigned)cubes, 1), kPoolThreads, 0, st>>>(
+        static_cast<const T*>(x), static_cast<const T*>(x), means, s.nb, s.Nv, cubes * D, *ras);
+  else
+    pool_means<T, D><<<dim3((unsigned)cubes, 1), kPoolThreads, 0, st>>>(static_cast<const T*>(x), static_cast<const T*>(x),
+                                                                        means, s.nb, s.Nv, cubes * D);
   return hipGetLastError();
 }
 
 }  // namespace
 
 // Pooled fp32 means of ONE tensor [B, Hh, N, d] -> means [B, Hh, nb, d].
-hipError_t launch_pool_means(const void* x, const Dims& s, float* means, hipStream_t st) {
-  if (s.bf16) return s.d == 128 ? run_pool<uint16_t, 128>(x, s, means, st) : run_pool<uint16_t, 64>(x, s, means, st);
-  return s.d == 128 ? run_pool<float, 128>(x, s, means, st) : run_pool<float, 64>(x, s, means, st);
+hipError_t launch_pool_means(const void* x, const Dims& s, float* means, hipStream_t st, const RasterArgs* ras) {
+  if (s.bf16)
+    return s.d == 128 ? run_pool<uint16_t, 128>(x, s, means, st, ras) : run_pool<uint16_t, 64>(x, s, means, st, ras);
+  return s.d == 128 ? run_pool<float, 128>(x, s, means, st, ras) : run_pool<float, 64>(x, s, means, st, ras);
 }
 
 hipError_t launch_block_scores(const void* q, const void* k, const Dims& s, float* scores, float* ws,

@@ -93,3 +93,40 @@ def test_raster_path_full_size_480p(usv):
     o_ref = usv.cube_scatter(usv.block_sparse_attn(qc, kc, vc, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32),
                              grid, cube)
     assert torch.equal(out.view(torch.int32), o_ref.view(torch.int32))
+
+
+@pytest.mark.parametrize("grid,cube,B,Hh,d,keep", [CASES[0], CASES[1], CASES[2]], ids=lambda v: str(v).replace(" ", ""))
+def test_raster_second_branch_equals_gather_path(usv, grid, cube, B, Hh, d, keep):
+    """usv_coarse_attn_raster and usv_block_sparse_attn_raster_fused (own cube forced, raster-order gates) against
+    gather -> usv_coarse_attn / usv_block_sparse_attn_fused -> scatter: bit for bit."""
+    Nv = grid[0] * grid[1] * grid[2]
+    w = synth.Workload("raster2", B, Hh, Nv, d, "bf16", 2.0, keep, seed=171 + d + keep)
+    Qr, Kr, Vr = raster_inputs(w, grid, cube)
+    q, k, v = gu.up(Qr), gu.up(Kr), gu.up(Vr)
+    N = w.seq_len
+    gen = torch.Generator(device=gu.DEV).manual_seed(5)
+    gates = [torch.rand((B, Hh, Nv, d), device=gu.DEV, generator=gen).to(torch.bfloat16) for _ in range(2)]
+    order = usv.cube_order(grid, cube, seq_len=N)
+    S = usv.block_scores_raster(q, k, order)
+    idx, cnt = usv.select_topk(S, k=keep, seq_valid=Nv, force_local=True)
+    coarse = usv.coarse_attn_raster(S, v, order)
+    qc, kc, vc, g0, g1 = (usv.cube_gather(x, grid, cube, seq_len=N) for x in (q, k, v, gates[0], gates[1]))
+    coarse_ref = usv.coarse_attn(S, vc, seq_valid=Nv)
+    assert torch.equal(coarse.view(torch.int32), coarse_ref.view(torch.int32))
+    for odt in (torch.float32, torch.bfloat16):
+        for gf, gc, rf, rc in ((gates[0], gates[1], g0, g1), (None, gates[1], None, g1), (None, None, None, None)):
+            out = usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out_dtype=odt, coarse=coarse, gate_fine=gf,
+                                               gate_coarse=gc)
+            ref = usv.cube_scatter(usv.block_sparse_attn(qc, kc, vc, idx, cnt, seq_valid=Nv, out_dtype=odt, coarse=coarse_ref,
+                                                         gate_fine=rf, gate_coarse=rc), grid, cube)
+            it = torch.int32 if odt == torch.float32 else torch.int16
+            assert torch.equal(out.view(it), ref.view(it))
+    # and the fused result against the oracle's two branches
+    Qf, Kf, Vf = (orc.cube_gather(synth.as_f32(x), grid, cube, N) for x in (Qr, Kr, Vr))
+    fine = orc.block_sparse_attn(Qf, Kf, Vf, gu.down(idx), gu.down(cnt), Nv)[0]
+    co = orc.coarse_attn(gu.down(S), Vf, Nv)
+    gcm = [orc.cube_gather(gu.down(g).astype(np.float64), grid, cube, N) for g in gates]
+    want = orc.cube_scatter(orc.fuse_outputs(fine, co, Nv, gcm[0], gcm[1]), grid, cube)
+    got = usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out_dtype=torch.float32, coarse=coarse,
+                                       gate_fine=gates[0], gate_coarse=gates[1])
+    gu.assert_attn_close(gu.down(got), want, "bf16", False, "raster fused attention")

@@ -180,6 +180,17 @@ def test_raster_entry_points_reject_bad_arguments_before_launch():
     wide = binding.UsvRaster(FAKE, binding.UsvStrides(1 << 40, 128, 8192), zero)
     assert name(args(big, wide)) == "USV_ERR_UNSUPPORTED"
     assert b"2 GiB" in L.usv_last_error()
+    # the second branch on raster tensors
+    cneed = L.usv_coarse_workspace_bytes(ctypes.byref(sh))
+    assert name(L.usv_coarse_attn_raster(FAKE, FAKE, ctypes.byref(sh), None, FAKE, FAKE, cneed, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_coarse_attn_raster(FAKE, FAKE, ctypes.byref(sh), ctypes.byref(view), FAKE, FAKE, cneed - 1, None)) == "USV_ERR_WORKSPACE"
+    assert name(L.usv_coarse_attn_raster(None, FAKE, ctypes.byref(sh), ctypes.byref(view), FAKE, FAKE, cneed, None)) == "USV_ERR_INVALID_ARG"
+    fused = lambda coarse, gf, gc: L.usv_block_sparse_attn_raster_fused(
+        FAKE, FAKE, FAKE, ctypes.byref(sh), ctypes.byref(view), FAKE, FAKE, 1, ctypes.c_float(0.0), coarse, gf, gc, bf16, FAKE,
+        None, None)
+    assert name(fused(None, FAKE, None)) == "USV_ERR_INVALID_ARG"       # gates without the cube-level rows
+    assert name(fused(FAKE + 4, None, None)) == "USV_ERR_INVALID_ARG"   # misaligned
+    assert name(fused(FAKE, FAKE + 2, None)) == "USV_ERR_INVALID_ARG"
 
 
 # --------------------------------------------------------------------------- #
