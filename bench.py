@@ -491,7 +491,7 @@ def main():
                           "select_topk": bytes_topk / (avg[1] * 1e-3) / 1e9},
         "roofline": {
             "kernel": "usv_block_sparse_attn (attn_bf16)" if w.dtype == "bf16" else "usv_block_sparse_attn (attn_f32)",
-            "bound": "mfma" if w.dtype == "bf16" else "alu",
+            "bound": "mfma",  # bf16 matrix cores for bf16 inputs, fp32 matrix cores (v_mfma_f32_32x32x2_f32) for fp32 inputs
             "achieved": flop / (avg[2] * 1e-3) / 1e12,
             "peak": PEAK_BF16_TFLOPS if w.dtype == "bf16" else 157.3,
             "unit": "TFLOP/s",

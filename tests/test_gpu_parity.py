@@ -21,6 +21,8 @@ def small_workloads():
         Workload("bf16_d64", 1, 2, 6 * 64, 64, "bf16", 2.0, 3, seed=13),
         Workload("bf16_d64_ragged", 1, 1, 6 * 64 - 40, 64, "bf16", 1.0, 5, seed=14),
         Workload("bf16_d128_70blocks", 1, 1, 70 * 64 - 1, 128, "bf16", 2.0, 7, seed=15),
+        Workload("f32_d128_64blocks", 1, 2, 64 * 64 - 7, 128, "f32", 2.0, 8, seed=16),
+        Workload("f32_d64_40blocks", 1, 1, 40 * 64 - 33, 64, "f32", 2.0, 6, seed=17),
     ]
 
 
