@@ -142,7 +142,8 @@ usv_status usv_select_topk_ex(const float* scores, const usv_shape* shape, int32
  * bf16 inputs: QK^T and PV run on bf16 MFMA with fp32 accumulation and an fp32
  * online softmax; the probabilities are rounded to bf16 before PV and the row
  * sums are taken over the rounded values.
- * fp32 inputs: everything in fp32 (plain FMA), for accuracy checks.
+ * fp32 inputs: both products on the fp32 matrix cores (fp32 operands and
+ * accumulation), fp32 softmax: within 1e-5 relative of an fp64 evaluation.
  */
 usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v,
                                  const usv_shape* shape, const int32_t* idx, const int32_t* cnt,
