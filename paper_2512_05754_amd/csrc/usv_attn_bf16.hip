@@ -268,7 +268,9 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   // The index list lives in a VGPR, 64 entries at a time (lane t holds entry 64*chunk + t), and is
   // read with v_readlane: one instruction per tile and no scalar-memory wait, which would also be
   // a wait for every LDS read in flight.
-  int list_v = lane < n_list ? min(max(list[lane], 0), nb - 1) : 0;  // ... ids are clamped into [0, nb)
+  // (read for every lane below kmax, whatever the count says, so that this load does not wait for the count's)
+  const int list_raw = lane < kmax ? list[lane] : 0;
+  int list_v = lane < n_list ? min(max(list_raw, 0), nb - 1) : 0;  // ... ids are clamped into [0, nb)
   auto list_at = [&](int n) { return __builtin_amdgcn_readlane(list_v, n & 63); };
 
   // ring item 2n = K(list[n]) -> slot (2n) % SLOTS, item 2n+1 = V(list[n]) -> slot (2n+1) % SLOTS;
