@@ -215,6 +215,32 @@ def test_long_lists_cross_the_index_reload_boundary(usv, nb, k):
     gu.assert_attn_close(got, np.stack([ref[i][0] for i in blocks]), "bf16", False, w.name)
 
 
+@pytest.mark.parametrize("nb,kmax,d", [(64, 24, 128), (64, 24, 64), (24, 24, 128), (40, 40, 64)],
+                         ids=["sparse_shape_d128", "sparse_shape_d64", "dense_shape_d128", "dense_shape_d64"])
+def test_every_list_length_in_both_launch_shapes(usv, nb, kmax, d):
+    """Query cube i gets a list of i % (kmax + 1) blocks: every length from 0 to kmax, i.e. every phase of the
+    K/V ring and every shape of its last, partial round, in the sparse launch shape (kmax < nb/2: five slots)
+    and in the dense-like one (three slots)."""
+    w = Workload("lengths", 1, 2, nb * 64 - 11, d, "bf16", 2.0, kmax, seed=300 + nb + d)
+    rng = np.random.default_rng(nb * 7 + kmax + d)
+    Q, K, V = synth.gen_qkv(w)
+    nbv = (w.seq_valid + 63) // 64
+    idx = np.full((1, 2, nb, kmax), -1, dtype=np.int32)
+    cnt = np.zeros((1, 2, nb), dtype=np.int32)
+    for h in range(2):
+        for i in range(nb):
+            c = (i + 3 * h) % (kmax + 1)
+            idx[0, h, i, :c] = np.sort(rng.choice(nbv, size=c, replace=False))
+            cnt[0, h, i] = c
+    out, lse = usv.block_sparse_attn(gu.up(Q), gu.up(K), gu.up(V), gu.up(idx), gu.up(cnt), seq_valid=w.seq_valid,
+                                     return_lse=True, out_dtype=torch.float32)
+    O, L = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), idx, cnt, w.seq_valid)
+    gu.assert_attn_close(gu.down(out), O, "bf16", False, f"nb {nb} kmax {kmax}")
+    live = np.isfinite(L)
+    assert np.array_equal(np.isneginf(gu.down(lse)), ~live)
+    assert np.abs(gu.down(lse)[live] - L[live]).max() <= 2e-2
+
+
 def test_online_softmax_survives_large_logit_offsets(usv):
     """Keys shifted by a large common vector: every logit of a row moves by the same amount."""
     w = Workload("shift", 1, 1, 8 * 64, 128, "bf16", 0.0, 8, seed=41)

@@ -130,3 +130,28 @@ def test_raster_second_branch_equals_gather_path(usv, grid, cube, B, Hh, d, keep
     got = usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out_dtype=torch.float32, coarse=coarse,
                                        gate_fine=gates[0], gate_coarse=gates[1])
     gu.assert_attn_close(gu.down(got), want, "bf16", False, "raster fused attention")
+
+
+def test_raster_every_list_length(usv):
+    """Every list length from 0 to 20 on raster tensors (the order ring and the K/V ring of the raster kernel run
+    through all their phases and partial last rounds), against the gather path bit for bit."""
+    grid, cube, B, Hh, d, kmax = (8, 12, 20), (4, 4, 4), 1, 2, 128, 20
+    Nv = grid[0] * grid[1] * grid[2]
+    w = synth.Workload("raster_lengths", B, Hh, Nv, d, "bf16", 2.0, kmax, seed=411)
+    Qr, Kr, Vr = raster_inputs(w, grid, cube)
+    q, k, v = gu.up(Qr), gu.up(Kr), gu.up(Vr)
+    N, nb = w.seq_len, w.nb
+    rng = np.random.default_rng(8)
+    idx = np.full((B, Hh, nb, kmax), -1, dtype=np.int32)
+    cnt = np.zeros((B, Hh, nb), dtype=np.int32)
+    for h in range(Hh):
+        for i in range(nb):
+            c = (i + 5 * h) % (kmax + 1)
+            idx[0, h, i, :c] = np.sort(rng.choice(nb, size=c, replace=False))
+            cnt[0, h, i] = c
+    order = usv.cube_order(grid, cube, seq_len=N)
+    qc, kc, vc = (usv.cube_gather(x, grid, cube, seq_len=N) for x in (q, k, v))
+    ref = usv.cube_scatter(usv.block_sparse_attn(qc, kc, vc, gu.up(idx), gu.up(cnt), seq_valid=Nv, out_dtype=torch.float32),
+                           grid, cube)
+    out = usv.block_sparse_attn_raster(q, k, v, order, gu.up(idx), gu.up(cnt), out_dtype=torch.float32)
+    assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
