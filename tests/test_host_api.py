@@ -26,6 +26,21 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, n) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/usv.h is a C header: it must compile as C99 with no C++ and no torch types."""
+    import shutil
+    import subprocess
+
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "usv.h"\nint main(void) { usv_shape s; usv_raster r; (void)s; (void)r; return (int)USV_OK; }\n')
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                          "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+
+
 def shape(**kw):
     base = dict(batch=1, heads=2, seq_len=1024, seq_valid=1024, head_dim=64, block=64, dtype=binding.USV_F32)
     base.update(kw)
