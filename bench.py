@@ -52,9 +52,35 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (the three calls) in a HIP graph and time --steps replays of it; the per-stage "
                          "times then come from a second, eager pass (attention and raster paths only)")
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="untimed steps run ahead of the --warmup steps until this much GPU time has passed: after an "
+                         "idle period the chip takes some 50 ms of sustained load to reach its steady clock, and a short "
+                         "--warmup would otherwise time the ramp; 0 switches it off")
     ap.add_argument("--no-mfma-peak", action="store_true",
                     help="skip the MFMA-only peak probe (paper_2512_05754_amd/tools/mfma_peak, ~1 s)")
     return ap.parse_args()
+
+
+def settle(step, ms):
+    """Run untimed steps until `ms` of GPU time have passed; returns how many ran.
+
+    The GPU's clock governor needs tens of milliseconds of sustained load to leave its idle state (the first 25
+    launches of the attention kernel after an idle second take 0.98 ms each, later ones 0.81 ms).  These steps come
+    ahead of the W warm-up steps, which then run without a gap before the timed region."""
+    if ms <= 0:
+        return 0
+    import torch
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = 0
+    a.record()
+    while True:
+        for _ in range(8):
+            step()
+        n += 8
+        b.record()
+        b.synchronize()
+        if a.elapsed_time(b) >= ms:
+            return n
 
 
 def pick_workload(name):
@@ -164,10 +190,10 @@ def reorder_main(args):
         if events is not None:
             events[2].record()
 
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    settled = settle(step, args.settle_ms)
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -184,6 +210,7 @@ def reorder_main(args):
     result = {
         "metric": "GB/s of raster <-> cube-major reorder (gather Q, K, V + scatter O), algorithmic bytes",
         "value": total / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "settle_steps": settled,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": w.name, "path": "reorder", "grid": list(grid), "cube": list(cube), "batch": B, "heads": Hh,
@@ -258,10 +285,10 @@ def merge_main(args):
         usv.unmerge_apply(o_merged, grid, mb, row_of, Nm, out=o_raster)
         rec(4)
 
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    settled = settle(step, args.settle_ms)
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -280,6 +307,7 @@ def merge_main(args):
     result = {
         "metric": "GB/s of token merging (similarity + plan + merge Q, K, V + unmerge O), algorithmic bytes",
         "value": total / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "settle_steps": settled,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "path": "merge", "grid": list(grid), "merge_block": list(mb), "batch": B, "heads": Hh,
@@ -422,12 +450,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # untimed: the settle steps, then the --warmup steps; timed: exactly --steps passes, bracketed by synchronize();
+    # per-stage events are recorded on the launch stream
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    settled = settle(step, args.settle_ms)
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
-
-    # timed region: exactly --steps passes; per-stage events are recorded on the launch stream
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     if args.graph and not two_branch:
         side = torch.cuda.Stream()
@@ -435,6 +463,7 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
             step()
+        settle(graph.replay, args.settle_ms)
         for _ in range(args.warmup):
             graph.replay()
         torch.cuda.synchronize()
@@ -469,6 +498,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settle_steps": settled,  # untimed steps ahead of the warm-up (--settle-ms of GPU time)
         "ms_per_step": ms_step,
         "higher_is_better": True,
         "scaling": "weak",
