@@ -82,6 +82,54 @@ def test_topk_ties_and_special_values(usv):
     check_topk(usv, S, 40, nb * 64 - 64 * 3 - 5)  # only 125 candidate blocks, partial last one
 
 
+@pytest.mark.parametrize("force_local", [False, True], ids=["plain", "force_local"])
+def test_topk_adversarial_rows(usv, force_local):
+    """Rows built to stress the threshold search: huge dynamic range, values one ulp apart, a single
+    outlier, all negative, few distinct values, signalling NaNs, infinities at the local cube."""
+    nb = 192  # three register slots per lane, the last rows only partly valid below
+    rng = np.random.default_rng(77)
+    S = np.empty((1, 1, nb, nb), dtype=np.float32)
+    base = rng.standard_normal((nb, nb)).astype(np.float32)
+    for i in range(nb):
+        kind = i % 12
+        r = base[i].copy()
+        if kind == 0:
+            r = np.exp(rng.uniform(-80, 80, nb)).astype(np.float32) * rng.choice([-1, 1], nb)  # 2^-115 .. 2^115
+        elif kind == 1:
+            r = (np.float32(3.0) + np.arange(nb, dtype=np.float32) * np.float32(2.0 ** -22))[rng.permutation(nb)]
+        elif kind == 2:
+            r[:] = -5.0
+            r[rng.integers(nb)] = 1e30
+        elif kind == 3:
+            r = -np.abs(r) - 1  # no positive score in the row
+        elif kind == 4:
+            r = rng.integers(0, 3, nb).astype(np.float32)  # three distinct values
+        elif kind == 5:
+            r.view(np.uint32)[::5] = 0x7FA00000  # signalling NaNs, positive
+            r.view(np.uint32)[1::7] = 0xFFA00001  # and negative ones
+        elif kind == 6:
+            r[i] = np.inf  # the local cube ties with other +inf scores
+            r[::9] = np.inf
+        elif kind == 7:
+            r[i] = np.nan  # the local cube has no score at all
+        elif kind == 8:
+            r[i] = -np.inf
+            r[1::2] = -np.inf
+        elif kind == 9:
+            r = (rng.integers(-4, 5, nb) * np.float32(1e-41)).astype(np.float32)  # denormals and zeros of both signs
+            r[::4] *= np.float32(-1.0)
+        elif kind == 10:
+            r[:] = np.float32(np.finfo(np.float32).max)
+            r[::2] = -np.float32(np.finfo(np.float32).max)
+        S[0, 0, i] = r
+    for seq_valid in (nb * 64, nb * 64 - 64 * 60 - 3):
+        for k in (1, 2, 17, 64, 65, 130, nb):
+            idx, cnt = usv.select_topk(gu.up(S), k=k, seq_valid=seq_valid, force_local=force_local)
+            ridx, rcnt = orc.select_topk(S, k, seq_valid, force_local=force_local)
+            assert np.array_equal(gu.down(cnt), rcnt), (seq_valid, k)
+            assert np.array_equal(gu.down(idx), ridx), (seq_valid, k)
+
+
 def test_topk_ragged_budgets(usv):
     nb, kmax = 256, 64
     rng = np.random.default_rng(9)
