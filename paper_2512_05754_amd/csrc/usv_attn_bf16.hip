@@ -19,7 +19,10 @@
 // What bounds the kernel, measured on MI355X: a wavefront issues at most one instruction (of any
 // kind) every ~8 clocks, a 32x32x16 MFMA occupies the matrix pipe for 32 clocks, and the CU's
 // vector-memory path moves 64 B/clk (a 64x64 tile needs 32 KiB of K and V: 512 clocks, the same
-// as its 16 MFMAs per SIMD).  So the design goal is few instructions per tile and two or three
+// as its 16 MFMAs per SIMD).  With two workgroups per CU the chip then sits at its power limit
+// (it clocks this kernel at ~1.7 GHz of 2.4) and, for lists without locality, near what the
+// L2-miss path delivers (~7 TB/s), so every instruction and every byte moved costs clock.
+// The design goal is therefore few instructions per tile and two or three
 // workgroups per CU (waves per SIMD) that cover each other's issue gaps and waits:
 //   - <= 168 VGPRs, so that three workgroups fit where the LDS ring allows it;
 //   - K/V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no register
