@@ -5,7 +5,7 @@
 //   coarse_attn   C[bh, i, :] = sum_j softmax_j(S[bh, i, :])_j * Vm[bh, j, :] over the cubes that hold a
 //                 valid token; S are the stage-1 scores, Vm the pooled fp32 means of V.  Two passes over
 //                 the 32 score rows of a workgroup: row maxima, then exp, row sums and P Vm on the fp32
-//                 matrix cores (v_mfma_f32_32x32x2_f32, same operand mapping as the score product).
+//                 matrix cores (v_mfma_f32_32x32x2_f32).
 //   fuse_outputs  out[r] = g_fine[r] * fine[r] + g_coarse[r] * C[cube(r)], elementwise: HBM bound.
 #include "usv_internal.h"
 
@@ -14,54 +14,58 @@ namespace {
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-// grid = (ceil(nb / 32), B*Hh); 256 threads.  Output tile: 32 query cubes x D channels.
-// Pass A finds the row maxima; pass B walks the key cubes 64 at a time: it stages P = exp(S - max)
-// and the transposed Vm tile in LDS, accumulates the row sums (8 lanes per row), and runs P Vm on the
-// matrix cores with the four waves splitting the 64 key cubes of a tile (16 each); the waves'
-// partial tiles are then added in a fixed order.
+// grid = (ceil(nb / 32), B*Hh); 8 D threads = 4 (D/32) wavefronts.  Output tile: 32 query cubes x D channels.
+// Pass A finds the row maxima; pass B walks the key cubes 64 at a time: it stages P = exp(S - max) and the Vm
+// tile in LDS, accumulates the row sums (8 lanes per row), and runs P Vm on the matrix cores.  Wavefront
+// (kg, cg) takes key cubes 16 kg .. +16 of every tile and channels 32 cg .. +32, so a workgroup puts four
+// (D=64: two) waves on every SIMD of its CU: the grid is small (192 workgroups at the 480p shape) and the
+// kernel is bound by exposed latencies, not by bandwidth or the matrix cores.  The four key groups' partial
+// tiles are added in a fixed order at the end.
 template <int D>
-__global__ __launch_bounds__(256) void coarse_attn(const float* __restrict__ scores, const float* __restrict__ vmean,
-                                                   float* __restrict__ coarse, int nb, int nb_valid) {
+__global__ __launch_bounds__(8 * D) void coarse_attn(const float* __restrict__ scores, const float* __restrict__ vmean,
+                                                     float* __restrict__ coarse, int nb, int nb_valid) {
+  constexpr int NT = 8 * D;        // threads
+  constexpr int NW = NT / 64;      // wavefronts
   constexpr int ROWS = 32;
-  constexpr int LD = 64 + 4;       // row stride in floats (16-byte reads of 32 consecutive rows spread over the banks)
-  constexpr int NACC = D / 32;     // 32x32 accumulators per wave: the whole 32 x D tile
-  constexpr int OLD = D + 4;       // row stride of the reduction buffer
-  __shared__ __attribute__((aligned(16))) float Ps[ROWS * LD];  // score / P tile, [query cube][key cube]
-  __shared__ __attribute__((aligned(16))) float Vt[D * LD];     // Vm tile transposed, [channel][key cube]; later the reduction buffer
+  constexpr int RPW = ROWS / NW;   // rows per wave in pass A
+  constexpr int LD = 64 + 4;       // row stride of the P tile in floats (16-byte reads of 32 consecutive rows spread over the banks)
+  constexpr int VLD = D + 4;       // row stride of the Vm tile and of the reduction buffer
+  __shared__ __attribute__((aligned(16))) float Ps[ROWS * LD];  // P tile, [query cube][key cube]
+  __shared__ __attribute__((aligned(16))) float Vs[64 * VLD];   // Vm tile, [key cube][channel]; later the reduction buffer
   __shared__ float row_max[ROWS], row_inv[ROWS];
-  static_assert(ROWS * OLD <= D * LD, "the reduction buffer overlays Vt");
   const int bh = blockIdx.y, i0 = blockIdx.x * ROWS;
   const float* S = scores + (long long)bh * nb * nb;
   const float* vm = vmean + (long long)bh * nb * D;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int srow = tid >> 3, spart = tid & 7;  // row statistics: 8 lanes per row, 8 key cubes each per tile
+  const int kg = wave & 3, cg = wave >> 2;
+  const int srow = (tid >> 3) & 31, spart = tid & 7;  // row statistics (threads 0..255): 8 lanes per row, 8 key cubes each per tile
 
-  // pass A: row maxima.  Wave w owns rows 8 w .. 8 w + 7; the loads of all 8 rows of a 512-cube chunk
+  // pass A: row maxima.  Wave w owns rows RPW w .. +RPW; the loads of all its rows of a 512-cube chunk
   // are issued together, so a chunk costs one memory latency.
   {
-    float mx[8];
+    float mx[RPW];
 #pragma unroll
-    for (int rr = 0; rr < 8; ++rr) mx[rr] = -INFINITY;
+    for (int rr = 0; rr < RPW; ++rr) mx[rr] = -INFINITY;
     for (int jc = 0; jc < nb_valid; jc += 512) {
-      float x[8][8];
+      float x[RPW][8];
 #pragma unroll
-      for (int rr = 0; rr < 8; ++rr)
+      for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-          const int i = i0 + wave * 8 + rr, j = jc + 64 * t + lane;
+          const int i = i0 + wave * RPW + rr, j = jc + 64 * t + lane;
           x[rr][t] = (i < nb_valid && j < nb_valid) ? S[(long long)i * nb + j] : -INFINITY;
         }
 #pragma unroll
-      for (int rr = 0; rr < 8; ++rr)
+      for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
         for (int t = 0; t < 8; ++t) mx[rr] = fmaxf(mx[rr], x[rr][t]);
     }
 #pragma unroll
-    for (int rr = 0; rr < 8; ++rr) {
+    for (int rr = 0; rr < RPW; ++rr) {
       float m = mx[rr];
 #pragma unroll
       for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-      if (lane == 0) row_max[wave * 8 + rr] = m == -INFINITY ? 0.f : m;  // rows of cubes without a valid token: P stays 0
+      if (lane == 0) row_max[wave * RPW + rr] = m == -INFINITY ? 0.f : m;  // rows of cubes without a valid token: P stays 0
     }
   }
   __syncthreads();
@@ -69,26 +73,24 @@ __global__ __launch_bounds__(256) void coarse_attn(const float* __restrict__ sco
   // pass B: C = P Vm (unnormalised), row sums on the side.  The next tile's scores and Vm rows are
   // fetched into registers while the current tile is in LDS.
   const int r = lane & 31, g = lane >> 5;
-  const int kofs = 16 * wave + 8 * g;  // an MFMA step contracts 2 key cubes, one per 32-lane half: wave w, half g takes cube 16 w + 8 g + t at step t
-  f32x16 acc[NACC];
+  const int kofs = 16 * kg + 8 * g;  // an MFMA step contracts 2 key cubes, one per 32-lane half: key group kg, half g takes cube 16 kg + 8 g + t at step t
+  f32x16 acc;
 #pragma unroll
-  for (int n = 0; n < NACC; ++n)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   float l = 0.f;
-  constexpr int SPT = ROWS * 64 / 256;       // scores per thread and tile
-  constexpr int VPT = 64 * (D / 4) / 256;    // float4 of Vm per thread and tile
+  constexpr int SPT = ROWS * 64 / NT;       // scores per thread and tile
+  constexpr int VPT = 64 * (D / 4) / NT;    // float4 of Vm per thread and tile
   float sreg[SPT];
   float4 vreg[VPT];
   auto fetch = [&](int j0) {
 #pragma unroll
     for (int t = 0; t < SPT; ++t) {
-      const int e = tid + 256 * t, row = e >> 6, col = e & 63, i = i0 + row, j = j0 + col;
+      const int e = tid + NT * t, row = e >> 6, col = e & 63, i = i0 + row, j = j0 + col;
       sreg[t] = (i < nb_valid && j < nb_valid) ? S[(long long)i * nb + j] : -INFINITY;
     }
 #pragma unroll
     for (int t = 0; t < VPT; ++t) {
-      const int e = tid + 256 * t, col = e / (D / 4), c = (e % (D / 4)) * 4, j = j0 + col;
+      const int e = tid + NT * t, col = e / (D / 4), c = (e % (D / 4)) * 4, j = j0 + col;
       vreg[t] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (j < nb_valid) vreg[t] = *reinterpret_cast<const float4*>(vm + (long long)j * D + c);
     }
@@ -98,63 +100,59 @@ __global__ __launch_bounds__(256) void coarse_attn(const float* __restrict__ sco
     if (j0) __syncthreads();  // the previous tile has been consumed
 #pragma unroll
     for (int t = 0; t < SPT; ++t) {
-      const int e = tid + 256 * t, row = e >> 6, col = e & 63;
+      const int e = tid + NT * t, row = e >> 6, col = e & 63;
       // exp2(-inf) = 0 covers the entries outside the valid cubes
       Ps[row * LD + col] = __builtin_amdgcn_exp2f((sreg[t] - row_max[row]) * kLog2e);
     }
 #pragma unroll
     for (int t = 0; t < VPT; ++t) {
-      const int e = tid + 256 * t, col = e / (D / 4), c = (e % (D / 4)) * 4;
-      Vt[(c + 0) * LD + col] = vreg[t].x;
-      Vt[(c + 1) * LD + col] = vreg[t].y;
-      Vt[(c + 2) * LD + col] = vreg[t].z;
-      Vt[(c + 3) * LD + col] = vreg[t].w;
+      const int e = tid + NT * t, col = e / (D / 4), c = (e % (D / 4)) * 4;
+      *reinterpret_cast<float4*>(Vs + col * VLD + c) = vreg[t];
     }
     __syncthreads();
     if (j0 + 64 < nb_valid) fetch(j0 + 64);
+    if (tid < 256) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) l += Ps[srow * LD + spart * 8 + t];
+      for (int t = 0; t < 8; ++t) l += Ps[srow * LD + spart * 8 + t];
+    }
     const float* ap = Ps + r * LD + kofs;
+    const float* bp = Vs + kofs * VLD + 32 * cg + r;  // operand of step t: Vm[cube kofs + t][channel 32 cg + r]
 #pragma unroll
     for (int t = 0; t < 8; t += 4) {
       const float4 a = *reinterpret_cast<const float4*>(ap + t);
-#pragma unroll
-      for (int n = 0; n < NACC; ++n) {
-        const float4 b = *reinterpret_cast<const float4*>(Vt + (32 * n + r) * LD + kofs + t);
-        acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc[n], 0, 0, 0);
-        acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc[n], 0, 0, 0);
-        acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc[n], 0, 0, 0);
-        acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc[n], 0, 0, 0);
-      }
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, bp[(t + 0) * VLD], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, bp[(t + 1) * VLD], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, bp[(t + 2) * VLD], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, bp[(t + 3) * VLD], acc, 0, 0, 0);
     }
   }
-  l += __shfl_xor(l, 1);
-  l += __shfl_xor(l, 2);
-  l += __shfl_xor(l, 4);
-  if (spart == 0) row_inv[srow] = l > 0.f ? 1.0f / l : 0.f;
-  __syncthreads();  // also: every wave is done reading Vt
+  if (tid < 256) {
+    l += __shfl_xor(l, 1);
+    l += __shfl_xor(l, 2);
+    l += __shfl_xor(l, 4);
+    if (spart == 0) row_inv[srow] = l > 0.f ? 1.0f / l : 0.f;
+  }
+  __syncthreads();  // also: every wave is done reading Vs
 
-  // add the four waves' partial tiles in wave order (deterministic), then normalise and store.
-  // accumulator register e of lane (r, g): row 8 (e/4) + 4 g + (e%4), channel 32 n + r
-  float* red = Vt;
+  // add the four key groups' partial tiles in group order (deterministic), then normalise and store.
+  // accumulator register e of lane (r, g): row 8 (e/4) + 4 g + (e%4), channel 32 cg + r
+  float* red = Vs;
   for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
+    if (kg == w) {
 #pragma unroll
-      for (int n = 0; n < NACC; ++n)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float* p = red + (8 * (e >> 2) + 4 * g + (e & 3)) * OLD + 32 * n + r;
-          *p = (w == 0 ? 0.f : *p) + acc[n][e];
-        }
+      for (int e = 0; e < 16; ++e) {
+        float* p = red + (8 * (e >> 2) + 4 * g + (e & 3)) * VLD + 32 * cg + r;
+        *p = (w == 0 ? 0.f : *p) + acc[e];
+      }
     }
     __syncthreads();
   }
   float* out = coarse + (long long)bh * nb * D;
-  for (int e = tid; e < ROWS * (D / 4); e += 256) {
+  for (int e = tid; e < ROWS * (D / 4); e += NT) {
     const int row = e / (D / 4), c = (e % (D / 4)) * 4, i = i0 + row;
     if (i < nb) {
       const float inv = i < nb_valid ? row_inv[row] : 0.f;
-      const float4 v = *reinterpret_cast<const float4*>(red + row * OLD + c);
+      const float4 v = *reinterpret_cast<const float4*>(red + row * VLD + c);
       *reinterpret_cast<float4*>(out + (long long)i * D + c) = make_float4(v.x * inv, v.y * inv, v.z * inv, v.w * inv);
     }
   }
@@ -224,9 +222,9 @@ hipError_t run_fuse(const void* fine, const float* coarse, const void* gf, const
 hipError_t launch_coarse_attn(const float* scores, const float* vmean, const Dims& s, float* coarse, hipStream_t st) {
   const dim3 grid((unsigned)((s.nb + 31) / 32), (unsigned)s.bh());
   if (s.d == 128)
-    coarse_attn<128><<<grid, 256, 0, st>>>(scores, vmean, coarse, s.nb, s.nb_valid);
+    coarse_attn<128><<<grid, 8 * 128, 0, st>>>(scores, vmean, coarse, s.nb, s.nb_valid);
   else
-    coarse_attn<64><<<grid, 256, 0, st>>>(scores, vmean, coarse, s.nb, s.nb_valid);
+    coarse_attn<64><<<grid, 8 * 64, 0, st>>>(scores, vmean, coarse, s.nb, s.nb_valid);
   return hipGetLastError();
 }
 

@@ -26,30 +26,35 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-// grid = (ceil(nb_valid / 32), B*Hh); 256 threads.
-__global__ __launch_bounds__(256) void entropy_partials(const float* __restrict__ scores, float* __restrict__ partial,
-                                                        int nb, int nb_valid, int tiles) {
+// grid = (ceil(nb_valid / 32), B*Hh); 1024 threads (the grid is small, 192 workgroups at the 480p shape, and every
+// step is a memory latency: sixteen waves per CU overlap what four cannot).
+constexpr int kPartThreads = 1024;
+__global__ __launch_bounds__(kPartThreads) void entropy_partials(const float* __restrict__ scores,
+                                                                 float* __restrict__ partial, int nb, int nb_valid,
+                                                                 int tiles) {
+  constexpr int NW = kPartThreads / 64, RPW = kRows / NW;  // 16 waves, 2 rows each
   __shared__ float row_max[kRows], row_inv[kRows];
+  __shared__ float upper[kPartThreads / 2];
   const int bh = blockIdx.y, i0 = blockIdx.x * kRows;
   const float* S = scores + (long long)bh * nb * nb;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  // row statistics: wave w owns rows 8 w .. 8 w + 7; the loads of all 8 rows of a 512-cube chunk are issued together
-  float mx[8], sum[8];
+  // row statistics: wave w owns rows RPW w .. +RPW; the loads of its rows of a 512-cube chunk are issued together
+  float mx[RPW], sum[RPW];
 #pragma unroll
-  for (int rr = 0; rr < 8; ++rr) mx[rr] = -INFINITY, sum[rr] = 0.f;
+  for (int rr = 0; rr < RPW; ++rr) mx[rr] = -INFINITY, sum[rr] = 0.f;
   for (int pass = 0; pass < 2; ++pass) {
     for (int jc = 0; jc < nb_valid; jc += 512) {
-      float x[8][8];
+      float x[RPW][8];
 #pragma unroll
-      for (int rr = 0; rr < 8; ++rr)
+      for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-          const int i = i0 + wave * 8 + rr, j = jc + 64 * t + lane;
+          const int i = i0 + wave * RPW + rr, j = jc + 64 * t + lane;
           x[rr][t] = (i < nb_valid && j < nb_valid) ? S[(long long)i * nb + j] : -INFINITY;
         }
 #pragma unroll
-      for (int rr = 0; rr < 8; ++rr)
+      for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           if (pass == 0)
@@ -60,32 +65,46 @@ __global__ __launch_bounds__(256) void entropy_partials(const float* __restrict_
     }
     if (pass == 0) {
 #pragma unroll
-      for (int rr = 0; rr < 8; ++rr) {
+      for (int rr = 0; rr < RPW; ++rr) {
         mx[rr] = wave_max(mx[rr]);
         if (mx[rr] == -INFINITY) mx[rr] = 0.f;  // a row of a cube without a valid token: all terms stay 0
       }
     }
   }
 #pragma unroll
-  for (int rr = 0; rr < 8; ++rr) {
+  for (int rr = 0; rr < RPW; ++rr) {
     const float l = wave_sum(sum[rr]);
     if (lane == 0) {
-      row_max[wave * 8 + rr] = mx[rr];
-      row_inv[wave * 8 + rr] = l > 0.f ? 1.0f / l : 0.f;
+      row_max[wave * RPW + rr] = mx[rr];
+      row_inv[wave * RPW + rr] = l > 0.f ? 1.0f / l : 0.f;
     }
   }
   __syncthreads();
 
-  // column sums of the 32 normalised rows, rows added in ascending order
+  // column sums of the 32 normalised rows: thread (column, half) adds rows 16 half .. +16 in ascending order,
+  // then lower half + upper half
   float* dst = partial + ((long long)bh * tiles + blockIdx.x) * nb;
-  for (int j = tid; j < nb_valid; j += 256) {
-    float x[kRows];
-#pragma unroll
-    for (int r = 0; r < kRows; ++r) x[r] = (i0 + r < nb_valid) ? S[(long long)(i0 + r) * nb + j] : -INFINITY;
+  const int col = tid & (kPartThreads / 2 - 1), half = tid / (kPartThreads / 2);
+  for (int j0 = 0; j0 < nb_valid; j0 += kPartThreads / 2) {  // uniform trip count: barriers inside
+    const int j = j0 + col;
     float c = 0.f;
+    if (j < nb_valid) {
+      float x[kRows / 2];
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) c += __builtin_amdgcn_exp2f((x[r] - row_max[r]) * kLog2e) * row_inv[r];
-    dst[j] = c;
+      for (int r = 0; r < kRows / 2; ++r) {
+        const int i = i0 + half * (kRows / 2) + r;
+        x[r] = i < nb_valid ? S[(long long)i * nb + j] : -INFINITY;
+      }
+#pragma unroll
+      for (int r = 0; r < kRows / 2; ++r) {
+        const int rl = half * (kRows / 2) + r;
+        c += __builtin_amdgcn_exp2f((x[r] - row_max[rl]) * kLog2e) * row_inv[rl];
+      }
+    }
+    if (half == 1) upper[col] = c;
+    __syncthreads();
+    if (half == 0 && j < nb_valid) dst[j] = c + upper[col];
+    __syncthreads();
   }
 }
 
@@ -136,7 +155,7 @@ __global__ __launch_bounds__(1024) void entropy_finish(const float* __restrict__
 // ws: B * Hh * tiles * nb floats, tiles = ceil(nb_valid / 32)
 hipError_t launch_attn_entropy(const float* scores, const Dims& s, float* entropy, float* ws, hipStream_t st) {
   const int tiles = (s.nb_valid + kRows - 1) / kRows;
-  entropy_partials<<<dim3((unsigned)tiles, (unsigned)s.bh()), 256, 0, st>>>(scores, ws, s.nb, s.nb_valid, tiles);
+  entropy_partials<<<dim3((unsigned)tiles, (unsigned)s.bh()), kPartThreads, 0, st>>>(scores, ws, s.nb, s.nb_valid, tiles);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   entropy_finish<<<(unsigned)s.B, 1024, 0, st>>>(ws, entropy, s.nb, s.nb_valid, s.Hh, tiles);
