@@ -307,3 +307,27 @@ def test_fused_attention_rejects_gates_without_coarse():
     assert L.usv_status_string(rc).decode() == "USV_ERR_INVALID_ARG" and b"coarse" in L.usv_last_error()
     rc = L.usv_block_sparse_attn_fused(*args, FAKE + 8, None, None, binding.USV_BF16, FAKE, None, None)
     assert L.usv_status_string(rc).decode() == "USV_ERR_INVALID_ARG"
+
+
+def _run_bench(*args):
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    return subprocess.run([sys.executable, os.path.join(root, "bench.py"), *args], capture_output=True, text=True,
+                          timeout=300)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = _run_bench("--gpus", "2")
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_bench_fails_loudly_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("checks the no-GPU error path")
+    r = _run_bench("--steps", "1", "--warmup", "0")
+    assert r.returncode != 0
+    assert "no CPU fallback" in (r.stdout + r.stderr)
+    assert "{" not in r.stdout  # no result line is printed
