@@ -361,6 +361,10 @@ def entropy_allocate(h, rho_bar, gamma, rho_min, rho_max):
     """Per-layer sparsity from per-layer entropies h[l]: w = (1 - h)^gamma, rho[l] = clip(rho_bar * w[l] / mean(w))."""
     h = _f64(h)
     w = (1.0 - h) ** gamma
+    if w.mean() == 0.0:
+        # every layer at entropy 1: the ratio w / mean(w) is 0/0 and no layer is told apart from
+        # another, so the base sparsity stands (Section 3.4 redistributes a budget, it does not create one)
+        return np.clip(np.full(h.shape, float(rho_bar)), rho_min, rho_max)
     return np.clip(rho_bar * w / w.mean(), rho_min, rho_max)
 
 

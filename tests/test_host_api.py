@@ -250,7 +250,11 @@ def test_entropy_allocate_matches_oracle():
     h = rng.uniform(0, 1, size=16).astype(np.float32)
     assert abs(binding.entropy_allocate(h, 0.8, 2.0, 0.0, 100.0).mean() - 0.8) < 1e-6
     # all layers at entropy 1: no weight anywhere, the base schedule is kept
-    assert binding.entropy_allocate([1.0, 1.0], 0.7, 2.0, 0.0, 1.0).tolist() == pytest.approx([0.7, 0.7])
+    for hs, bar, lo, hi in [([1.0, 1.0], 0.7, 0.0, 1.0), ([1.0] * 5, 0.7, 0.0, 0.6), ([1.0], 0.2, 0.3, 0.9)]:
+        got = binding.entropy_allocate(hs, bar, 2.0, lo, hi)
+        ref = orc.entropy_allocate(np.asarray(hs, dtype=np.float64), bar, 2.0, lo, hi)
+        assert np.isfinite(ref).all()
+        np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-7)
 
 
 def test_entropy_calls_reject_bad_arguments():

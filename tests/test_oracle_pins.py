@@ -529,6 +529,14 @@ def test_entropy_allocate_properties():
     g1 = orc.entropy_allocate([0.2, 0.6], 0.5, 1.0, 0.0, 1.0)
     g4 = orc.entropy_allocate([0.2, 0.6], 0.5, 4.0, 0.0, 1.0)
     assert g4[0] - g4[1] > g1[0] - g1[1] > 0
+    # every layer at entropy 1 (all weights zero, the ratio is 0/0): the base sparsity is kept, clipped;
+    # it is also the limit of equal entropies h -> 1 (equal weights give rho_bar whatever their size)
+    np.testing.assert_array_equal(orc.entropy_allocate([1.0, 1.0, 1.0], 0.7, 2.0, 0.0, 1.0), [0.7, 0.7, 0.7])
+    np.testing.assert_array_equal(orc.entropy_allocate([1.0, 1.0], 0.7, 2.0, 0.0, 0.6), [0.6, 0.6])
+    near = orc.entropy_allocate([1.0 - 1e-9] * 3, 0.7, 2.0, 0.0, 1.0)
+    np.testing.assert_allclose(near, 0.7, rtol=1e-12)
+    # one layer with weight, the others without: no special case
+    np.testing.assert_allclose(orc.entropy_allocate([1.0, 0.5], 0.4, 1.0, 0.0, 1.0), [0.0, 0.8], rtol=1e-14)
 
 
 # --------------------------------------------------------------------------- #
