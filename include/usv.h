@@ -151,8 +151,8 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v,
                                  void* stream);
 
 /*
- * Cube-level branch and fusion (Figure 2, right: the branch outputs are "broadcast
- * back to the full token grid, and fused to produce the final block output";
+ * Cube-level branch and fusion (Figure 2, right: each branch's result is spread over
+ * the whole token grid again and the branches are then combined into one output;
  * Section 2.2: the coarse level of the coarse-to-fine scheme).  The paper prints
  * no formula for either; the readings, following the coarse-to-fine sparse
  * attention it builds on:

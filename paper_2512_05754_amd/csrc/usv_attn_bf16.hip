@@ -119,7 +119,9 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {  // LDS byte ad
 // instruction offset applies to both addresses).  Inline assembly so that the compiler does not
 // pair the DMA with a conservative "wait for all memory" before the next LDS read of ANOTHER slot;
 // completion is awaited explicitly (vmcnt) where the pipeline needs it.  M0 carries the LDS
-// address; nothing else in this kernel uses M0.
+// address; nothing else in this kernel uses M0 (no LDS-direct reads, no relative register indexing: every
+// register array is indexed by compile-time constants), and the compiler refuses M0 on a clobber list (reserved
+// register), so every block writes M0 itself right before the instructions that read it.
 template <int N>
 __device__ __forceinline__ void dma_tile(const void* gbase, const int (&voff)[N], unsigned lds_addr);
 template <>
@@ -357,7 +359,10 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   // folds into the instruction.  On entry K(n) is in LDS and visible to every wave and the slot of
   // V(n-1) is free.  A freed slot of item e is refilled with item e + SLOTS.  STEADY (compile time)
   // says that tile n+LEAD exists, which spares the main loop every end-of-list check.
-  const int partial_j = (Nv % kBlock) ? (Nv / kBlock) : -1;  // the only block with padded keys, if any
+  // blocks from this one on hold padded keys: the partial block (if Nv is not a multiple of 64) and, when the
+  // tensors are padded by whole blocks, every block behind it.  A caller's list may name those too: all of
+  // their keys are masked, as the masked-attention equation has it (they then add nothing to the row).
+  const int first_padded_j = Nv / kBlock;
   auto tile_step = [&](auto phase_c, auto steady_c, int n) {
     constexpr int phase = decltype(phase_c)::value;
     constexpr int kslot = (2 * phase) % kSlots, vslot = (2 * phase + 1) % kSlots;
@@ -416,8 +421,8 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     jq[QD] = list_at(n + 1 + QD);
 
     // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
-    if (j == partial_j) {
-      const int lim = (Nv % kBlock) - (kh * 32 + 4 * g);  // valid keys of the tile ahead of this lane's first
+    if (j >= first_padded_j) {
+      const int lim = Nv - j * kBlock - (kh * 32 + 4 * g);  // valid keys of the tile ahead of this lane's first
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = (8 * (r >> 2) + (r & 3)) < lim ? s[r] : -INFINITY;
     }
@@ -561,7 +566,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     const float a0 = fast_exp2(m - m_ref), a1 = fast_exp2(m1 - m_ref);
     const float lt = l_row * a0 + l1 * a1;
     const int token = i * kBlock + qh * 32 + col;
-    const bool live = token < Nv && n_list > 0;
+    const bool live = token < Nv && lt > 0.f;  // lt == 0: empty list, or every listed key is padding
     const float inv = live ? 1.f / lt : 0.f;
     const float w0 = live ? a0 * inv : 0.f, w1 = live ? a1 * inv : 0.f;
 #pragma unroll

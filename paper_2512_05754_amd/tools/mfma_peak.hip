@@ -3,9 +3,7 @@
 // DATA: with constant operands the clock stays near its maximum, with operands distributed like real
 // activations the chip throttles (power), so both are reported.  This is the practical ceiling the
 // attention kernel's roofline fraction should be read against; the nominal peak is 2.5 PFLOP/s.
-// Usage: mfma_peak                       prints one JSON object;
-//        mfma_peak hold <0|1> <seconds>  keeps the loop running with constant (0) or Gaussian (1) operands, for
-//                                        watching clock and power from another shell (amd-smi metric -p -c).
+// Usage: mfma_peak    prints one JSON object.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -58,7 +56,8 @@ static float gauss() {  // Irwin-Hall approximation of N(0,1): enough for a powe
   } while (0)
 
 int main(int argc, char** argv) {
-  const bool hold = argc == 4 && strcmp(argv[1], "hold") == 0;
+  (void)argc;
+  (void)argv;
   hipDeviceProp_t prop;
   CK(hipGetDeviceProperties(&prop, 0));
   const int cus = prop.multiProcessorCount;
@@ -73,16 +72,8 @@ int main(int argc, char** argv) {
   srand(1);
   double best[2] = {0, 0};
   for (int mode = 0; mode < 2; ++mode) {
-    if (hold && mode != atoi(argv[2])) continue;
     for (int i = 0; i < 4096 * 8; i++) host[i] = to_bf16(mode == 0 ? 1.0f : gauss() * 2.2f);
     CK(hipMemcpy(data, host, 4096 * 16, hipMemcpyHostToDevice));
-    if (hold) {
-      const double per_launch_s = 0.01;  // ~10 ms launches at 2 waves per SIMD
-      const int launches = (int)(atof(argv[3]) / per_launch_s);
-      for (int i = 0; i < launches; ++i) mfma_loop<<<cus * 2, 256>>>(data, out, 5000);
-      CK(hipDeviceSynchronize());
-      return 0;
-    }
     for (int waves = 2; waves <= 3; ++waves) {
       const int grid = cus * waves, iters = 5000;
       mfma_loop<<<grid, 256>>>(data, out, 1000);  // warm the clocks

@@ -22,7 +22,15 @@ def run_and_check(usv, w, n_samples, budgets=None, out_dtype=torch.float32, chec
     S = usv.block_scores(q, k, seq_valid=w.seq_valid)
     idx, cnt = usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, kmax=w.kmax,
                                budgets=None if budgets is None else gu.up(budgets))
-    out, lse = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, return_lse=True, out_dtype=out_dtype)
+    out, lse = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, return_lse=True, out_dtype=torch.float32)
+    if out_dtype == torch.bfloat16:
+        # the bf16-stored result is the fp32-stored one rounded to nearest even, bit for bit, at every element;
+        # the oracle comparison below is then made on the fp32-stored result, to the strict bounds
+        out_bf, lse_bf = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, return_lse=True,
+                                               out_dtype=torch.bfloat16)
+        gu.assert_bf16_store_is_rne(out_bf, out, w.name)
+        assert torch.equal(lse_bf.view(torch.int32), lse.view(torch.int32))
+        del out_bf, lse_bf
     torch.cuda.synchronize()
     S_h, idx_h, cnt_h = gu.down(S), gu.down(idx), gu.down(cnt)
 
@@ -46,14 +54,14 @@ def run_and_check(usv, w, n_samples, budgets=None, out_dtype=torch.float32, chec
         assert np.array_equal(idx_h[b, h], ridx[0, 0]) and np.array_equal(cnt_h[b, h], rcnt[0, 0])
 
     # stage 3: sampled query blocks + the last block of each sampled head
-    per_head = max(1, n_samples // len(sample_heads))
+    per_head = -(-n_samples // len(sample_heads))  # rounded up: at least n_samples (head, query block) rows in all
     worst = (0.0, 0.0)
     for b, h in sample_heads:
         blocks = sorted(set(rng.choice(w.nb, size=per_head, replace=False).tolist()) | {w.nb - 1, 0})
         ref = gu.oracle_attn_blocks(Q[b, h], K[b, h], V[b, h], idx_h[b, h], cnt_h[b, h], w.seq_valid, blocks)
         got = np.stack([gu.down(out[b, h, i * 64:(i + 1) * 64]) for i in blocks])
         want = np.stack([ref[i][0] for i in blocks])
-        mx, mean = gu.assert_attn_close(got, want, w.dtype, out_dtype != torch.float32, f"{w.name} head {(b, h)}")
+        mx, mean = gu.assert_attn_close(got, want, w.dtype, f"{w.name} head {(b, h)}")
         worst = (max(worst[0], mx), max(worst[1], mean))
         got_lse = np.stack([gu.down(lse[b, h, i * 64:(i + 1) * 64]) for i in blocks])
         want_lse = np.stack([ref[i][1] for i in blocks])
@@ -75,12 +83,12 @@ def test_wan13_480p_keep10(usv):
 
 
 def test_wan13_480p_keep10_bf16_output(usv):
-    run_and_check(usv, synth.WAN13_480P, n_samples=24, out_dtype=torch.bfloat16, check_all_topk=False)
+    run_and_check(usv, synth.WAN13_480P, n_samples=64, out_dtype=torch.bfloat16, check_all_topk=False)
 
 
 @pytest.mark.parametrize("ratio", [1.0, 0.5, 0.25, 0.05])
 def test_wan13_480p_sweep(usv, ratio):
-    run_and_check(usv, synth.sweep(ratio), n_samples=12 if ratio >= 0.5 else 24, check_all_topk=False)
+    run_and_check(usv, synth.sweep(ratio), n_samples=64, check_all_topk=False)
 
 
 def test_merged_ragged_budgets(usv):
@@ -89,7 +97,7 @@ def test_merged_ragged_budgets(usv):
 
 
 def test_wan14_720p_keep5(usv):
-    run_and_check(usv, synth.WAN14_720P, n_samples=36, check_all_topk=False)
+    run_and_check(usv, synth.WAN14_720P, n_samples=64, check_all_topk=False)
 
 
 def test_maximum_supported_block_count(usv):

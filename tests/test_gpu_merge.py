@@ -126,7 +126,7 @@ def test_merge_then_attention_then_unmerge(usv):
     ridx, rcnt = orc.select_topk(gu.down(S), 2, Nm)
     np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
     ref = orc.unmerge_apply(orc.block_sparse_attn(qm, km, vm, ridx, rcnt, Nm)[0], rr)
-    gu.assert_attn_close(out, ref, "bf16", False, "merged pipeline")
+    gu.assert_attn_close(out, ref, "bf16", "merged pipeline")
 
 
 def test_full_size_480p_half_merged(usv):

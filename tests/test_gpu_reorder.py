@@ -97,7 +97,7 @@ def test_pipeline_from_raster_tokens(usv):
     np.testing.assert_array_equal(idx.cpu().numpy(), ridx)
     np.testing.assert_array_equal(cnt.cpu().numpy(), rcnt)
     ref = orc.cube_scatter(orc.block_sparse_attn(Qo, Ko, Vo, ridx, rcnt, w.seq_valid)[0], grid, cube)
-    gu.assert_attn_close(o_raster, ref, "bf16", False, "raster pipeline")
+    gu.assert_attn_close(o_raster, ref, "bf16", "raster pipeline")
 
 
 @pytest.mark.parametrize("grid,Hh,dtype", [((21, 30, 52), 12, "bf16"), ((21, 30, 52), 12, "f32"), ((21, 45, 80), 40, "bf16")],
