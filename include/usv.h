@@ -80,6 +80,27 @@ usv_status usv_block_scores(const void* q, const void* k, const usv_shape* shape
                             float* scores, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * usv_block_scores for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * same kernels, with the pooled means kept in a static device array of
+ * USV_STATIC_SCRATCH_BYTES that is part of the library image instead of in a
+ * caller workspace.  The call allocates and frees nothing; the caller still
+ * passes q, k and scores.  Same results as usv_block_scores, bit for bit.
+ *
+ * Limit: usv_workspace_bytes(shape) <= USV_STATIC_SCRATCH_BYTES (64 MiB; the
+ * 480p shape needs 6.3 MB, the 720p shape 48.4 MB), else USV_ERR_WORKSPACE and
+ * nothing is launched.  Every GPU the library is used on holds its own copy of
+ * the array until the process ends.  All calls on one GPU share that copy:
+ * calls that can overlap on one GPU (different streams, different threads)
+ * race on it and must be ordered by the caller.  The first call on a device
+ * looks the array's address up (no allocation); make that call outside graph
+ * capture.
+ */
+#define USV_STATIC_SCRATCH_BYTES (64u << 20)
+usv_status usv_block_scores_static(const void* q, const void* k, const usv_shape* shape,
+                                   float* scores, void* stream);
+
+/*
  * Stage 2 - per-query-block top-k key-block selection ("top-k cube selection",
  * Figure 2).  For every row (b, h, i) with i a block holding a valid token:
  *   candidates = key blocks j that hold a valid token

@@ -6,6 +6,7 @@ package (for example for its input generators) never needs the GPU.
 
 _BINDING_NAMES = (
     "block_scores",
+    "block_scores_static",
     "select_topk",
     "block_sparse_attn",
     "merge_similarity",

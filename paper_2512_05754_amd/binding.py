@@ -18,6 +18,7 @@ USV_F32, USV_BF16 = 0, 1
 EXPORTED_SYMBOLS = (
     "usv_workspace_bytes",
     "usv_block_scores",
+    "usv_block_scores_static",
     "usv_select_topk",
     "usv_select_topk_ex",
     "usv_coarse_workspace_bytes",
@@ -99,6 +100,7 @@ def lib() -> ctypes.CDLL:
     sp = ctypes.POINTER(UsvShape)
     L.usv_workspace_bytes.restype, L.usv_workspace_bytes.argtypes = sz, [sp]
     L.usv_block_scores.restype, L.usv_block_scores.argtypes = i32, [vp, vp, sp, vp, vp, sz, vp]
+    L.usv_block_scores_static.restype, L.usv_block_scores_static.argtypes = i32, [vp, vp, sp, vp, vp]
     L.usv_select_topk.restype, L.usv_select_topk.argtypes = i32, [vp, sp, i32, vp, i32, vp, vp, vp]
     L.usv_select_topk_ex.restype = i32
     L.usv_select_topk_ex.argtypes = [vp, sp, i32, vp, i32, ctypes.c_uint32, vp, vp, vp]
@@ -192,6 +194,19 @@ def block_scores(q, k, seq_valid=None, out=None, workspace=None):
             _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream(),
         )
     )
+    return out
+
+
+def block_scores_static(q, k, out, seq_valid=None):
+    """usv_block_scores_static: stage 1 without a workspace; `out` [B, Hh, nb, nb] fp32 is the caller's."""
+    sh = _shape_of(q, seq_valid)
+    if k.shape != q.shape or k.dtype != q.dtype:
+        raise ValueError("k must match q in shape and dtype")
+    nb = sh.seq_len // BLOCK
+    if tuple(out.shape) != (sh.batch, sh.heads, nb, nb):
+        raise ValueError("out must be [B, Hh, nb, nb]")
+    _check(lib().usv_block_scores_static(_dev(q, "q"), _dev(k, "k"), ctypes.byref(sh),
+                                         _dev(out, "scores", torch.float32), _stream()))
     return out
 
 

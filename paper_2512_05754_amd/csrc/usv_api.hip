@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "usv_internal.h"
 
@@ -151,6 +152,54 @@ usv_status usv_block_scores(const void* q, const void* k, const usv_shape* shape
     return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
   return hip_result(usv::launch_block_scores(q, k, s, scores, static_cast<float*>(ws), static_cast<hipStream_t>(stream)),
                     "usv_block_scores launch");
+}
+
+// ---- stage 1 for callers that cannot allocate: the pooled means live in a static device array ----------
+namespace {
+
+// Each GPU the library runs on holds its own copy of this array, at its own address, until the process ends.
+// In host code the name is only a handle for hipGetSymbolAddress: the per-device address it returns is what
+// kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[USV_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, resolved on first use
+
+usv_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(USV_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(USV_ERR_UNSUPPORTED, "device ordinal %d is beyond %d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // the current device's copy
+    if (e != hipSuccess || !p) return fail(USV_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return USV_OK;
+}
+
+}  // namespace
+
+usv_status usv_block_scores_static(const void* q, const void* k, const usv_shape* shape, float* scores, void* stream) {
+  usv::Dims s;
+  USV_TRY(check_shape(shape, true, &s));
+  USV_TRY(check_ptr(q, "q"));
+  USV_TRY(check_ptr(k, "k"));
+  USV_TRY(check_ptr(scores, "scores"));
+  const size_t need = usv_workspace_bytes(shape);
+  if (need > (size_t)USV_STATIC_SCRATCH_BYTES)
+    return fail(USV_ERR_WORKSPACE, "the pooled means of this shape need %zu bytes, the static scratch holds %zu: use usv_block_scores",
+                need, (size_t)USV_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  USV_TRY(static_scratch(&ws));
+  // every element of the scratch that the product kernel reads is written by the pooling kernel of this
+  // same call first (same stream), so nothing needs clearing between calls
+  return hip_result(usv::launch_block_scores(q, k, s, scores, static_cast<float*>(ws), static_cast<hipStream_t>(stream)),
+                    "usv_block_scores_static launch");
 }
 
 usv_status usv_select_topk(const float* scores, const usv_shape* shape, int32_t k, const int32_t* budgets,
