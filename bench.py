@@ -129,13 +129,12 @@ def cpu_baseline(w, Q, K, V, n_heads, two_branch=False):
 
 
 def measured_traffic(workload_name, key="attn_hbm_bytes_per_launch"):
-    """HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc runs summarised under profiles/ (null if none)."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
-    try:
-        with open(path) as f:
-            return json.load(f).get(workload_name, {}).get(key)
-    except (OSError, ValueError):
-        return None
+    """{"traffic": HBM bytes per launch of the dominant kernel, "traffic_source": provenance} from the rocprofv3 --pmc
+    runs summarised under profiles/; traffic is null when none was recorded or when the kernel sources changed since."""
+    from paper_2512_05754_amd import traffic
+
+    value, source = traffic.lookup(workload_name, key)
+    return {"traffic": value, "traffic_source": source}
 
 
 def mfma_only_peak():
@@ -220,7 +219,7 @@ def reorder_main(args):
         "roofline": {"kernel": "usv_cube_gather (cube_move<true, 16>)", "bound": "hbm",
                      "achieved": gather_bytes / (gather_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": gather_bytes / (gather_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                     "traffic": measured_traffic("reorder:" + w.name, "gather_hbm_bytes_per_launch"),
+                     **measured_traffic("reorder:" + w.name, "gather_hbm_bytes_per_launch"),
                      "avg_launch_ms": gather_ms},
     }
     if not args.no_cpu_baseline:
@@ -319,7 +318,7 @@ def merge_main(args):
         "roofline": {"kernel": "usv_merge_apply (merge_rows<bf16, 128>)", "bound": "hbm",
                      "achieved": bytes_apply / (apply_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": bytes_apply / (apply_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                     "traffic": measured_traffic("merge:" + w.name, "apply_hbm_bytes_per_launch"), "avg_launch_ms": apply_ms},
+                     **measured_traffic("merge:" + w.name, "apply_hbm_bytes_per_launch"), "avg_launch_ms": apply_ms},
     }
     if not args.no_cpu_baseline:
         from oracle import usv_oracle as orc
@@ -526,7 +525,7 @@ def main():
             "peak": PEAK_BF16_TFLOPS if w.dtype == "bf16" else 157.3,
             "unit": "TFLOP/s",
             "frac": flop / (avg[2] * 1e-3) / 1e12 / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else 157.3),
-            "traffic": measured_traffic(w.name),
+            **measured_traffic(w.name),
             "avg_launch_ms": float(avg[2]),
         },
     }
@@ -539,7 +538,7 @@ def main():
                                     "usv_block_scores_raster + usv_select_topk_ex + usv_coarse_attn_raster + "
                                     "usv_block_sparse_attn_raster_fused + usv_attn_entropy")
         result["roofline"]["kernel"] = "usv_block_sparse_attn_raster (attn_bf16, raster addressing)"
-        result["roofline"]["traffic"] = measured_traffic("raster:" + w.name)
+        result["roofline"].update(measured_traffic("raster:" + w.name))
     if two_branch:
         c_ms = float(np.mean([evs[i][2].elapsed_time(branch_events[i][0]) for i in range(args.steps)]))
         a_ms = float(np.mean([branch_events[i][0].elapsed_time(branch_events[i][1]) for i in range(args.steps)]))

@@ -7,26 +7,31 @@
 //   are merged once, at the end, through LDS.  All four waves share the K/V tile in LDS, so a
 //   tile is fetched from L2/HBM once per query block.
 //
-// Matrix-core mapping (v_mfma_f32_32x32x16_bf16, fp32 accumulate):
-//   S^T (32 keys x 32 queries) = K_tile (A operand, rows = keys) x Q^T (B operand, cols = queries)
-//   O^T (32 d    x 32 queries) = V^T    (A operand, rows = d)    x P^T (B operand, cols = queries)
-// Working on the transposes puts one query per lane column: row max, row sum and the rescale
-// factor are per-lane values, and the S^T accumulator registers are, as they stand, the P^T
-// operand of the second product (the contraction index of an MFMA can be enumerated in any
-// order as long as both operands agree, so V^T is read in the order the accumulator holds keys).
+// Matrix-core mapping (v_mfma_f32_16x16x32_bf16, fp32 accumulate; lane = (c, G) with c = lane % 16,
+// G = lane / 16; the A operand holds row c, contraction slots 8 G .. 8 G + 7, the B operand column c
+// and the same slots, the result column c, rows 4 G .. 4 G + 3):
+//   S^T (16 keys x 16 queries) = K_tile (A, rows = keys) x Q^T (B, cols = queries), 4 steps over d = 128
+//   O^T (16 d    x 16 queries) = V^T    (A, rows = d)    x P^T (B, cols = queries), ONE step over 32 keys
+// A wave's 32 keys x 32 queries are 2 x 2 such tiles.  Working on the transposes keeps a query in a
+// lane column: lane (c, G) holds queries c and 16 + c, eight keys of each (16 mt + 4 G + r), and those
+// eight S^T accumulator values are, as they stand, the eight contraction slots of the P^T operand for
+// that query (the contraction index of an MFMA can be enumerated in any order as long as both operands
+// agree, so V^T is read in the order the accumulators hold the keys).  Row statistics therefore stay
+// in the lane; only a raise of the reference maximum (rare) looks across the four lanes of a query.
 // V^T fragments come from the row-major V tile with the LDS transpose read ds_read_b64_tr_b16.
+// The 16x16x32 shape was chosen over 32x32x16 by measurement: the same flops draw less power, and
+// under this kernel the chip runs at its power limit, where less energy per tile is more clock.
 //
 // What bounds the kernel, measured on MI355X: a wavefront issues at most one instruction (of any
-// kind) every ~8 clocks, a 32x32x16 MFMA occupies the matrix pipe for 32 clocks, and the CU's
-// vector-memory path moves 64 B/clk (a 64x64 tile needs 32 KiB of K and V: 512 clocks, the same
-// as its 16 MFMAs per SIMD).  With two workgroups per CU the chip then sits at its power limit
+// kind) every ~8 clocks, a tile's 32 MFMAs per wave occupy the matrix pipe for 512 clocks, and the
+// CU's vector-memory path moves 64 B/clk (a 64x64 tile needs 32 KiB of K and V: 512 clocks as
+// well).  With two workgroups per CU the chip then sits at its power limit
 // (it clocks this kernel at ~1.7 GHz of 2.4) and, for lists without locality, near what the
 // L2-miss path delivers (~7 TB/s), so every instruction and every byte moved costs clock.
 // The design goal is therefore few instructions per tile and two or three
 // workgroups per CU (waves per SIMD) that cover each other's issue gaps and waits:
-//   - <= 168 VGPRs, so that three workgroups fit where the LDS ring allows it;
 //   - K/V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no register
-//     staging, M0 set once per tile) through a ring of 3 or 5 tile slots K(n), V(n), K(n+1), ...;
+//     staging, M0 set once per tile) through a ring of tile slots K(n), V(n), K(n+1), ... (3 as launched);
 //     a slot is refilled as soon as the barrier after its last reader has passed;
 //   - the 16-byte chunks of a row are XOR-permuted on the way in (applied to the global address;
 //     the LDS side of the DMA is lane-linear) so that both the 16-byte K fragment reads and the
@@ -45,7 +50,29 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
 typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8v;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// Accumulators are kept four 16x16 tiles to a 16-register tuple and the MFMAs work on quarter q of it:
+// with one allocation unit per tuple the compiler updates the accumulators in place (given 64 separate
+// 4-register values it rotated them through fresh registers and copied all of them back on every tile).
+__device__ __forceinline__ f32x4 quarter(const f32x16& v, int q) {
+  switch (q) {
+    case 0: return __builtin_shufflevector(v, v, 0, 1, 2, 3);
+    case 1: return __builtin_shufflevector(v, v, 4, 5, 6, 7);
+    case 2: return __builtin_shufflevector(v, v, 8, 9, 10, 11);
+    default: return __builtin_shufflevector(v, v, 12, 13, 14, 15);
+  }
+}
+__device__ __forceinline__ void set_quarter(f32x16& v, int q, const f32x4& c) {
+  const f32x16 w = __builtin_shufflevector(c, c, 0, 1, 2, 3, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1);
+  switch (q) {
+    case 0: v = __builtin_shufflevector(v, w, 16, 17, 18, 19, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15); break;
+    case 1: v = __builtin_shufflevector(v, w, 0, 1, 2, 3, 16, 17, 18, 19, 8, 9, 10, 11, 12, 13, 14, 15); break;
+    case 2: v = __builtin_shufflevector(v, w, 0, 1, 2, 3, 4, 5, 6, 7, 16, 17, 18, 19, 12, 13, 14, 15); break;
+    default: v = __builtin_shufflevector(v, w, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 16, 17, 18, 19); break;
+  }
+}
 
 constexpr int kThreads = 256;
 constexpr float kRescaleSlack = 8.0f;  // log2 units
@@ -67,10 +94,11 @@ struct Tile {
   static constexpr int kRowsPerDma = 1024 / kRowBytes;
   // K: lanes 0..15 of a fragment read hit 16 consecutive rows at one chunk column.
   __device__ static int k_swz(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
-  // V: one LDS cycle of a transposing read covers 4 consecutive rows x 4 consecutive chunks (one
-  // 64-byte group); XOR-ing the group index with the row spreads the 4 rows over all banks.  Rows
-  // r, r+8, r+16 share the permutation, so the fragment addresses differ by constants.
-  __device__ static int v_swz(int row) { return D == 128 ? ((row & 3) << 2) : ((row & 1) << 2); }
+  // V: a transposing read addresses, per 16-lane group, 4 consecutive rows x 32 bytes (2 chunks) and
+  // one LDS cycle serves two groups, i.e. 8 consecutive rows at the same pair of chunks; XOR-ing the
+  // chunk-pair index with the row spreads those 8 rows over all banks.  Rows r and r + 16 share the
+  // permutation, so the two reads of a fragment differ by a constant.
+  __device__ static int v_swz(int row) { return D == 128 ? ((row & 7) << 1) : (((row >> 1) & 3) << 1); }
   __device__ static int k_off(int row, int chunk) { return row * kRowBytes + ((chunk ^ k_swz(row)) << 4); }
   __device__ static int v_off(int row, int chunk) { return row * kRowBytes + ((chunk ^ v_swz(row)) << 4); }
 };
@@ -83,8 +111,8 @@ __device__ __forceinline__ float4 load_bf16x4(const uint16_t* p) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Lanes l and l ^ 32 hold the two key halves of one query.  v_permlane32_swap on two copies of x
-// leaves (x of the low lane, x of the high lane) in both lanes: one VALU op, no LDS round trip.
+// v_permlane32_swap on two copies of x leaves (x of lane l % 32, x of lane l % 32 + 32) in both lanes:
+// one VALU op, no LDS round trip.
 __device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
   const unsigned u = __float_as_uint(x);
   const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
@@ -92,22 +120,41 @@ __device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
   hi = __uint_as_float(r[1]);
 }
 
-// Max of the 16 accumulator registers in 8 instructions.  One assembly block: v_max3 without the
-// NaN-quieting moves the compiler adds around fmaxf (the inputs are never NaN).
-__device__ __forceinline__ float max16(const f32x16& s) {
-  float a, b;
+// Max of the 8 accumulator values a lane holds for one query, in 4 instructions.  One assembly block:
+// v_max3 without the NaN-quieting moves the compiler adds around fmaxf (the inputs are never NaN).
+__device__ __forceinline__ float max8(float a0, float a1, float a2, float a3, float b0, float b1, float b2, float b3) {
+  float x, y;
   asm("v_max3_f32 %0, %2, %3, %4\n\t"
       "v_max3_f32 %1, %5, %6, %7\n\t"
       "v_max3_f32 %0, %0, %8, %9\n\t"
-      "v_max3_f32 %1, %1, %10, %11\n\t"
-      "v_max3_f32 %0, %0, %12, %13\n\t"
-      "v_max3_f32 %1, %1, %14, %15\n\t"
-      "v_max3_f32 %0, %0, %16, %17\n\t"
-      "v_max3_f32 %0, %0, %1, %1"
-      : "=&v"(a), "=&v"(b)
-      : "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]), "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]), "v"(s[8]),
-        "v"(s[9]), "v"(s[10]), "v"(s[11]), "v"(s[12]), "v"(s[13]), "v"(s[14]), "v"(s[15]));
-  return a;
+      "v_max_f32 %0, %0, %1"
+      : "=&v"(x), "=&v"(y)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(b0), "v"(b1), "v"(b2), "v"(b3));
+  return x;
+}
+
+// The four lanes c, c + 16, c + 32, c + 48 hold the keys of one query.  v_permlane16_swap on two copies
+// of x leaves (x of the even 16-lane row, x of the odd row) of each row pair in both rows, and
+// v_permlane32_swap does the same for the two wave halves: two VALU ops per step, no LDS round trip.
+__device__ __forceinline__ void row_pair(float x, float& even, float& odd) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  even = __uint_as_float(r[0]);
+  odd = __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float max_over_groups(float x) {
+  float a, b;
+  row_pair(x, a, b);
+  x = fmaxf(a, b);
+  both_halves(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_over_groups(float x) {
+  float a, b;
+  row_pair(x, a, b);
+  x = a + b;
+  both_halves(x, a, b);
+  return a + b;
 }
 
 __device__ __forceinline__ unsigned lds_address(const void* p) {  // LDS byte address of a __shared__ pointer
@@ -165,15 +212,15 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
                                                                 float p_shift, int total, int per_xcd, FuseArgs fuse,
                                                                 RasterArgs ras) {
   using T = Tile<D>;
-  constexpr int KSTEPS = D / 16;  // MFMA k-steps of the QK^T product
-  constexpr int DSUB = D / 32;    // 32-wide d sub-tiles of the output
+  constexpr int KS = D / 32;  // MFMA k-steps of the QK^T product
+  constexpr int DT = D / 16;  // 16-wide d sub-tiles of the output
   constexpr int kDma = T::kDmaPerWave;
   constexpr int kSlots = SLOTS;
   constexpr int LEAD = (SLOTS - 1) / 2;
   static_assert(SLOTS % 2 == 1 && SLOTS >= 3, "odd ring: K items land on the slots V items left and vice versa");
-  constexpr int XROWS = DSUB * 16 + 2;  // exchange rows per wave: O registers, m, l
-  constexpr int OSTRIDE = D + 4;        // fp32 staging row stride (floats), bank-spread
-  static_assert(XROWS * 64 == 32 * OSTRIDE, "the staging rows of a query half overlay its exchange area");
+  constexpr int XROWS = DT * 8 + 4;  // exchange rows per wave: O registers, m and l of its two queries per lane
+  constexpr int OSTRIDE = D + 4;     // fp32 staging row stride (floats), bank-spread
+  static_assert(XROWS * 64 >= 32 * OSTRIDE, "the staging rows of a query half overlay its exchange area");
   constexpr int kEpilogueBytes = 2 * XROWS * 64 * 4;
   constexpr int kSmem = kSlots * T::kBytes > kEpilogueBytes ? kSlots * T::kBytes : kEpilogueBytes;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kSmem];
@@ -191,7 +238,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction; keep it scalar
   const int qh = wave & 1, kh = wave >> 1;
-  const int col = lane & 31, g = lane >> 5;
+  const int c16 = lane & 15, G = lane >> 4;  // MFMA lane coordinates: column / row within a 16-row group, group
   const int n_list = min(max(cnt[work], 0), kmax);  // device contents are not trusted with addresses:
   const int32_t* list = idx + (long long)work * kmax;
   const uint16_t* kbase = k + head_off;
@@ -299,52 +346,65 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
 #pragma unroll
   for (int t = 0; t <= QD; ++t) jq[t] = list_at(t);
 
-  // Q fragments: lane holds query row 32*qh + col, channels 16 t + 8 g .. + 8 for every k-step t
-  bf16x8 qf[KSTEPS];
-  {
-    const uint16_t* qp = q + head_off + (long long)(i * kBlock + qh * 32 + col) * D + g * 8;
+  // Q fragments: for query tile nt the lane holds query row 32*qh + 16*nt + c16, channels 32 t + 8 G .. + 8
+  // for every k-step t
+  bf16x8 qf[2][KS];
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const int qrow = i * kBlock + qh * 32 + 16 * nt + c16;
+    const uint16_t* qp = q + head_off + (long long)qrow * D + G * 8;
     if constexpr (RASTER)
       qp = reinterpret_cast<const uint16_t*>(reinterpret_cast<const unsigned char*>(q) + ras_off +
-                                             (long long)ras.order[i * kBlock + qh * 32 + col] * ras.tok) + g * 8;
+                                             (long long)ras.order[qrow] * ras.tok) + G * 8;
 #pragma unroll
-    for (int t = 0; t < KSTEPS; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(qp + t * 16);
+    for (int t = 0; t < KS; ++t) qf[nt][t] = *reinterpret_cast<const bf16x8*>(qp + t * 32);
     if constexpr (RASTER) {
       // padding positions have no token: their query rows are zero, as in a gathered copy (their lanes
       // take part in the wave-wide rescale decisions, so what they hold is not quite without effect)
-      if (i * kBlock + qh * 32 + col >= Nv) {
+      if (qrow >= Nv) {
 #pragma unroll
-        for (int t = 0; t < KSTEPS; ++t)
+        for (int t = 0; t < KS; ++t)
 #pragma unroll
-          for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)0.0f;
+          for (int e = 0; e < 8; ++e) qf[nt][t][e] = (__bf16)0.0f;
       }
     }
   }
 
-  f32x16 o[DSUB];
+  // O^T accumulators: quarter dt % 4 of o[nt][dt / 4], element r = channel 16 dt + 4 G + r of query 32 qh + 16 nt + c16
+  constexpr int OT = (DT + 3) / 4;
+  f32x16 o[2][OT];
 #pragma unroll
-  for (int ds = 0; ds < DSUB; ++ds)
+  for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[ds][r] = 0.f;
-  float m = -INFINITY;  // running reference max (log2 domain), identical in both lane halves
-  float l = 0.f;        // this lane's partial row sum (its 16 keys per tile)
+    for (int k = 0; k < OT; ++k)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[nt][k][r] = 0.f;
+  // per query tile nt (this lane's two queries); each is identical in the four lanes of its query
+  float m[2] = {-INFINITY, -INFINITY};  // running reference max (log2 domain)
+  float l[2] = {0.f, 0.f};              // this lane's partial row sum (its 8 keys per tile)
   // derived from m, refreshed only when m moves (rare): the exponent offset and the raise threshold
-  float neg_m = 0.f;            // -m - p_shift, or 0 while every key seen so far was masked (m = -inf)
-  float m_raise = -INFINITY;    // m + kRescaleSlack
+  float neg_m[2] = {0.f, 0.f};                  // -m - p_shift, or 0 while every key seen so far was masked (m = -inf)
+  float m_raise[2] = {-INFINITY, -INFINITY};    // m + kRescaleSlack
 
   // per-lane LDS byte offsets of the fragment reads (loop invariant)
-  int kfrag[KSTEPS];
+  // K fragment of key tile mt, k-step t: key row 32 kh + 16 mt + c16, chunk 4 t + G; +16 rows is a constant
+  // (both tables are XOR patterns: kfrag[t] = kfrag[0] ^ (t << 6) and vfrag[dt] = vfrag[0] ^ (dt << 5), because the
+  // swizzles only touch address bits that t and dt alone set.  The three-workgroup shape has no registers to
+  // spare and derives the entries with one v_xor per use; the other shapes keep them in registers.)
+  constexpr bool kLean = WGS >= 3;
+  int kfrag[KS];
 #pragma unroll
-  for (int t = 0; t < KSTEPS; ++t) kfrag[t] = T::k_off(kh * 32 + col, 2 * t + g);
-  // V^T fragment of d sub-tile ds, k-step t: slots 0..3 are keys 16 t + 4 g + (0..3), slots 4..7
-  // keys 16 t + 8 + 4 g + (0..3) of this wave's half; +8 and +16 rows are constant byte offsets
-  int vfrag[DSUB];
+  for (int t = 0; t < KS; ++t) kfrag[t] = T::k_off(kh * 32 + c16, 4 * t + G);
+  // V^T fragment of d sub-tile dt: contraction slots 0..3 are keys 4 G + (0..3), slots 4..7 keys
+  // 16 + 4 G + (0..3) of this wave's half (the order the S^T accumulators hold them); the 16 lanes of a
+  // group address the 4 key rows x 16 channels that the transposing read hands out column by column
+  int vfrag[DT];
   {
-    const int l16 = lane & 15;
-    const int key0 = kh * 32 + 4 * g + (l16 >> 2);
+    const int key0 = kh * 32 + 4 * G + (c16 >> 2);
 #pragma unroll
-    for (int ds = 0; ds < DSUB; ++ds) {
-      const int dcol = 32 * ds + 16 * ((lane >> 4) & 1) + 4 * (l16 & 3);  // 4 channels = half a chunk
-      vfrag[ds] = T::v_off(key0, dcol >> 3) + ((dcol >> 2) & 1) * 8;
+    for (int dt = 0; dt < DT; ++dt) {
+      const int dcol = 16 * dt + 4 * (c16 & 3);  // 4 channels = half a chunk
+      vfrag[dt] = T::v_off(key0, dcol >> 3) + ((dcol >> 2) & 1) * 8;
     }
   }
 
@@ -352,7 +412,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   // pin the Q fragments here: otherwise the compiler sinks their loads into the loop and then waits
   // for "all outstanding loads" there, which would also wait for the tile prefetch it cannot see
 #pragma unroll
-  for (int t = 0; t < KSTEPS; ++t) asm volatile("" ::"v"(qf[t]));
+  for (int t = 0; t < KS; ++t) asm volatile("" ::"v"(qf[0][t]), "v"(qf[1][t]));
   __syncthreads();
 
   // One tile.  PHASE = n % SLOTS is a compile-time constant so that every LDS offset of the ring
@@ -377,25 +437,36 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     }
     if (steady) issue_k(j_pre, freed_v);  // item 2n-1+SLOTS = K(n+LEAD)
 
-    // ---- S^T = K Q^T over this wave's 32 keys --------------------------------------------
-    f32x16 s;
+    // ---- S^T = K Q^T over this wave's 32 keys x 32 queries: s[mt][nt] --------------------------
+    f32x16 s;  // quarter 2 mt + nt = tile (mt, nt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
     {
-      // fragments are read four at a time and awaited once per batch: every s_waitcnt costs the
+      // fragments are read in batches and awaited once per batch: every s_waitcnt costs the
       // wave an issue slot, and the other waves of the SIMD cover the LDS latency
       const unsigned char* kb = smem + kslot * T::kBytes;
-      constexpr int KB = WGS <= 2 ? (KSTEPS < 8 ? KSTEPS : 8) : 4;  // fragments per batch (register budget)
+      if constexpr (kLean) asm volatile("" : "+v"(kfrag[0]));  // keeps the XORs in the loop (hoisted, they are the table again)
+      constexpr int KB = WGS <= 2 ? KS : 1;  // k-steps per batch (register budget)
 #pragma unroll
-      for (int t0 = 0; t0 < KSTEPS; t0 += KB) {
-        bf16x8 kf[KB];
+      for (int t0 = 0; t0 < KS; t0 += KB) {
+        bf16x8 kf[KB][2];
 #pragma unroll
-        for (int t = 0; t < KB; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kb + kfrag[t0 + t]);
+        for (int t = 0; t < KB; ++t)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            kf[t][mt] = *reinterpret_cast<const bf16x8*>(kb + (kLean ? kfrag[0] ^ ((t0 + t) << 6) : kfrag[t0 + t]) +
+                                                         mt * 16 * T::kRowBytes);
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
         // the fences keep each batch together: reads, one wait, back-to-back MFMAs
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < KB; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t0 + t], s, 0, 0, 0);
+        for (int t = 0; t < KB; ++t)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+              set_quarter(s, 2 * mt + nt,
+                          __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][mt], qf[nt][t0 + t], quarter(s, 2 * mt + nt), 0, 0, 0));
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -420,87 +491,100 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     }
     jq[QD] = list_at(n + 1 + QD);
 
-    // register r of lane (col, g) is key 32 kh + 8 (r/4) + 4 g + (r%4) of the tile, query col
+    // s[8 mt + 4 nt + r] of lane (c16, G) is key 32 kh + 16 mt + 4 G + r of the tile, query 32 qh + 16 nt + c16
     if (j >= first_padded_j) {
-      const int lim = Nv - j * kBlock - (kh * 32 + 4 * g);  // valid keys of the tile ahead of this lane's first
+      const int lim = Nv - j * kBlock - (kh * 32 + 4 * G);  // valid keys of the tile ahead of this lane's first
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = (8 * (r >> 2) + (r & 3)) < lim ? s[r] : -INFINITY;
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) s[8 * mt + 4 * nt + r] = (16 * mt + r) < lim ? s[8 * mt + 4 * nt + r] : -INFINITY;
     }
 
     // ---- online softmax (log2 domain, lazily raised reference max) -------------------------
-    float mx;
-    {
-      float lo, hi;
-      both_halves(max16(s), lo, hi);
-      asm("v_max_f32 %0, %1, %2" : "=v"(mx) : "v"(lo), "v"(hi));  // no NaN-quieting moves: never NaN
-      mx *= scale_log2e;
-    }
-    if (__any(mx > m_raise)) {  // wave-uniform; always taken on the first live tile
-      const float m_new = fmaxf(m, mx);
-      const float alpha = fast_exp2(m - (m_new == -INFINITY ? 0.f : m_new));  // m = -inf -> 0
-      m = m_new;
-      neg_m = m == -INFINITY ? 0.f : -m - p_shift;
-      m_raise = m + kRescaleSlack;
-      l *= alpha;
+    // The raise test needs no cross-lane step: if no lane holds a value above its query's threshold,
+    // no query has one.  Only a raise itself (rare) takes the maximum over the four lanes of a query.
+    float mx[2];
 #pragma unroll
-      for (int ds = 0; ds < DSUB; ++ds)
+    for (int nt = 0; nt < 2; ++nt)
+      mx[nt] = max8(s[4 * nt], s[4 * nt + 1], s[4 * nt + 2], s[4 * nt + 3], s[8 + 4 * nt], s[8 + 4 * nt + 1],
+                    s[8 + 4 * nt + 2], s[8 + 4 * nt + 3]) * scale_log2e;
+    if (__any(mx[0] > m_raise[0] || mx[1] > m_raise[1])) {  // wave-uniform; always taken on the first live tile
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[ds][r] *= alpha;
+      for (int nt = 0; nt < 2; ++nt) {
+        const float m_new = fmaxf(m[nt], max_over_groups(mx[nt]));
+        const float alpha = fast_exp2(m[nt] - (m_new == -INFINITY ? 0.f : m_new));  // m = -inf -> 0
+        m[nt] = m_new;
+        neg_m[nt] = m_new == -INFINITY ? 0.f : -m_new - p_shift;
+        m_raise[nt] = m_new + kRescaleSlack;
+        l[nt] *= alpha;
+#pragma unroll
+        for (int k = 0; k < OT; ++k)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[nt][k][r] *= alpha;
+      }
     }
-    // P^T of this wave's 32 keys, rounded to bf16 and packed two per register: the same registers
-    // feed the row sum (v_dot2 with ones) and, as they stand, the B operand of the second product
+    // P^T of this wave's 32 keys, rounded to bf16 and packed two per register: per query the same four
+    // registers feed the row sum (v_dot2 with ones) and, as they stand, the B operand of the second product
     typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned uint4v;
-    bf16x2 pk[8];
+    bf16x8 pf[2];
 #pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      pk[r >> 1][0] = (__bf16)fast_exp2(fmaf(s[r], scale_log2e, neg_m));
-      pk[r >> 1][1] = (__bf16)fast_exp2(fmaf(s[r + 1], scale_log2e, neg_m));
-    }
-    {
+    for (int nt = 0; nt < 2; ++nt) {
+      bf16x2 pk[4];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; r += 2) {
+          pk[2 * mt + (r >> 1)][0] = (__bf16)fast_exp2(fmaf(s[8 * mt + 4 * nt + r], scale_log2e, neg_m[nt]));
+          pk[2 * mt + (r >> 1)][1] = (__bf16)fast_exp2(fmaf(s[8 * mt + 4 * nt + r + 1], scale_log2e, neg_m[nt]));
+        }
       // the row sum is taken over the ROUNDED probabilities, the ones P V actually uses, so that
       // the final division cancels the rounding of a dominant key instead of keeping it
       bf16x2 ones;
       ones[0] = (__bf16)1.0f;
       ones[1] = (__bf16)1.0f;
 #pragma unroll
-      for (int r = 0; r < 8; ++r) l = __builtin_amdgcn_fdot2_f32_bf16(pk[r], ones, l, false);
-    }
-    bf16x8 pf[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const uint4v w = {__builtin_bit_cast(unsigned, pk[4 * t]), __builtin_bit_cast(unsigned, pk[4 * t + 1]),
-                        __builtin_bit_cast(unsigned, pk[4 * t + 2]), __builtin_bit_cast(unsigned, pk[4 * t + 3])};
-      pf[t] = __builtin_bit_cast(bf16x8, w);
+      for (int r = 0; r < 4; ++r) l[nt] = __builtin_amdgcn_fdot2_f32_bf16(pk[r], ones, l[nt], false);
+      const uint4v w = {__builtin_bit_cast(unsigned, pk[0]), __builtin_bit_cast(unsigned, pk[1]),
+                        __builtin_bit_cast(unsigned, pk[2]), __builtin_bit_cast(unsigned, pk[3])};
+      pf[nt] = __builtin_bit_cast(bf16x8, w);
     }
 
-    // ---- O^T += V^T P^T ---------------------------------------------------------------------
+    // ---- O^T += V^T P^T: one MFMA per (d sub-tile, query tile), its 32 contraction slots = this wave's keys ----
     {
       const unsigned char* vb = smem + vslot * T::kBytes;
-      constexpr int VB = WGS <= 2 ? DSUB : 2;  // d sub-tiles per batch
+      if constexpr (kLean) asm volatile("" : "+v"(vfrag[0]));
+      constexpr int VB = WGS <= 2 ? DT : 2;  // d sub-tiles per batch
 #pragma unroll
-      for (int ds0 = 0; ds0 < DSUB; ds0 += VB) {
-        bf16x8 vf[VB][2];
+      for (int dt0 = 0; dt0 < DT; dt0 += VB) {
+        bf16x8 vf[VB];
 #pragma unroll
-        for (int dd = 0; dd < VB; ++dd)
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            const unsigned char* p = vb + vfrag[ds0 + dd] + t * 16 * T::kRowBytes;
-            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
-            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (short4v __attribute__((address_space(3)))*)(p + 8 * T::kRowBytes));
-            const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            __builtin_memcpy(&vf[dd][t], &both, sizeof(bf16x8));
-          }
+        for (int dd = 0; dd < VB; ++dd) {
+          const unsigned char* p = vb + (kLean ? vfrag[0] ^ ((dt0 + dd) << 5) : vfrag[dt0 + dd]);
+          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
+          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (short4v __attribute__((address_space(3)))*)(p + 16 * T::kRowBytes));
+          const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          __builtin_memcpy(&vf[dd], &both, sizeof(bf16x8));
+        }
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int dd = 0; dd < VB; ++dd)
 #pragma unroll
-          for (int t = 0; t < 2; ++t)
-            o[ds0 + dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dd][t], pf[t], o[ds0 + dd], 0, 0, 0);
+          for (int nt = 0; nt < 2; ++nt)
+            set_quarter(o[nt][(dt0 + dd) >> 2], (dt0 + dd) & 3,
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dd], pf[nt], quarter(o[nt][(dt0 + dd) >> 2], (dt0 + dd) & 3), 0, 0, 0));
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+
+    // pin each accumulator tuple to one 16-register unit once per tile (see quarter())
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int k = 0; k < OT; ++k) asm volatile("" : "+v"(o[nt][k]));
 
     // K(n+1) has landed; again at most SLOTS-2 younger items are in flight
     constexpr int kEndWait = RASTER ? (LEAD - 1) * (2 * kDma + 1) + kDma : (kSlots - 2) * kDma;
@@ -544,67 +628,78 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   // ---- merge the two key halves, stage the block row-major in LDS, store coalesced ----------
   // (the loop ended with a barrier, so the tile slots are free).  The staging rows of a query half
   // overlay the exchange area that the SAME wave has just read into registers.
-  float l_lo, l_hi;
-  both_halves(l, l_lo, l_hi);
-  const float l_row = l_lo + l_hi;
+  float l_row[2];  // this wave's row sums: over the four lanes of each query
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) l_row[nt] = sum_over_groups(l[nt]);
   float* xch = reinterpret_cast<float*>(smem) + qh * XROWS * 64;  // [XROWS][64 lanes] of this query half
   if (kh == 1) {
     float* dst = xch + lane;
 #pragma unroll
-    for (int ds = 0; ds < DSUB; ++ds)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dst[(ds * 16 + r) * 64] = o[ds][r];
-    dst[(DSUB * 16) * 64] = m;
-    dst[(DSUB * 16 + 1) * 64] = l_row;
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dst[((dt * 2 + nt) * 4 + r) * 64] = o[nt][dt >> 2][4 * (dt & 3) + r];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      dst[(DT * 8 + nt) * 64] = m[nt];
+      dst[(DT * 8 + 2 + nt) * 64] = l_row[nt];
+    }
   }
   __syncthreads();
   if (kh == 0) {
     const float* src = xch + lane;
-    const float m1 = src[(DSUB * 16) * 64], l1 = src[(DSUB * 16 + 1) * 64];
-    const float mm = fmaxf(m, m1);
-    const float m_ref = mm == -INFINITY ? 0.f : mm;
-    const float a0 = fast_exp2(m - m_ref), a1 = fast_exp2(m1 - m_ref);
-    const float lt = l_row * a0 + l1 * a1;
-    const int token = i * kBlock + qh * 32 + col;
-    const bool live = token < Nv && lt > 0.f;  // lt == 0: empty list, or every listed key is padding
-    const float inv = live ? 1.f / lt : 0.f;
-    const float w0 = live ? a0 * inv : 0.f, w1 = live ? a1 * inv : 0.f;
 #pragma unroll
-    for (int ds = 0; ds < DSUB; ++ds)
+    for (int nt = 0; nt < 2; ++nt) {
+      const float m1 = src[(DT * 8 + nt) * 64], l1 = src[(DT * 8 + 2 + nt) * 64];
+      const float mm = fmaxf(m[nt], m1);
+      const float m_ref = mm == -INFINITY ? 0.f : mm;
+      const float a0 = fast_exp2(m[nt] - m_ref), a1 = fast_exp2(m1 - m_ref);
+      const float lt = l_row[nt] * a0 + l1 * a1;
+      const int token = i * kBlock + qh * 32 + 16 * nt + c16;
+      const bool live = token < Nv && lt > 0.f;  // lt == 0: empty list, or every listed key is padding
+      const float inv = live ? 1.f / lt : 0.f;
+      const float w0 = live ? a0 * inv : 0.f, w1 = live ? a1 * inv : 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float val = o[ds][r] * w0 + src[(ds * 16 + r) * 64] * w1;
-        o[ds][r] = live ? val : 0.f;
-      }
-    if (lse && g == 0) {
-      const float val = live ? (mm + p_shift + __log2f(lt)) * kLn2 : -INFINITY;
-      if constexpr (RASTER) {  // [B, Hh, Nv] in raster order; padded rows have no place there
-        if (token < Nv) lse[head * (long long)Nv + ras.order[token]] = val;
-      } else {
-        lse[head * (long long)nb * kBlock + token] = val;
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float val = o[nt][dt >> 2][4 * (dt & 3) + r] * w0 + src[((dt * 2 + nt) * 4 + r) * 64] * w1;
+          o[nt][dt >> 2][4 * (dt & 3) + r] = live ? val : 0.f;
+        }
+      if (lse && G == 0) {
+        const float val = live ? (mm + p_shift + __log2f(lt)) * kLn2 : -INFINITY;
+        if constexpr (RASTER) {  // [B, Hh, Nv] in raster order; padded rows have no place there
+          if (token < Nv) lse[head * (long long)Nv + ras.order[token]] = val;
+        } else {
+          lse[head * (long long)nb * kBlock + token] = val;
+        }
       }
     }
     // every exchange value of this wave must be in registers before its area is overwritten
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    float* stage = xch + col * OSTRIDE;  // row (32 qh + col) of the block
 #pragma unroll
-    for (int ds = 0; ds < DSUB; ++ds)
+    for (int nt = 0; nt < 2; ++nt) {
+      float* stage = xch + (16 * nt + c16) * OSTRIDE;  // row 32 qh + 16 nt + c16 of the block
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq)  // register r = 4 rq + e is channel 32 ds + 8 rq + 4 g + e
-        *reinterpret_cast<float4*>(stage + 32 * ds + 8 * rq + 4 * g) =
-            make_float4(o[ds][rq * 4], o[ds][rq * 4 + 1], o[ds][rq * 4 + 2], o[ds][rq * 4 + 3]);
+      for (int dt = 0; dt < DT; ++dt) {  // quarter dt % 4 of o[nt][dt / 4] is channels 16 dt + 4 G .. + 3
+        const f32x16& t = o[nt][dt >> 2];
+        const int e = 4 * (dt & 3);
+        *reinterpret_cast<float4*>(stage + 16 * dt + 4 * G) = make_float4(t[e], t[e + 1], t[e + 2], t[e + 3]);
+      }
+    }
   }
   __syncthreads();
   {
     // 64 rows x D channels, 4 channels per thread per pass, consecutive threads -> consecutive addresses
-    const float* stage = reinterpret_cast<const float*>(smem);  // row r at r * OSTRIDE
+    const float* stage = reinterpret_cast<const float*>(smem);  // row r at (r / 32) * XROWS * 64 + (r % 32) * OSTRIDE
     constexpr int PIECES = kBlock * D / 4;
     const long long blk_off = head_off + (long long)i * kBlock * D;
 #pragma unroll
     for (int it = 0; it < PIECES / kThreads; ++it) {
       const int id = it * kThreads + tid;
       const int row = id / (D / 4), c4 = (id % (D / 4)) * 4;
-      float4 val = *reinterpret_cast<const float4*>(stage + row * OSTRIDE + c4);
+      float4 val = *reinterpret_cast<const float4*>(stage + (row >> 5) * (XROWS * 64) + (row & 31) * OSTRIDE + c4);
       if (fuse.coarse && i * kBlock + row < Nv) {
         // second branch folded into the store: out = gate_fine * attention + gate_coarse * cube-level row of this cube
         const float4 cz = *reinterpret_cast<const float4*>(fuse.coarse + (head * nb + i) * (long long)D + c4);
@@ -664,15 +759,17 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
                             const FuseArgs& fuse, hipStream_t st) {
-  // Two launch shapes (measured at the 480p shape, 51 of 512 blocks kept):
-  //   sparse lists: 5-slot ring, 2 workgroups per CU.  Independent lists miss the 4 MiB L2 about half
-  //     the time, and what then limits the tile feed is the number of bytes in flight per CU;
+  // Two launch shapes, both with a 3-slot ring (48 KiB at d = 128), chosen by measurement at the 480p shape:
+  //   sparse lists: 2 workgroups per CU with the whole register file between them, so that every fragment
+  //     of a tile is read in one batch (a 5-slot ring that requests tiles two iterations ahead was 1 % slower
+  //     at 51, 25 and ragged 8..64 blocks and at the 720p shape; 3 workgroups per CU with the small batches
+  //     their 168 registers allow was 19 % slower);
   //   dense-like lists (at least half of the blocks kept, so neighbouring query blocks share most
-  //     tiles and L2 serves them): 3-slot ring, 3 workgroups per CU, for the extra wave per SIMD.
+  //     tiles and L2 serves them): 3 workgroups per CU, for the extra wave per SIMD (2 % faster there).
   const bool dense_like = 2 * (long long)kmax >= s.nb;
 #define USV_ATTN_CASE(DD, F32)                                                                         \
   return dense_like ? run<DD, F32, 3, 3>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st)        \
-                    : run<DD, F32, 5, 2>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st)
+                    : run<DD, F32, 3, 2>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st)
   if (s.d == 128) {
     if (out_f32) USV_ATTN_CASE(128, true);
     USV_ATTN_CASE(128, false);
@@ -682,8 +779,7 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const D
 #undef USV_ATTN_CASE
 }
 
-// Raster-order tensors: 3-slot ring, 2 workgroups per CU (the order ring takes the LDS that a 5-slot ring
-// would need for a second workgroup; the two shapes measured the same on cube-major inputs).
+// Raster-order tensors: the sparse shape (3-slot ring, 2 workgroups per CU) plus the order ring.
 hipError_t launch_attn_bf16_raster(const void* q, const void* k, const void* v, const Dims& s, const RasterArgs& ras,
                                    const int32_t* idx, const int32_t* cnt, int kmax, float scale, void* out,
                                    bool out_f32, float* lse, const FuseArgs& fuse, hipStream_t st) {
