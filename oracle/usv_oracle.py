@@ -64,6 +64,10 @@ Readings taken where the paper is silent:
     follow in the same raster order, packed without gaps (so only the tail of
     the sequence is padding, which is what seq_valid expresses); inside a cube,
     tokens are in raster order of their local coordinates.
+  * cube-faithful variant of that order (cube_token_order_padded): every cube, cut or not, gets a 64-position
+    block of its own, in raster order of the cube coordinates; a cut cube's tokens come first in its block and
+    the rest of the block is padding.  The stages then take per-block valid counts (block_valid) in place of
+    the single seq_valid: means over a block's valid tokens, padded keys masked, padded query rows 0.
   * coarse branch (the cube level of the coarse-to-fine scheme, Section 2.2): attention
     among the pooled cubes, C_i = sum_j softmax_j(S_ij) mean(V_j) over the cubes that hold
     a valid token, with S the stage-1 scores (they already carry the 1/sqrt(d)).
@@ -103,33 +107,45 @@ def _f64(x):
 # --------------------------------------------------------------------------- #
 # stage 1: pooled block scores (coarse stage of the coarse-to-fine scheme)
 # --------------------------------------------------------------------------- #
-def block_means(X, seq_valid, block=BLOCK):
+def _valid_counts(nb, seq_valid, block, block_valid):
+    """Valid tokens of each block: block_valid[i] if given (the first block_valid[i] rows of block i), else the
+    blocks are filled front to back by the first seq_valid tokens."""
+    if block_valid is not None:
+        v = np.asarray(block_valid, dtype=np.int64)
+        assert v.shape == (nb,) and (v >= 0).all() and (v <= block).all()
+        return v
+    return np.clip(seq_valid - block * np.arange(nb), 0, block)
+
+
+def block_means(X, seq_valid, block=BLOCK, block_valid=None):
     """Mean over the valid tokens of each block.  X: [..., N, d] -> [..., nb, d] (fp64).
 
     Blocks without a valid token get NaN means (they have no mean)."""
     X = _f64(X)
     N, d = X.shape[-2], X.shape[-1]
     nb = N // block
+    nv = _valid_counts(nb, seq_valid, block, block_valid)
     out = np.full(X.shape[:-2] + (nb, d), np.nan)
     for i in range(nb):
-        lo, hi = i * block, min((i + 1) * block, seq_valid)
-        if hi > lo:
-            out[..., i, :] = X[..., lo:hi, :].sum(axis=-2) / (hi - lo)
+        if nv[i] > 0:
+            out[..., i, :] = X[..., i * block : i * block + nv[i], :].sum(axis=-2) / nv[i]
     return out
 
 
-def block_scores(Q, K, seq_valid, block=BLOCK):
+def block_scores(Q, K, seq_valid, block=BLOCK, block_valid=None):
     """S[b,h,i,j] = mean(Q_blk i) . mean(K_blk j) / sqrt(d), fp64 then rounded once to fp32.
 
-    Q, K: [B, Hh, N, d].  Rows/columns of blocks with no valid token are -inf."""
+    Q, K: [B, Hh, N, d].  Rows/columns of blocks with no valid token are -inf.
+    block_valid: per-block valid counts (one cube per block, cut cubes padded: cube_token_order_padded)."""
     d = Q.shape[-1]
-    qm = block_means(Q, seq_valid, block)
-    km = block_means(K, seq_valid, block)
+    qm = block_means(Q, seq_valid, block, block_valid)
+    km = block_means(K, seq_valid, block, block_valid)
     nb = qm.shape[-2]
-    nb_valid = (seq_valid + block - 1) // block
+    live = _valid_counts(nb, seq_valid, block, block_valid) > 0
     S = np.full(qm.shape[:-2] + (nb, nb), -np.inf)
-    S[..., :nb_valid, :nb_valid] = (
-        np.einsum("...id,...jd->...ij", qm[..., :nb_valid, :], km[..., :nb_valid, :]) / math.sqrt(d)
+    ii = np.nonzero(live)[0]
+    S[np.ix_(*[np.arange(n) for n in S.shape[:-2]], ii, ii)] = (
+        np.einsum("...id,...jd->...ij", qm[..., ii, :], km[..., ii, :]) / math.sqrt(d)
     )
     return S.astype(np.float32)
 
@@ -218,26 +234,26 @@ def block_mask(idx, cnt, seq_len, seq_valid, block=BLOCK):
     return M
 
 
-def block_sparse_attn_head(Q, K, V, idx, cnt, seq_valid, scale=None, qblocks=None, block=BLOCK):
+def block_sparse_attn_head(Q, K, V, idx, cnt, seq_valid, scale=None, qblocks=None, block=BLOCK, block_valid=None):
     """Block-masked attention for one head.  Q,K,V: [N, d]; idx [nb,kmax], cnt [nb].
 
     For each query block i the keys with log M = 0 are exactly the valid tokens of the listed
     blocks; the softmax is taken over those keys (the others contribute exp(-inf) = 0).
     Returns O [N, d] fp64 and lse [N] fp64; rows of query blocks not in `qblocks` (default: all)
-    are left at 0 / -inf, as are padded rows and rows of blocks with an empty list."""
+    are left at 0 / -inf, as are padded rows and rows of blocks with an empty list.
+    block_valid: per-block valid counts (see block_scores); default: the first seq_valid tokens are valid."""
     Q, K, V = _f64(Q), _f64(K), _f64(V)
     N, d = Q.shape
     scale = 1.0 / math.sqrt(d) if scale is None else scale
     O = np.zeros((N, d))
     lse = np.full((N,), -np.inf)
     nb = N // block
+    nv = _valid_counts(nb, seq_valid, block, block_valid)
     for i in range(nb) if qblocks is None else qblocks:
-        r0, r1 = i * block, min((i + 1) * block, seq_valid)
+        r0, r1 = i * block, i * block + nv[i]
         if r1 <= r0 or cnt[i] == 0:
             continue
-        cols = np.concatenate(
-            [np.arange(j * block, min((j + 1) * block, seq_valid)) for j in idx[i, : cnt[i]]]
-        )
+        cols = np.concatenate([np.arange(j * block, j * block + nv[j]) for j in idx[i, : cnt[i]]])
         if cols.size == 0:
             continue
         P, l = _softmax_rows((Q[r0:r1] @ K[cols].T) * scale)
@@ -246,7 +262,7 @@ def block_sparse_attn_head(Q, K, V, idx, cnt, seq_valid, scale=None, qblocks=Non
     return O, lse
 
 
-def block_sparse_attn(Q, K, V, idx, cnt, seq_valid, scale=None, block=BLOCK):
+def block_sparse_attn(Q, K, V, idx, cnt, seq_valid, scale=None, block=BLOCK, block_valid=None):
     """All heads.  Q,K,V: [B,Hh,N,d]; idx [B,Hh,nb,kmax]; cnt [B,Hh,nb] -> O [B,Hh,N,d], lse [B,Hh,N] (fp64)."""
     B, Hh, N, d = Q.shape
     O = np.zeros((B, Hh, N, d))
@@ -254,7 +270,7 @@ def block_sparse_attn(Q, K, V, idx, cnt, seq_valid, scale=None, block=BLOCK):
     for b in range(B):
         for h in range(Hh):
             O[b, h], lse[b, h] = block_sparse_attn_head(
-                Q[b, h], K[b, h], V[b, h], idx[b, h], cnt[b, h], seq_valid, scale, None, block
+                Q[b, h], K[b, h], V[b, h], idx[b, h], cnt[b, h], seq_valid, scale, None, block, block_valid
             )
     return O, lse
 
@@ -282,6 +298,46 @@ def cube_token_order(grid, cube):
     return np.asarray(order, dtype=np.int64)
 
 
+def cube_token_order_padded(grid, cube):
+    """One cube per block, EVERY cube (Figure 2, right: Q, K and V are split into local 3-D cubes): the cubes
+    in raster order of their cube coordinates, each given a block of ct*ch*cw positions; a cube the grid
+    boundary cuts fills the first positions of its block with its tokens (raster order of the local coordinates
+    inside the clipped cube) and leaves the rest as padding.
+    Returns order [n_cubes * ct*ch*cw] (raster index, or -1 at a padding position) and valid [n_cubes]."""
+    T, H, W = grid
+    ct, ch, cw = cube
+    size = ct * ch * cw
+    order, valid = [], []
+    for a in range(0, T, ct):
+        for b in range(0, H, ch):
+            for c in range(0, W, cw):
+                toks = [(t * H + h) * W + w for t in range(a, min(a + ct, T)) for h in range(b, min(b + ch, H))
+                        for w in range(c, min(c + cw, W))]
+                valid.append(len(toks))
+                order.extend(toks + [-1] * (size - len(toks)))
+    return np.asarray(order, dtype=np.int64), np.asarray(valid, dtype=np.int64)
+
+
+def order_gather(X, order):
+    """X [..., tokens, d] -> [..., len(order), d]: row p is X[order[p]], or zero where order[p] < 0."""
+    X = np.asarray(X)
+    order = np.asarray(order)
+    out = np.zeros(X.shape[:-2] + (len(order), X.shape[-1]), dtype=X.dtype)
+    keep = order >= 0
+    out[..., keep, :] = X[..., order[keep], :]
+    return out
+
+
+def order_scatter(Y, order, tokens):
+    """The inverse of order_gather: out[order[p]] = Y[p] for the positions that hold a token."""
+    Y = np.asarray(Y)
+    order = np.asarray(order)
+    keep = order >= 0
+    out = np.zeros(Y.shape[:-2] + (tokens, Y.shape[-1]), dtype=Y.dtype)
+    out[..., order[keep], :] = Y[..., keep, :]
+    return out
+
+
 def cube_gather(X, grid, cube, seq_len):
     """Raster-ordered X [..., T*H*W, d] -> cube-major [..., seq_len, d]; rows past T*H*W are zero."""
     X = np.asarray(X)
@@ -303,20 +359,20 @@ def cube_scatter(Y, grid, cube):
 # --------------------------------------------------------------------------- #
 # cube-level branch and output fusion (Figure 2, right; Section 2.2's coarse level)
 # --------------------------------------------------------------------------- #
-def coarse_attn(S, V, seq_valid, block=BLOCK):
+def coarse_attn(S, V, seq_valid, block=BLOCK, block_valid=None):
     """C[b,h,i,:] = sum_j softmax_j(S[b,h,i,:])_j * mean(V_j) over the cubes holding a valid token.
 
     S: fp32 scores [B,Hh,nb,nb] (already scaled); V: [B,Hh,N,d].  Returns fp64 [B,Hh,nb,d];
-    rows of cubes without a valid token are 0."""
+    rows of cubes without a valid token are 0.  block_valid: per-block valid counts (see block_scores)."""
     S = _f64(S)
     nb = S.shape[-1]
-    nbv = (seq_valid + block - 1) // block
-    Vm = block_means(V, seq_valid, block)[..., :nbv, :]
-    L = S[..., :nbv, :nbv]
+    live = np.nonzero(_valid_counts(nb, seq_valid, block, block_valid) > 0)[0]
+    Vm = block_means(V, seq_valid, block, block_valid)[..., live, :]
+    L = S[..., live, :][..., live]
     P = np.exp(L - L.max(axis=-1, keepdims=True))
     P = P / P.sum(axis=-1, keepdims=True)
     C = np.zeros(S.shape[:-1] + (Vm.shape[-1],))
-    C[..., :nbv, :] = P @ Vm
+    C[..., live, :] = P @ Vm
     assert C.shape[-2] == nb
     return C
 

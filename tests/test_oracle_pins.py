@@ -396,6 +396,97 @@ def test_cube_gather_scatter_roundtrip_and_padding():
 
 
 # --------------------------------------------------------------------------- #
+# one cube per block, cut cubes padded; per-block valid counts through the stages
+# --------------------------------------------------------------------------- #
+def test_padded_cube_order_hand_enumerated():
+    """A small grid written out by hand (order and valid counts)."""
+    with open(f"{GOLDEN}/cube_order_padded_3x2x5_cube_2x2x2.txt") as f:
+        rows = [ln for ln in f if ln.strip() and not ln.startswith("#")]
+    order, valid = orc.cube_token_order_padded((3, 2, 5), (2, 2, 2))
+    np.testing.assert_array_equal(order, np.array(rows[0].split(), dtype=np.int64))
+    np.testing.assert_array_equal(valid, np.array(rows[1].split(), dtype=np.int64))
+
+
+@pytest.mark.parametrize("grid", [(5, 6, 7), (21, 30, 52), (4, 8, 8), (1, 4, 17)])
+def test_padded_cube_order_structure(grid):
+    """Every token exactly once; block b holds exactly the tokens of cube b (cube id from the coordinates), its
+    valid ones first and in raster order of the local coordinates; the count is the clipped volume; on a grid the
+    cube divides it is the packed order.  Catches a cube walked with the full extents, swapped axes, a wrong count."""
+    T, H, W = grid
+    cube = (4, 4, 4) if T >= 4 else (1, 8, 8)
+    ct, ch, cw = cube
+    order, valid = orc.cube_token_order_padded(grid, cube)
+    nH, nW = -(-H // ch), -(-W // cw)
+    assert len(order) == 64 * len(valid) and len(valid) == -(-T // ct) * nH * nW
+    toks = order[order >= 0]
+    assert sorted(toks.tolist()) == list(range(T * H * W))
+    for b in range(len(valid)):
+        blk = order[64 * b:64 * b + 64]
+        n = valid[b]
+        assert (blk[:n] >= 0).all() and (blk[n:] == -1).all() and n >= 1
+        t, h, w = blk[:n] // (H * W), (blk[:n] // W) % H, blk[:n] % W
+        assert ((((t // ct) * nH + h // ch) * nW + w // cw) == b).all()
+        it, ih, iw = b // (nH * nW), (b // nW) % nH, b % nW
+        assert n == min(ct, T - it * ct) * min(ch, H - ih * ch) * min(cw, W - iw * cw)
+        assert (np.diff(blk[:n]) > 0).all()  # raster order of the local coordinates = ascending raster index
+    if T % ct == 0 and H % ch == 0 and W % cw == 0:
+        np.testing.assert_array_equal(order, orc.cube_token_order(grid, cube))
+        assert (valid == 64).all()
+
+
+def test_order_gather_scatter_with_padding():
+    grid, cube = (5, 6, 7), (4, 4, 4)
+    order, valid = orc.cube_token_order_padded(grid, cube)
+    X = randn(2, 2, 5 * 6 * 7, 4)
+    Y = orc.order_gather(X, order)
+    assert Y.shape[-2] == len(order) and np.all(Y[..., order < 0, :] == 0)
+    np.testing.assert_array_equal(Y[0, 1, 70], X[0, 1, order[70]])
+    np.testing.assert_array_equal(orc.order_scatter(Y, order, X.shape[-2]), X)
+
+
+def test_block_valid_counts_through_scores_and_attention():
+    """Per-block valid counts: (a) counts that describe a filled prefix give exactly the seq_valid results;
+    (b) in general the scores are the mean of the valid x valid part of the dense logit tile and the attention
+    equals the masked-attention equation with a token-level mask built from the counts, whatever the padded rows
+    hold.  Catches counts applied to queries but not keys (or the reverse), means divided by 64, leaked padding."""
+    rng = np.random.default_rng(77)
+    nb, d = 6, 16
+    N = nb * 64
+    Q, K, V = (rng.standard_normal((1, 2, N, d)) for _ in range(3))
+    # (a) prefix counts
+    Nv = 5 * 64 - 23
+    pref = np.clip(Nv - 64 * np.arange(nb), 0, 64)
+    np.testing.assert_array_equal(orc.block_scores(Q, K, Nv), orc.block_scores(Q, K, N, block_valid=pref))
+    idx, cnt = orc.select_topk(orc.block_scores(Q, K, Nv), 3, Nv)
+    O1, L1 = orc.block_sparse_attn(Q, K, V, idx, cnt, Nv)
+    O2, L2 = orc.block_sparse_attn(Q, K, V, idx, cnt, N, block_valid=pref)
+    np.testing.assert_array_equal(O1, O2)
+    np.testing.assert_array_equal(L1, L2)
+    # (b) ragged counts, garbage in the padded rows
+    valid = np.array([64, 7, 64, 1, 30, 16])
+    tok_ok = np.concatenate([np.arange(64) < v for v in valid])
+    for x in (Q, K, V):
+        x[:, :, ~tok_ok] = 1e4
+    S = orc.block_scores(Q, K, N, block_valid=valid)
+    dense = np.einsum("bhid,bhjd->bhij", Q, K) / math.sqrt(d)
+    for i in range(nb):
+        for j in range(nb):
+            tile = dense[0, 1, 64 * i:64 * i + valid[i], 64 * j:64 * j + valid[j]]
+            assert abs(S[0, 1, i, j] - tile.mean()) < 1e-4 * max(1, abs(tile.mean()))
+    idx, cnt = orc.select_topk(S, 3, N)
+    O, L = orc.block_sparse_attn(Q, K, V, idx, cnt, N, block_valid=valid)
+    for h in range(2):
+        M = np.zeros((N, N))
+        for i in range(nb):
+            for j in idx[0, h, i, :cnt[0, h, i]]:
+                M[64 * i:64 * i + 64, 64 * j:64 * j + valid[j]] = 1.0
+        ref, lse = orc.masked_dense_attn(Q[0, h], K[0, h], V[0, h], M)
+        np.testing.assert_allclose(O[0, h][tok_ok], ref[tok_ok], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(L[0, h][tok_ok], lse[tok_ok], rtol=1e-12, atol=1e-12)
+        assert not O[0, h][~tok_ok].any() and np.isneginf(L[0, h][~tok_ok]).all()
+
+
+# --------------------------------------------------------------------------- #
 # local-cube allocation, cube-level branch, fusion (Figure 2, right)
 # --------------------------------------------------------------------------- #
 def test_force_local_brute_force():
