@@ -316,9 +316,33 @@ typedef struct {
   const int32_t* order;    /* device, [seq_len] int32, from usv_cube_order (any permutation works) */
   usv_strides in_strides;  /* element strides of q, k, v; token == 0 means contiguous [B, Hh, Nv, d] */
   usv_strides out_strides; /* element strides of out; token == 0 means contiguous [B, Hh, Nv, d] */
+  const int32_t* block_valid; /* NULL, or device [seq_len / 64] int32 from usv_cube_order_padded: see there */
 } usv_raster;
 
 usv_status usv_cube_order(const usv_shape* shape, const usv_grid* grid, int32_t* order, void* stream);
+
+/*
+ * One cube per block, EVERY cube (Figure 2, right: Q, K and V are split into
+ * local 3-D cubes): where usv_cube_order packs the cubes that the grid boundary
+ * cuts, this table gives each of them a 64-position block of its own, in raster
+ * order of the cube coordinates, so that every block's pooled mean, score and
+ * selection is a quantity of ONE cube.  Block b holds the block_valid[b] tokens
+ * of cube b in its first positions (raster order of the local coordinates inside
+ * the clipped cube); the rest of the block is padding, and order[] holds 0 there
+ * (a readable row; block_valid says that it does not count).
+ *   blocks   = usv_cube_count(grid) = ceil(T/ct) * ceil(H/ch) * ceil(W/cw)
+ *   order    : device, [64 * blocks] int32 (written)
+ *   block_valid : device, [blocks] int32 (written), every entry in 1..64
+ * Use: the raster entry points with shape->seq_len = 64 * blocks,
+ * shape->seq_valid = T*H*W (the raster tensors' token count) and
+ * view->block_valid set; usv_select_topk on these scores takes seq_valid =
+ * seq_len (every block is a candidate).  With view->block_valid the kernels
+ * average over a block's first block_valid[i] rows, mask the other keys, and
+ * neither compute nor store the other query rows.
+ */
+int32_t usv_cube_count(const usv_grid* grid); /* 0 for an invalid grid */
+usv_status usv_cube_order_padded(const usv_grid* grid, int32_t* order, int32_t* block_valid,
+                                 void* stream);
 
 /* Arguments as usv_block_scores; q, k laid out by view->in_strides. */
 usv_status usv_block_scores_raster(const void* q, const void* k, const usv_shape* shape,

@@ -18,6 +18,7 @@ _BINDING_NAMES = (
     "coarse_attn",
     "fuse_outputs",
     "cube_order",
+    "cube_order_padded",
     "block_scores_raster",
     "block_sparse_attn_raster",
     "coarse_attn_raster",

@@ -35,6 +35,8 @@ EXPORTED_SYMBOLS = (
     "usv_merge_apply",
     "usv_unmerge_apply",
     "usv_cube_order",
+    "usv_cube_count",
+    "usv_cube_order_padded",
     "usv_block_scores_raster",
     "usv_block_sparse_attn_raster",
     "usv_coarse_attn_raster",
@@ -75,7 +77,8 @@ class UsvStrides(ctypes.Structure):
 
 
 class UsvRaster(ctypes.Structure):
-    _fields_ = [("order", ctypes.c_void_p), ("in_strides", UsvStrides), ("out_strides", UsvStrides)]
+    _fields_ = [("order", ctypes.c_void_p), ("in_strides", UsvStrides), ("out_strides", UsvStrides),
+                ("block_valid", ctypes.c_void_p)]
 
 
 def lib_path() -> str:
@@ -126,6 +129,8 @@ def lib() -> ctypes.CDLL:
     L.usv_unmerge_apply.restype, L.usv_unmerge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp]
     rp = ctypes.POINTER(UsvRaster)
     L.usv_cube_order.restype, L.usv_cube_order.argtypes = i32, [sp, gp, vp, vp]
+    L.usv_cube_count.restype, L.usv_cube_count.argtypes = i32, [gp]
+    L.usv_cube_order_padded.restype, L.usv_cube_order_padded.argtypes = i32, [gp, vp, vp, vp]
     L.usv_block_scores_raster.restype, L.usv_block_scores_raster.argtypes = i32, [vp, vp, sp, rp, vp, vp, sz, vp]
     L.usv_block_sparse_attn_raster.restype = i32
     L.usv_block_sparse_attn_raster.argtypes = [vp, vp, vp, sp, rp, vp, vp, i32, f32, i32, vp, vp, vp]
@@ -486,13 +491,37 @@ def cube_order(grid, cube=(4, 4, 4), seq_len=None, device="cuda:0", out=None):
     return out
 
 
+def cube_order_padded(grid, cube=(4, 4, 4), device="cuda:0"):
+    """usv_cube_order_padded: one cube per block, cut cubes padded -> (order int32 [64 * cubes], block_valid int32 [cubes])."""
+    g = _grid(grid, cube)
+    n = int(lib().usv_cube_count(ctypes.byref(g)))
+    if n == 0:
+        raise ValueError("invalid grid / cube, or too many cubes")
+    order = torch.empty((n * BLOCK,), dtype=torch.int32, device=device)
+    valid = torch.empty((n,), dtype=torch.int32, device=device)
+    _check(lib().usv_cube_order_padded(ctypes.byref(g), _dev(order, "order", torch.int32),
+                                       _dev(valid, "block_valid", torch.int32), _stream()))
+    return order, valid
+
+
+def _view(order, st, ost, block_valid):
+    bv = None
+    if block_valid is not None:
+        if block_valid.numel() * BLOCK != order.numel():
+            raise ValueError("block_valid must hold one count per 64 entries of order")
+        bv = _dev(block_valid, "block_valid", torch.int32)
+    return UsvRaster(_dev(order, "order", torch.int32), st, ost, bv)
+
+
 def _raster_shape(x, order):
     B, Hh, Nv, d = x.shape
     return UsvShape(B, Hh, order.numel(), Nv, d, BLOCK, USV_BF16 if x.dtype == torch.bfloat16 else USV_F32)
 
 
-def block_scores_raster(q, k, order, out=None, workspace=None):
-    """usv_block_scores_raster: q, k raster-ordered [B, Hh, Nv, d] (strided views allowed) -> scores [B, Hh, nb, nb]."""
+def block_scores_raster(q, k, order, out=None, workspace=None, block_valid=None):
+    """usv_block_scores_raster: q, k raster-ordered [B, Hh, Nv, d] (strided views allowed) -> scores [B, Hh, nb, nb].
+
+    block_valid (with the order table of cube_order_padded): one cube per block, cut cubes padded."""
     sh = _raster_shape(q, order)
     qp, st = _raster(q, "q")
     kp, st_k = _raster(k, "k")
@@ -504,13 +533,13 @@ def block_scores_raster(q, k, order, out=None, workspace=None):
     need = int(lib().usv_workspace_bytes(ctypes.byref(sh)))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
-    view = UsvRaster(_dev(order, "order", torch.int32), st, UsvStrides(0, 0, 0))
+    view = _view(order, st, UsvStrides(0, 0, 0), block_valid)
     _check(lib().usv_block_scores_raster(qp, kp, ctypes.byref(sh), ctypes.byref(view), _dev(out, "scores", torch.float32),
                                          _dev(workspace, "workspace"), workspace.numel(), _stream()))
     return out
 
 
-def coarse_attn_raster(scores, v, order, out=None, workspace=None):
+def coarse_attn_raster(scores, v, order, out=None, workspace=None, block_valid=None):
     """usv_coarse_attn_raster: usv_coarse_attn with v in raster order [B, Hh, Nv, d] (strided views allowed)."""
     sh = _raster_shape(v, order)
     vp_, st = _raster(v, "v")
@@ -522,7 +551,7 @@ def coarse_attn_raster(scores, v, order, out=None, workspace=None):
     need = int(lib().usv_coarse_workspace_bytes(ctypes.byref(sh)))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=v.device)
-    view = UsvRaster(_dev(order, "order", torch.int32), st, UsvStrides(0, 0, 0))
+    view = _view(order, st, UsvStrides(0, 0, 0), block_valid)
     _check(lib().usv_coarse_attn_raster(_dev(scores, "scores", torch.float32), vp_, ctypes.byref(sh), ctypes.byref(view),
                                         _dev(out, "coarse", torch.float32), _dev(workspace, "workspace"),
                                         workspace.numel() * workspace.element_size(), _stream()))
@@ -530,7 +559,7 @@ def coarse_attn_raster(scores, v, order, out=None, workspace=None):
 
 
 def block_sparse_attn_raster(q, k, v, order, idx, cnt, scale=0.0, out=None, out_dtype=None, return_lse=False,
-                             coarse=None, gate_fine=None, gate_coarse=None):
+                             coarse=None, gate_fine=None, gate_coarse=None, block_valid=None):
     """usv_block_sparse_attn_raster(_fused): raster-ordered q, k, v [B, Hh, Nv, d] -> out [B, Hh, Nv, d] in raster order.
 
     coarse (+ optional raster-order gates laid out like q): out = gate_fine * attention + gate_coarse * coarse[cube]."""
@@ -548,7 +577,7 @@ def block_sparse_attn_raster(q, k, v, order, idx, cnt, scale=0.0, out=None, out_
         out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
     op, ost = _raster(out, "out")
     lse = torch.empty((sh.batch, sh.heads, sh.seq_valid), dtype=torch.float32, device=q.device) if return_lse else None
-    view = UsvRaster(_dev(order, "order", torch.int32), st, ost)
+    view = _view(order, st, ost, block_valid)
     gates = []
     for name, g_ in (("gate_fine", gate_fine), ("gate_coarse", gate_coarse)):
         if g_ is None:

@@ -429,8 +429,31 @@ usv_status check_raster(const usv_raster* view, const usv::Dims& s, long long ou
   // the tile requests carry the row offset in 32 bits
   if ((long long)s.Nv * in_b[2] > 0x7fffffffLL - 65536)
     return fail(USV_ERR_UNSUPPORTED, "seq_valid * token stride must stay below 2 GiB");
-  *ras = usv::RasterArgs{view->order, in_b[2], in_b[1], in_b[0], out_b[2], out_b[1], out_b[0], s.Hh};
+  if (view->block_valid) USV_TRY(check_ptr(view->block_valid, "block_valid"));
+  *ras = usv::RasterArgs{view->order, in_b[2], in_b[1], in_b[0], out_b[2], out_b[1], out_b[0], s.Hh, view->block_valid};
   return USV_OK;
+}
+
+// One cube per block: every block holds a token, whatever seq_valid (the raster token count) would leave of it.
+void all_blocks_live(const usv_raster* view, usv::Dims* s) {
+  if (view->block_valid) s->nb_valid = s->nb;
+}
+
+int32_t usv_cube_count(const usv_grid* grid) {
+  usv::CubeGrid g;
+  if (check_grid(grid, nullptr, &g) != USV_OK) return 0;
+  const long long n = (long long)((g.T + g.ct - 1) / g.ct) * ((g.H + g.ch - 1) / g.ch) * ((g.W + g.cw - 1) / g.cw);
+  return n > USV_MAX_BLOCKS ? 0 : (int32_t)n;
+}
+
+usv_status usv_cube_order_padded(const usv_grid* grid, int32_t* order, int32_t* block_valid, void* stream) {
+  usv::CubeGrid g;
+  USV_TRY(check_grid(grid, nullptr, &g));
+  USV_TRY(check_ptr(order, "order"));
+  USV_TRY(check_ptr(block_valid, "block_valid"));
+  if (usv_cube_count(grid) == 0) return fail(USV_ERR_UNSUPPORTED, "more than %d cubes", USV_MAX_BLOCKS);
+  return hip_result(usv::launch_cube_order_padded(order, block_valid, g, static_cast<hipStream_t>(stream)),
+                    "usv_cube_order_padded launch");
 }
 
 usv_status usv_cube_order(const usv_shape* shape, const usv_grid* grid, int32_t* order, void* stream) {
@@ -448,6 +471,7 @@ usv_status usv_block_scores_raster(const void* q, const void* k, const usv_shape
   usv::RasterArgs ras;
   USV_TRY(check_shape(shape, true, &s));
   USV_TRY(check_raster(view, s, s.bf16 ? 2 : 4, &ras));
+  all_blocks_live(view, &s);
   USV_TRY(check_ptr(q, "q"));
   USV_TRY(check_ptr(k, "k"));
   USV_TRY(check_ptr(scores, "scores"));
@@ -471,6 +495,7 @@ usv_status usv_coarse_attn_raster(const float* scores, const void* v, const usv_
   usv::RasterArgs ras;
   USV_TRY(check_shape(shape, true, &s));
   USV_TRY(check_raster(view, s, s.bf16 ? 2 : 4, &ras));
+  all_blocks_live(view, &s);
   USV_TRY(check_ptr(scores, "scores"));
   USV_TRY(check_ptr(v, "v"));
   USV_TRY(check_ptr(coarse, "coarse"));

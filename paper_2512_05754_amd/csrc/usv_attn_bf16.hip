@@ -241,6 +241,10 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   const int c16 = lane & 15, G = lane >> 4;  // MFMA lane coordinates: column / row within a 16-row group, group
   const int n_list = min(max(cnt[work], 0), kmax);  // device contents are not trusted with addresses:
   const int32_t* list = idx + (long long)work * kmax;
+  // valid query rows of this block: the first nq of its 64 positions hold tokens
+  int nq = min(kBlock, max(0, Nv - i * kBlock));
+  if constexpr (RASTER)
+    if (ras.block_valid) nq = min(kBlock, max(0, ras.block_valid[i]));
   const uint16_t* kbase = k + head_off;
   const uint16_t* vbase = v + head_off;
   // raster mode: byte bases of this (batch, head); the K/V ones are lowered by kBias (see kc/vc below)
@@ -324,6 +328,16 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   const int list_raw = lane < kmax ? list[lane] : 0;
   int list_v = lane < n_list ? min(max(list_raw, 0), nb - 1) : 0;  // ... ids are clamped into [0, nb)
   auto list_at = [&](int n) { return __builtin_amdgcn_readlane(list_v, n & 63); };
+  // raster mode: the valid keys of every listed block travel beside its id (lane t: block of entry t), either
+  // looked up in the per-block counts (one cube per block, cut cubes padded) or, without them, what the first
+  // Nv positions leave of the block
+  int valid_v = kBlock;
+  auto load_valid = [&]() {
+    if constexpr (RASTER)
+      valid_v = ras.block_valid ? min(kBlock, max(0, ras.block_valid[list_v])) : min(kBlock, max(0, Nv - list_v * kBlock));
+  };
+  load_valid();
+  auto valid_at = [&](int n) { return __builtin_amdgcn_readlane(valid_v, n & 63); };
 
   // ring item 2n = K(list[n]) -> slot (2n) % SLOTS, item 2n+1 = V(list[n]) -> slot (2n+1) % SLOTS;
   // the first LEAD tiles are requested here
@@ -343,8 +357,12 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
       issue_v(j, (2 * t + 1) % kSlots);
     }
   int jq[QD + 1];  // block ids of tiles n .. n+QD (entries beyond the list read as block 0, unused)
+  int nkq[QD + 1]; // raster mode: their valid key counts
 #pragma unroll
-  for (int t = 0; t <= QD; ++t) jq[t] = list_at(t);
+  for (int t = 0; t <= QD; ++t) {
+    jq[t] = list_at(t);
+    nkq[t] = kBlock;
+  }
 
   // Q fragments: for query tile nt the lane holds query row 32*qh + 16*nt + c16, channels 32 t + 8 G .. + 8
   // for every k-step t
@@ -361,7 +379,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     if constexpr (RASTER) {
       // padding positions have no token: their query rows are zero, as in a gathered copy (their lanes
       // take part in the wave-wide rescale decisions, so what they hold is not quite without effect)
-      if (qrow >= Nv) {
+      if (qh * 32 + 16 * nt + c16 >= nq) {
 #pragma unroll
         for (int t = 0; t < KS; ++t)
 #pragma unroll
@@ -409,6 +427,10 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   }
 
   __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles and Q have landed
+  if constexpr (RASTER) {  // (read here, behind the wait that everything shares: an earlier read would hold the Q loads back)
+#pragma unroll
+    for (int t = 0; t <= QD; ++t) nkq[t] = valid_at(t);
+  }
   // pin the Q fragments here: otherwise the compiler sinks their loads into the loop and then waits
   // for "all outstanding loads" there, which would also wait for the tile prefetch it cannot see
 #pragma unroll
@@ -422,6 +444,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
   // blocks from this one on hold padded keys: the partial block (if Nv is not a multiple of 64) and, when the
   // tensors are padded by whole blocks, every block behind it.  A caller's list may name those too: all of
   // their keys are masked, as the masked-attention equation has it (they then add nothing to the row).
+  // (raster mode carries the valid key count of every listed block in nkq instead)
   const int first_padded_j = Nv / kBlock;
   auto tile_step = [&](auto phase_c, auto steady_c, int n) {
     constexpr int phase = decltype(phase_c)::value;
@@ -482,18 +505,29 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
     __syncthreads();  // ... for every wave; and nobody reads K(n) any more
     if (steady) issue_v(j_pre, kslot);  // item 2n+SLOTS = V(n+LEAD) takes K(n)'s slot
     // block ids for the next iteration: shift the queue and append tile n+1+LEAD
+    const int nk = nkq[0];
 #pragma unroll
-    for (int t = 0; t < QD; ++t) jq[t] = jq[t + 1];
+    for (int t = 0; t < QD; ++t) {
+      jq[t] = jq[t + 1];
+      nkq[t] = nkq[t + 1];
+    }
     if (((n + 1 + QD) & 63) == 0) {  // next 64 entries; awaited right here (once per 64 tiles) so that
       list_v = n + 1 + QD + lane < n_list ? min(max(list[n + 1 + QD + lane], 0), nb - 1) : 0;  // the hot path carries no
       __builtin_amdgcn_s_waitcnt(0x0f70);                                  // vector-memory wait
       asm volatile("" ::"v"(list_v));
+      if constexpr (RASTER) {
+        load_valid();
+        __builtin_amdgcn_s_waitcnt(0x0f70);
+        asm volatile("" ::"v"(valid_v));
+      }
     }
     jq[QD] = list_at(n + 1 + QD);
+    if constexpr (RASTER) nkq[QD] = valid_at(n + 1 + QD);
 
     // s[8 mt + 4 nt + r] of lane (c16, G) is key 32 kh + 16 mt + 4 G + r of the tile, query 32 qh + 16 nt + c16
-    if (j >= first_padded_j) {
-      const int lim = Nv - j * kBlock - (kh * 32 + 4 * G);  // valid keys of the tile ahead of this lane's first
+    if (RASTER ? nk < kBlock : j >= first_padded_j) {
+      // valid keys of the tile ahead of this lane's first
+      const int lim = (RASTER ? nk : Nv - j * kBlock) - (kh * 32 + 4 * G);
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -656,8 +690,8 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
       const float m_ref = mm == -INFINITY ? 0.f : mm;
       const float a0 = fast_exp2(m[nt] - m_ref), a1 = fast_exp2(m1 - m_ref);
       const float lt = l_row[nt] * a0 + l1 * a1;
-      const int token = i * kBlock + qh * 32 + 16 * nt + c16;
-      const bool live = token < Nv && lt > 0.f;  // lt == 0: empty list, or every listed key is padding
+      const int row = qh * 32 + 16 * nt + c16, token = i * kBlock + row;
+      const bool live = row < nq && lt > 0.f;  // lt == 0: empty list, or every listed key is padding
       const float inv = live ? 1.f / lt : 0.f;
       const float w0 = live ? a0 * inv : 0.f, w1 = live ? a1 * inv : 0.f;
 #pragma unroll
@@ -670,7 +704,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
       if (lse && G == 0) {
         const float val = live ? (mm + p_shift + __log2f(lt)) * kLn2 : -INFINITY;
         if constexpr (RASTER) {  // [B, Hh, Nv] in raster order; padded rows have no place there
-          if (token < Nv) lse[head * (long long)Nv + ras.order[token]] = val;
+          if (row < nq) lse[head * (long long)Nv + ras.order[token]] = val;
         } else {
           lse[head * (long long)nb * kBlock + token] = val;
         }
@@ -700,7 +734,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
       const int id = it * kThreads + tid;
       const int row = id / (D / 4), c4 = (id % (D / 4)) * 4;
       float4 val = *reinterpret_cast<const float4*>(stage + (row >> 5) * (XROWS * 64) + (row & 31) * OSTRIDE + c4);
-      if (fuse.coarse && i * kBlock + row < Nv) {
+      if (fuse.coarse && row < nq) {
         // second branch folded into the store: out = gate_fine * attention + gate_coarse * cube-level row of this cube
         const float4 cz = *reinterpret_cast<const float4*>(fuse.coarse + (head * nb + i) * (long long)D + c4);
         float4 gf = make_float4(1.f, 1.f, 1.f, 1.f), gc = gf;
@@ -716,7 +750,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
       }
       void* dst;
       if constexpr (RASTER) {
-        if (i * kBlock + row >= Nv) continue;  // the raster tensor has no padded rows
+        if (row >= nq) continue;  // the raster tensor has no padded rows
         dst = static_cast<unsigned char*>(out) + ras_out + (long long)ras.order[i * kBlock + row] * ras.o_tok +
               c4 * (OUT_F32 ? 4 : 2);
       } else {

@@ -61,12 +61,15 @@ struct FuseArgs {
   const uint16_t* gate_coarse;
 };
 // Raster-order tensors for the attention and pooling kernels: order[p] = raster index of cube-major position p
-// (entries p >= Nv hold any valid index); strides in BYTES; the output has its own strides.
+// (padding positions hold any valid index); strides in BYTES; the output has its own strides.
+// block_valid == nullptr: the first Nv positions hold tokens.  Otherwise block i holds block_valid[i] tokens in
+// its first positions (one cube per block, cut cubes padded) and the rest of the block is padding.
 struct RasterArgs {
   const int32_t* order;
   long long tok, head, batch;
   long long o_tok, o_head, o_batch;
   int Hh;
+  const int32_t* block_valid;
 };
 // ras == nullptr: cube-major Q, K
 hipError_t launch_block_scores(const void* q, const void* k, const Dims& s, float* scores, float* ws,
@@ -80,6 +83,7 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const D
 
 // gather: raster -> cube-major (+ zeroed padding); else cube-major -> raster.  Strides of the raster tensor in BYTES.
 hipError_t launch_cube_order(int32_t* order, const CubeGrid& g, int N, int Nv, hipStream_t stream);
+hipError_t launch_cube_order_padded(int32_t* order, int32_t* block_valid, const CubeGrid& g, hipStream_t stream);
 hipError_t launch_cube_move(bool gather, const void* src, void* dst, const CubeGrid& g, const Dims& s, long long sb,
                             long long sh, long long st, hipStream_t stream);
 

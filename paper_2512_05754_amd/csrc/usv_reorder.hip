@@ -106,6 +106,27 @@ __global__ __launch_bounds__(256) void cube_order(int32_t* __restrict__ order, C
   }
 }
 
+// One cube per block, every cube (cut cubes padded): position p = 64 b + r belongs to cube b (raster order of the
+// cube coordinates); its first n_b = clipped volume positions hold the cube's tokens in raster order of the local
+// coordinates, the rest is padding (order = 0, a valid index; block_valid tells the kernels which rows count).
+__global__ __launch_bounds__(256) void cube_order_padded(int32_t* __restrict__ order, int32_t* __restrict__ block_valid,
+                                                         CubeGrid g, int n_cubes) {
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  const int b = p / kBlock, r = p - b * kBlock;
+  if (b >= n_cubes) return;
+  const int nH = (g.H + g.ch - 1) / g.ch, nW = (g.W + g.cw - 1) / g.cw;
+  const int it = b / (nH * nW), rem = b - it * nH * nW, ih = rem / nW, iw = rem - ih * nW;
+  const int et = imin(g.ct, g.T - it * g.ct), eh = imin(g.ch, g.H - ih * g.ch), ew = imin(g.cw, g.W - iw * g.cw);
+  const int n = et * eh * ew;
+  if (r == 0) block_valid[b] = n;
+  int v = 0;
+  if (r < n) {
+    const int lt = r / (eh * ew), r2 = r - lt * eh * ew, lh = r2 / ew, lw = r2 - lh * ew;
+    v = ((it * g.ct + lt) * g.H + ih * g.ch + lh) * g.W + iw * g.cw + lw;
+  }
+  order[p] = v;
+}
+
 template <bool GATHER, int CHUNKS>
 hipError_t run(const void* src, void* dst, const CubeGrid& g, const Dims& s, long long sb, long long sh, long long st,
                hipStream_t stream) {
@@ -133,6 +154,12 @@ hipError_t launch_cube_move(bool gather, const void* src, void* dst, const CubeG
 
 hipError_t launch_cube_order(int32_t* order, const CubeGrid& g, int N, int Nv, hipStream_t stream) {
   cube_order<<<(unsigned)((N + 255) / 256), 256, 0, stream>>>(order, g, N, Nv);
+  return hipGetLastError();
+}
+
+hipError_t launch_cube_order_padded(int32_t* order, int32_t* block_valid, const CubeGrid& g, hipStream_t stream) {
+  const int n_cubes = ((g.T + g.ct - 1) / g.ct) * ((g.H + g.ch - 1) / g.ch) * ((g.W + g.cw - 1) / g.cw);
+  cube_order_padded<<<(unsigned)((n_cubes * kBlock + 255) / 256), 256, 0, stream>>>(order, block_valid, g, n_cubes);
   return hipGetLastError();
 }
 

@@ -59,7 +59,9 @@ __global__ __launch_bounds__(kPoolThreads) void pool_means(const T* __restrict__
     rbase = reinterpret_cast<const unsigned char*>(blockIdx.y == 0 ? q : k) + b * ras.batch + h * ras.head;
   }
   float* dst = ws + (long long)blockIdx.y * mean_elems_per_tensor + blk * D;
-  const int nvalid = min(kBlock, max(0, Nv - i * kBlock));
+  int nvalid = min(kBlock, max(0, Nv - i * kBlock));
+  if constexpr (RASTER)
+    if (ras.block_valid) nvalid = min(kBlock, max(0, ras.block_valid[i]));
 
   const int tid = threadIdx.x;
   const int r0 = tid / LPR, c0 = (tid % LPR) * VEC;

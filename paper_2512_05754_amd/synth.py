@@ -142,3 +142,28 @@ def gen_budgets(w: Workload) -> np.ndarray:
 def as_f32(x: np.ndarray) -> np.ndarray:
     """Storage format -> fp32 values (exact)."""
     return bf16_bits_to_f32(x) if x.dtype == np.uint16 else np.asarray(x, dtype=np.float32)
+
+
+def gen_raster_qkv(w: Workload, grid, cube):
+    """Q, K, V [B, Hh, T*H*W, d] in RASTER token order, storage format, with the shared vector u drawn per TRUE
+    cube of the grid (cubes cut by the boundary included): X = noise + cube_gain * u[cube of the token].
+    w.seq_valid must be T*H*W; the draws are rng([seed, b, h]): noise_Q, noise_K, noise_V, u_Q, u_K, u_V."""
+    T, H, Wd = grid
+    ct, ch, cw = cube
+    n = T * H * Wd
+    assert w.seq_valid == n
+    nH, nW = -(-H // ch), -(-Wd // cw)
+    t, h, x = np.meshgrid(np.arange(T), np.arange(H), np.arange(Wd), indexing="ij")
+    cube_of = (((t // ct) * nH + h // ch) * nW + x // cw).reshape(-1)
+    n_cubes = -(-T // ct) * nH * nW
+    st = np.uint16 if w.dtype == "bf16" else np.float32
+    out = [np.empty((w.batch, w.heads, n, w.head_dim), dtype=st) for _ in range(3)]
+    for b in range(w.batch):
+        for hd in range(w.heads):
+            rng = np.random.default_rng([w.seed, b, hd])
+            noise = [rng.standard_normal((n, w.head_dim), dtype=np.float32) for _ in range(3)]
+            us = [rng.standard_normal((n_cubes, w.head_dim), dtype=np.float32) for _ in range(3)]
+            for o, nz, u in zip(out, noise, us):
+                val = nz + np.float32(w.cube_gain) * u[cube_of]
+                o[b, hd] = f32_to_bf16_bits(val) if w.dtype == "bf16" else val
+    return out
