@@ -41,7 +41,10 @@ def parse():
                     help="also run one plain 256 MiB device copy (untimed) so that a rocprofv3 --pmc run of this "
                          "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
-    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch", "merge", "raster", "raster_two_branch"],
+    ap.add_argument("--no-work-order", action="store_true",
+                    help="ragged budgets: plain usv_block_sparse_attn (query blocks in index order) instead of "
+                         "usv_attn_work_order + usv_block_sparse_attn_ordered")
+    ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch", "merge", "raster", "raster_two_branch", "raster_cubes"],
                     help="attention: the three-stage hot path (the headline metric); reorder: the raster <-> "
                          "cube-major token reorder either side of it (gather Q, K, V + scatter O); two_branch: the "
                          "hot path with the local cube forced into every list, plus the cube-level branch and the "
@@ -372,23 +375,39 @@ def main():
     q, k, v = up(Q), up(K), up(V)
     budgets = None if w.keep else torch.from_numpy(synth.gen_budgets(w)).to(dev)
     two_branch = args.path in ("two_branch", "raster_two_branch")
-    raster = args.path in ("raster", "raster_two_branch")
+    raster = args.path in ("raster", "raster_two_branch", "raster_cubes")
+    cubes = args.path == "raster_cubes"  # one cube per block, cut cubes padded (usv_cube_order_padded + block_valid)
+    bv = None
     if raster:
         if w.name not in GRIDS:
             print(f"bench.py: --path raster needs a workload with a latent grid ({sorted(GRIDS)})", file=sys.stderr)
             sys.exit(2)
         # the same tokens in raster order of the latent grid (the layout a DiT block's projections leave behind)
         r_grid, r_cube = GRIDS[w.name], (4, 4, 4)
-        q, k, v = (usv.cube_scatter(x, r_grid, r_cube) for x in (q, k, v))
-        order = usv.cube_order(r_grid, r_cube, seq_len=w.seq_len)
+        if cubes:
+            # raster tensors whose shared per-cube vector follows the TRUE cubes of the grid, cut ones included
+            q, k, v = (up(x) for x in synth.gen_raster_qkv(w, r_grid, r_cube))
+            order, bv = usv.cube_order_padded(r_grid, r_cube)
+        else:
+            q, k, v = (usv.cube_scatter(x, r_grid, r_cube) for x in (q, k, v))
+            order = usv.cube_order(r_grid, r_cube, seq_len=w.seq_len)
     out_dtype = torch.float32 if (args.out_dtype == "f32" or w.dtype == "f32") else torch.bfloat16
 
     # every buffer is allocated once, outside the timed region
     B, Hh, N, d, nb, kmax = w.batch, w.heads, w.seq_len, w.head_dim, w.nb, w.kmax
+    keep_k, topk_valid = w.keep, w.seq_valid
+    if cubes:
+        nb = order.numel() // 64
+        N = nb * 64
+        keep_k = kmax = synth.keep_count(w.keep / w.nb, nb)  # the same keep ratio over more blocks
+        topk_valid = N  # every block holds a token
     S = torch.empty((B, Hh, nb, nb), dtype=torch.float32, device=dev)
-    ws = torch.empty(usv.workspace_bytes(B, Hh, N, w.seq_valid, d, w.dtype), dtype=torch.uint8, device=dev)
+    ws = torch.empty(usv.workspace_bytes(B, Hh, N, min(w.seq_valid, N), d, w.dtype), dtype=torch.uint8, device=dev)
     idx = torch.empty((B, Hh, nb, kmax), dtype=torch.int32, device=dev)
     cnt = torch.empty((B, Hh, nb), dtype=torch.int32, device=dev)
+    # ragged budgets: the attention launch walks each head's query blocks longest list first (usv_attn_work_order)
+    ordered = budgets is not None and not raster and not two_branch and w.dtype == "bf16" and not args.no_work_order
+    work_order = torch.empty((B, Hh, nb), dtype=torch.int32, device=dev) if ordered else None
     out = torch.empty((B, Hh, w.seq_valid if raster else N, d), dtype=out_dtype, device=dev)
     if two_branch:
         gen = torch.Generator(device=dev).manual_seed(w.seed)
@@ -405,13 +424,15 @@ def main():
         if events is not None:
             events[0].record()
         if raster:
-            usv.block_scores_raster(q, k, order, out=S, workspace=ws)
+            usv.block_scores_raster(q, k, order, out=S, workspace=ws, block_valid=bv)
         else:
             usv.block_scores(q, k, seq_valid=w.seq_valid, out=S, workspace=ws)
         if events is not None:
             events[1].record()
-        usv.select_topk(S, k=w.keep, seq_valid=w.seq_valid, budgets=budgets, kmax=kmax, idx=idx, cnt=cnt,
+        usv.select_topk(S, k=keep_k, seq_valid=topk_valid, budgets=budgets, kmax=kmax, idx=idx, cnt=cnt,
                         force_local=two_branch)
+        if ordered:  # timed with the selection
+            usv.attn_work_order(cnt, kmax, out=work_order)
         if events is not None:
             events[2].record()
         if two_branch:  # the cube-level branch first: the attention kernel folds it and the gates into its store
@@ -431,9 +452,9 @@ def main():
             if be is not None:
                 be[1].record()
         elif raster:
-            usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out=out)
+            usv.block_sparse_attn_raster(q, k, v, order, idx, cnt, out=out, block_valid=bv)
         else:
-            usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=out)
+            usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out=out, work_order=work_order)
         if events is not None:
             events[3].record()
         if two_branch:
@@ -506,7 +527,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": w.name, "batch": B, "heads": Hh, "head_dim": d, "seq_len": N, "seq_valid": w.seq_valid,
-            "block": 64, "blocks": nb, "keep": w.keep if w.keep else f"U[{w.budget_lo},{w.budget_hi}]",
+            "block": 64, "blocks": nb, "keep": keep_k if w.keep else f"U[{w.budget_lo},{w.budget_hi}]",
             "computed_tiles": tiles, "flop_per_step": flop, "out_dtype": args.out_dtype if w.dtype == "bf16" else "f32",
             "step": "usv_block_scores + usv_select_topk + usv_block_sparse_attn"
                     + (" + usv_coarse_attn + usv_attn_entropy; the attention is usv_block_sparse_attn_fused (local cube forced, "
@@ -529,6 +550,9 @@ def main():
             "avg_launch_ms": float(avg[2]),
         },
     }
+    if ordered:
+        result["config"]["step"] = ("usv_block_scores + usv_select_topk + usv_attn_work_order (timed with the selection) + "
+                                    "usv_block_sparse_attn_ordered")
     if args.graph and not two_branch:
         result["config"]["launch"] = "hip graph replay (one graph = one step)"
     if raster:
@@ -538,7 +562,13 @@ def main():
                                     "usv_block_scores_raster + usv_select_topk_ex + usv_coarse_attn_raster + "
                                     "usv_block_sparse_attn_raster_fused + usv_attn_entropy")
         result["roofline"]["kernel"] = "usv_block_sparse_attn_raster (attn_bf16, raster addressing)"
-        result["roofline"].update(measured_traffic("raster:" + w.name))
+        result["roofline"].update(measured_traffic(("cubes:" if cubes else "raster:") + w.name))
+    if cubes:
+        result["config"]["path"] = "raster_cubes"
+        result["config"]["seq_len"] = N
+        result["config"]["layout"] = ("one cube per block (usv_cube_order_padded): %d blocks, %d of them cut cubes padded to 64 rows; "
+                                      "computed tiles count padded rows in full" % (nb, int((bv < 64).sum().item())))
+        result["config"]["step"] = "usv_block_scores_raster + usv_select_topk + usv_block_sparse_attn_raster, view->block_valid set"
     if two_branch:
         c_ms = float(np.mean([evs[i][2].elapsed_time(branch_events[i][0]) for i in range(args.steps)]))
         a_ms = float(np.mean([branch_events[i][0].elapsed_time(branch_events[i][1]) for i in range(args.steps)]))

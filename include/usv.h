@@ -172,6 +172,37 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v,
                                  void* stream);
 
 /*
+ * Longest-list-first work order for ragged budgets (per-row budgets, or any
+ * caller-made lists of very different length).  Stage 3 is the same whichever
+ * query block a workgroup takes, so its launch may walk the query blocks of a
+ * head in any order; walking them by list length, longest first, keeps the
+ * workgroups that run together on lists of similar length (their sweeps over
+ * the head's K/V then stay together in the L2) and leaves the shortest lists
+ * for the last round (measured on MI355X at the merged 480p shape, budgets
+ * uniform in 8..64: 12 % faster than index order).
+ *
+ *   usv_attn_work_order   work_order[b,h,s] = the query block that slot s of head
+ *                         (b,h) takes: the blocks of the head sorted by cnt,
+ *                         descending (order among equal counts unspecified)
+ *   usv_block_sparse_attn_ordered   usv_block_sparse_attn with that table;
+ *                         work_order == NULL is usv_block_sparse_attn.  The
+ *                         output does not depend on the table as long as every
+ *                         head's slice is a permutation of 0..nb-1 (entries are
+ *                         clamped into range; a block named twice is computed
+ *                         twice, a block never named is not written).  fp32
+ *                         inputs ignore the table.
+ * cnt        : [B, Hh, nb] int32 (device, read only), as written by stage 2
+ * work_order : [B, Hh, nb] int32 (device)
+ */
+usv_status usv_attn_work_order(const int32_t* cnt, const usv_shape* shape, int32_t kmax,
+                               int32_t* work_order, void* stream);
+usv_status usv_block_sparse_attn_ordered(const void* q, const void* k, const void* v,
+                                         const usv_shape* shape, const int32_t* idx,
+                                         const int32_t* cnt, int32_t kmax,
+                                         const int32_t* work_order, float scale, int32_t out_dtype,
+                                         void* out, float* lse, void* stream);
+
+/*
  * Cube-level branch and fusion (Figure 2, right: each branch's result is spread over
  * the whole token grid again and the branches are then combined into one output;
  * Section 2.2: the coarse level of the coarse-to-fine scheme).  The paper prints

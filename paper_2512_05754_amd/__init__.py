@@ -9,6 +9,7 @@ _BINDING_NAMES = (
     "block_scores_static",
     "select_topk",
     "block_sparse_attn",
+    "attn_work_order",
     "merge_similarity",
     "merge_plan",
     "merge_apply",

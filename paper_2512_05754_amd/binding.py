@@ -29,6 +29,8 @@ EXPORTED_SYMBOLS = (
     "usv_entropy_allocate",
     "usv_block_sparse_attn",
     "usv_block_sparse_attn_fused",
+    "usv_attn_work_order",
+    "usv_block_sparse_attn_ordered",
     "usv_merge_workspace_bytes",
     "usv_merge_similarity",
     "usv_merge_plan",
@@ -118,6 +120,9 @@ def lib() -> ctypes.CDLL:
     L.usv_entropy_allocate.argtypes = [vp, i32, f32, f32, f32, f32, vp]
     L.usv_block_sparse_attn.restype = i32
     L.usv_block_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, i32, f32, i32, vp, vp, vp]
+    L.usv_attn_work_order.restype, L.usv_attn_work_order.argtypes = i32, [vp, sp, i32, vp, vp]
+    L.usv_block_sparse_attn_ordered.restype = i32
+    L.usv_block_sparse_attn_ordered.argtypes = [vp, vp, vp, sp, vp, vp, i32, vp, f32, i32, vp, vp, vp]
     gp, stp = ctypes.POINTER(UsvGrid), ctypes.POINTER(UsvStrides)
     L.usv_cube_token_order.restype, L.usv_cube_token_order.argtypes = i32, [gp, vp]
     L.usv_cube_gather.restype, L.usv_cube_gather.argtypes = i32, [vp, stp, sp, gp, vp, vp]
@@ -243,12 +248,24 @@ def select_topk(scores, k=0, seq_valid=None, budgets=None, kmax=None, idx=None, 
     return idx, cnt
 
 
+def attn_work_order(cnt, kmax, out=None):
+    """usv_attn_work_order: per head, the query blocks sorted by list length, longest first -> int32 [B, Hh, nb]."""
+    B, Hh, nb = cnt.shape
+    sh = UsvShape(B, Hh, nb * BLOCK, nb * BLOCK, 0, BLOCK, USV_F32)
+    if out is None:
+        out = torch.empty((B, Hh, nb), dtype=torch.int32, device=cnt.device)
+    _check(lib().usv_attn_work_order(_dev(cnt, "cnt", torch.int32), ctypes.byref(sh), int(kmax),
+                                     _dev(out, "work_order", torch.int32), _stream()))
+    return out
+
+
 def block_sparse_attn(q, k, v, idx, cnt, seq_valid=None, scale=0.0, out=None, lse=None, return_lse=False,
-                      out_dtype=None, coarse=None, gate_fine=None, gate_coarse=None):
-    """usv_block_sparse_attn(_fused): attention over the listed K/V blocks.  Returns out (and lse if asked).
+                      out_dtype=None, coarse=None, gate_fine=None, gate_coarse=None, work_order=None):
+    """usv_block_sparse_attn(_fused, _ordered): attention over the listed K/V blocks.  Returns out (and lse if asked).
 
     out_dtype: dtype of the result; defaults to q's dtype, torch.float32 is also allowed for bf16 inputs.
-    coarse (+ optional gates): usv_block_sparse_attn_fused, out = gate_fine * attention + gate_coarse * coarse[cube]."""
+    coarse (+ optional gates): usv_block_sparse_attn_fused, out = gate_fine * attention + gate_coarse * coarse[cube].
+    work_order (from attn_work_order): usv_block_sparse_attn_ordered, the launch walks the query blocks in that order."""
     sh = _shape_of(q, seq_valid)
     for name, t in (("k", k), ("v", v)):
         if t.shape != q.shape or t.dtype != q.dtype:
@@ -271,7 +288,13 @@ def block_sparse_attn(q, k, v, idx, cnt, seq_valid=None, scale=0.0, out=None, ls
     head = (_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), ctypes.byref(sh), _dev(idx, "idx", torch.int32),
             _dev(cnt, "cnt", torch.int32), int(kmax), float(scale))
     tail = (odt, _dev(out, "out"), None if lse is None else _dev(lse, "lse", torch.float32), _stream())
-    if coarse is None and gate_fine is None and gate_coarse is None:
+    if work_order is not None:
+        if coarse is not None or gate_fine is not None or gate_coarse is not None:
+            raise ValueError("work_order and the fused second branch are separate calls")
+        if tuple(work_order.shape) != (sh.batch, sh.heads, nb):
+            raise ValueError("work_order must be [B, Hh, nb]")
+        _check(lib().usv_block_sparse_attn_ordered(*head[:7], _dev(work_order, "work_order", torch.int32), head[7], *tail))
+    elif coarse is None and gate_fine is None and gate_coarse is None:
         _check(lib().usv_block_sparse_attn(*head, *tail))
     else:
         for name, g in (("gate_fine", gate_fine), ("gate_coarse", gate_coarse)):

@@ -233,10 +233,41 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v, co
                                      lse, stream);
 }
 
+usv_status usv_attn_work_order(const int32_t* cnt, const usv_shape* shape, int32_t kmax, int32_t* work_order,
+                               void* stream) {
+  usv::Dims s;
+  USV_TRY(check_shape(shape, false, &s));
+  USV_TRY(check_ptr(cnt, "cnt"));
+  USV_TRY(check_ptr(work_order, "work_order"));
+  if (kmax < 1 || kmax > s.nb) return fail(USV_ERR_INVALID_ARG, "kmax (%d) must be in [1, blocks = %d]", kmax, s.nb);
+  return hip_result(usv::launch_attn_work_order(cnt, s, kmax, work_order, static_cast<hipStream_t>(stream)),
+                    "usv_attn_work_order launch");
+}
+
+namespace {
+usv_status attn_any(const void* q, const void* k, const void* v, const usv_shape* shape, const int32_t* idx,
+                    const int32_t* cnt, int32_t kmax, const int32_t* work_order, float scale, const float* coarse,
+                    const void* gate_fine, const void* gate_coarse, int32_t out_dtype, void* out, float* lse, void* stream);
+}
+
+usv_status usv_block_sparse_attn_ordered(const void* q, const void* k, const void* v, const usv_shape* shape,
+                                         const int32_t* idx, const int32_t* cnt, int32_t kmax, const int32_t* work_order,
+                                         float scale, int32_t out_dtype, void* out, float* lse, void* stream) {
+  if (work_order) USV_TRY(check_ptr(work_order, "work_order"));
+  return attn_any(q, k, v, shape, idx, cnt, kmax, work_order, scale, nullptr, nullptr, nullptr, out_dtype, out, lse, stream);
+}
+
 usv_status usv_block_sparse_attn_fused(const void* q, const void* k, const void* v, const usv_shape* shape,
                                        const int32_t* idx, const int32_t* cnt, int32_t kmax, float scale,
                                        const float* coarse, const void* gate_fine, const void* gate_coarse,
                                        int32_t out_dtype, void* out, float* lse, void* stream) {
+  return attn_any(q, k, v, shape, idx, cnt, kmax, nullptr, scale, coarse, gate_fine, gate_coarse, out_dtype, out, lse, stream);
+}
+
+namespace {
+usv_status attn_any(const void* q, const void* k, const void* v, const usv_shape* shape, const int32_t* idx,
+                    const int32_t* cnt, int32_t kmax, const int32_t* work_order, float scale, const float* coarse,
+                    const void* gate_fine, const void* gate_coarse, int32_t out_dtype, void* out, float* lse, void* stream) {
   usv::Dims s;
   USV_TRY(check_shape(shape, true, &s));
   USV_TRY(check_ptr(q, "q"));
@@ -258,10 +289,12 @@ usv_status usv_block_sparse_attn_fused(const void* q, const void* k, const void*
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (s.bf16) {
     const usv::FuseArgs fuse{coarse, static_cast<const uint16_t*>(gate_fine), static_cast<const uint16_t*>(gate_coarse)};
-    return hip_result(usv::launch_attn_bf16(q, k, v, s, idx, cnt, kmax, scale, out, out_dtype == USV_F32, lse, fuse, st),
+    return hip_result(usv::launch_attn_bf16(q, k, v, s, idx, cnt, kmax, scale, out, out_dtype == USV_F32, lse, fuse, st,
+                                            work_order),
                       "usv_block_sparse_attn launch");
   }
-  // fp32 inputs (the accuracy path): attention, then the fusion kernel in place
+  // fp32 inputs (the accuracy path; it takes the query blocks in index order whatever work_order says): attention,
+  // then the fusion kernel in place
   hipError_t e = usv::launch_attn_f32(static_cast<const float*>(q), static_cast<const float*>(k),
                                       static_cast<const float*>(v), s, idx, cnt, kmax, scale, static_cast<float*>(out),
                                       lse, st);
@@ -269,6 +302,7 @@ usv_status usv_block_sparse_attn_fused(const void* q, const void* k, const void*
     e = usv::launch_fuse_outputs(out, true, coarse, gate_fine, gate_coarse, true, out, true, s, st);
   return hip_result(e, "usv_block_sparse_attn launch");
 }
+}  // namespace
 
 size_t usv_coarse_workspace_bytes(const usv_shape* shape) {
   usv::Dims s;

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
                                                                 void* __restrict__ out, float* __restrict__ lse,
                                                                 int nb, int Nv, int kmax, float scale_log2e,
                                                                 float p_shift, int total, int per_xcd, FuseArgs fuse,
-                                                                RasterArgs ras) {
+                                                                RasterArgs ras, const int32_t* __restrict__ work_order) {
   using T = Tile<D>;
   constexpr int KS = D / 32;  // MFMA k-steps of the QK^T product
   constexpr int DT = D / 16;  // 16-wide d sub-tiles of the output
@@ -231,16 +231,21 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
 
   const int work = xcd_contiguous_id(blockIdx.x, per_xcd);
   if (work >= total) return;  // whole workgroup leaves before any barrier
-  const int i = work % nb;
   const long long head = work / nb;
+  // which query block of the head this workgroup takes: its slot number, or what the caller's work order puts
+  // there (longest lists first: workgroups that run together then have lists of similar length, their sweeps
+  // over the head's K/V stay together in L2, and the last round of the launch is made of the shortest lists)
+  int i = work % nb;
+  if (work_order) i = min(max(work_order[work], 0), nb - 1);
+  const long long row_id = head * nb + i;
   const long long head_off = head * (long long)nb * kBlock * D;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction; keep it scalar
   const int qh = wave & 1, kh = wave >> 1;
   const int c16 = lane & 15, G = lane >> 4;  // MFMA lane coordinates: column / row within a 16-row group, group
-  const int n_list = min(max(cnt[work], 0), kmax);  // device contents are not trusted with addresses:
-  const int32_t* list = idx + (long long)work * kmax;
+  const int n_list = min(max(cnt[row_id], 0), kmax);  // device contents are not trusted with addresses:
+  const int32_t* list = idx + row_id * kmax;
   // valid query rows of this block: the first nq of its 64 positions hold tokens
   int nq = min(kBlock, max(0, Nv - i * kBlock));
   if constexpr (RASTER)
@@ -771,7 +776,7 @@ __global__ __launch_bounds__(kThreads, WGS) void attn_bf16(const uint16_t* __res
 template <int D, bool OUT_F32, int SLOTS, int WGS, bool RASTER = false>
 hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx, const int32_t* cnt,
                int kmax, float scale, void* out, float* lse, const FuseArgs& fuse, hipStream_t st,
-               const RasterArgs& ras = RasterArgs{}) {
+               const RasterArgs& ras = RasterArgs{}, const int32_t* work_order = nullptr) {
   const long long total = s.bh() * s.nb;
   const int per_xcd = (int)((total + kNumXcd - 1) / kNumXcd);
   const unsigned grid = (unsigned)per_xcd * kNumXcd;
@@ -784,7 +789,7 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
   auto K = static_cast<const uint16_t*>(k);
   auto V = static_cast<const uint16_t*>(v);
   attn_bf16<D, OUT_F32, SLOTS, WGS, RASTER><<<grid, kThreads, 0, st>>>(Q, K, V, idx, cnt, out, lse, s.nb, s.Nv, kmax, sl2,
-                                                                     p_shift, (int)total, per_xcd, fuse, ras);
+                                                                     p_shift, (int)total, per_xcd, fuse, ras, work_order);
   return hipGetLastError();
 }
 
@@ -792,7 +797,7 @@ hipError_t run(const void* q, const void* k, const void* v, const Dims& s, const
 
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
-                            const FuseArgs& fuse, hipStream_t st) {
+                            const FuseArgs& fuse, hipStream_t st, const int32_t* work_order) {
   // Two launch shapes, both with a 3-slot ring (48 KiB at d = 128), chosen by measurement at the 480p shape:
   //   sparse lists: 2 workgroups per CU with the whole register file between them, so that every fragment
   //     of a tile is read in one batch (a 5-slot ring that requests tiles two iterations ahead was 1 % slower
@@ -802,8 +807,8 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const D
   //     tiles and L2 serves them): 3 workgroups per CU, for the extra wave per SIMD (2 % faster there).
   const bool dense_like = 2 * (long long)kmax >= s.nb;
 #define USV_ATTN_CASE(DD, F32)                                                                         \
-  return dense_like ? run<DD, F32, 3, 3>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st)        \
-                    : run<DD, F32, 3, 2>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st)
+  return dense_like ? run<DD, F32, 3, 3>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st, RasterArgs{}, work_order) \
+                    : run<DD, F32, 3, 2>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st, RasterArgs{}, work_order)
   if (s.d == 128) {
     if (out_f32) USV_ATTN_CASE(128, true);
     USV_ATTN_CASE(128, false);

@@ -204,7 +204,54 @@ hipError_t run(const float* scores, const Dims& s, int k, const int32_t* budgets
   return hipGetLastError();
 }
 
+// Longest-list-first work order of the attention launch: per (batch, head) the query blocks sorted by list
+// length, descending (a counting sort in LDS: histogram of the lengths, starts from the long end, one slot per
+// row by an LDS atomic; the order among rows of equal length is whatever the atomics make it, which the
+// attention result does not depend on).  One workgroup per (batch, head).
+__global__ __launch_bounds__(256) void attn_work_order(const int32_t* __restrict__ cnt, int32_t* __restrict__ order, int nb,
+                                                       int kmax) {
+  extern __shared__ int hist[];  // kmax + 1 bins, then 256 partial sums
+  int* part = hist + kmax + 1;
+  const int tid = threadIdx.x;
+  const int32_t* c = cnt + (long long)blockIdx.x * nb;
+  int32_t* o = order + (long long)blockIdx.x * nb;
+  for (int b = tid; b <= kmax; b += 256) hist[b] = 0;
+  __syncthreads();
+  for (int i = tid; i < nb; i += 256) atomicAdd(&hist[min(max(c[i], 0), kmax)], 1);
+  __syncthreads();
+  // start[b] = rows with a longer list than b: suffix sums, each thread over a contiguous run of bins
+  const int per = (kmax + 256) / 256;  // bins per thread
+  const int hi = kmax - tid * per, lo = max(hi - per + 1, 0);  // thread 0 owns the longest lists
+  int sum = 0;
+  for (int b = hi; b >= lo; --b) sum += hist[b];
+  part[tid] = hi >= 0 ? sum : 0;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int t = 0; t < 256; ++t) {
+      const int v = part[t];
+      part[t] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  int run = part[tid];
+  for (int b = hi; b >= lo; --b) {
+    const int v = hist[b];
+    hist[b] = run;
+    run += v;
+  }
+  __syncthreads();
+  for (int i = tid; i < nb; i += 256) o[atomicAdd(&hist[min(max(c[i], 0), kmax)], 1)] = i;
+}
+
 }  // namespace
+
+hipError_t launch_attn_work_order(const int32_t* cnt, const Dims& s, int kmax, int32_t* work_order, hipStream_t st) {
+  const size_t lds = (size_t)(kmax + 1 + 256) * sizeof(int);
+  attn_work_order<<<(unsigned)s.bh(), 256, lds, st>>>(cnt, work_order, s.nb, kmax);
+  return hipGetLastError();
+}
 
 hipError_t launch_select_topk(const float* scores, const Dims& s, int k, const int32_t* budgets, int kmax,
                               bool force_local, int32_t* idx, int32_t* cnt, hipStream_t st) {

@@ -27,6 +27,7 @@ PATH = os.path.join(ROOT, "profiles", "traffic.json")
 SOURCES = {
     "attention": ("usv_attn_bf16.hip", "usv_internal.h"),
     "raster": ("usv_attn_bf16.hip", "usv_internal.h"),
+    "cubes": ("usv_attn_bf16.hip", "usv_internal.h"),
     "reorder": ("usv_reorder.hip", "usv_internal.h"),
     "merge": ("usv_merge.hip", "usv_internal.h"),
 }

@@ -457,3 +457,48 @@ def test_three_stages_replay_from_a_hip_graph(usv):
         torch.cuda.synchronize()
         for got, ref in zip((S, idx, cnt, out), want):
             assert torch.equal(got.view(torch.int32), ref.view(torch.int32))
+
+
+# --------------------------------------------------------------------------- #
+# longest-list-first work order
+# --------------------------------------------------------------------------- #
+def test_work_order_sorts_by_list_length_and_does_not_change_the_result(usv):
+    """usv_attn_work_order: per head a permutation of the query blocks with non-increasing list lengths;
+    usv_block_sparse_attn_ordered: the same bits as usv_block_sparse_attn whatever permutation it is given."""
+    w = Workload("ragged_small", 2, 3, 40 * 64 - 17, 128, "bf16", 2.0, 0, budget_lo=0, budget_hi=24, seed=77)
+    Q, K, V = synth.gen_qkv(w)
+    q, k, v = gu.up(Q), gu.up(K), gu.up(V)
+    budgets = synth.gen_budgets(w)
+    budgets[0, 0, :5] = [0, 24, 24, 1, 0]
+    S = usv.block_scores(q, k, seq_valid=w.seq_valid)
+    idx, cnt = usv.select_topk(S, seq_valid=w.seq_valid, budgets=gu.up(budgets), kmax=w.kmax)
+    order = usv.attn_work_order(cnt, w.kmax)
+    o_h, c_h = gu.down(order), gu.down(cnt)
+    for b in range(w.batch):
+        for h in range(w.heads):
+            assert sorted(o_h[b, h].tolist()) == list(range(w.nb))
+            lens = c_h[b, h][o_h[b, h]]
+            assert (np.diff(lens) <= 0).all()
+    ref, lse_ref = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32, return_lse=True)
+    rng = np.random.default_rng(3)
+    shuffled = np.stack([np.stack([rng.permutation(w.nb) for _ in range(w.heads)]) for _ in range(w.batch)]).astype(np.int32)
+    for wo in (order, gu.up(shuffled), gu.up(np.ascontiguousarray(o_h[..., ::-1]))):
+        out, lse = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32, return_lse=True,
+                                         work_order=wo)
+        assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
+        assert torch.equal(lse.view(torch.int32), lse_ref.view(torch.int32))
+    # and the ordered call against the oracle
+    O, _ = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), gu.down(idx), c_h, w.seq_valid)
+    gu.assert_attn_close(gu.down(ref), O, "bf16", "ragged lists")
+
+
+def test_work_order_long_lists_and_large_kmax(usv):
+    """kmax up to the block count (the histogram has kmax + 1 bins) and more rows than one pass of the workgroup."""
+    rng = np.random.default_rng(5)
+    B, Hh, nb = 1, 2, 700
+    cnt = rng.integers(0, nb + 1, size=(B, Hh, nb), dtype=np.int32)
+    cnt[0, 0, :3] = [nb, 0, nb]
+    order = gu.down(usv.attn_work_order(gu.up(cnt), nb))
+    for h in range(Hh):
+        assert sorted(order[0, h].tolist()) == list(range(nb))
+        assert (np.diff(cnt[0, h][order[0, h]]) <= 0).all()
