@@ -335,3 +335,11 @@ def test_bench_fails_loudly_without_a_gpu():
     assert r.returncode != 0
     assert "no CPU fallback" in (r.stdout + r.stderr)
     assert "{" not in r.stdout  # no result line is printed
+
+
+def test_traffic_figures_belong_to_the_kernel_sources_in_the_tree():
+    """profiles/traffic.json entries carry a digest of the kernel sources they were measured with: an entry that is
+    older than its kernel must be re-measured (or bench.py reports it as null)."""
+    from paper_2512_05754_amd import traffic
+
+    assert traffic.check() == 0, "stale entry in profiles/traffic.json: run the rocprofv3 passes again and record them"
