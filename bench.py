@@ -42,8 +42,8 @@ def parse():
                          "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
     ap.add_argument("--no-work-order", action="store_true",
-                    help="ragged budgets: plain usv_block_sparse_attn (query blocks in index order) instead of "
-                         "usv_attn_work_order + usv_block_sparse_attn_ordered")
+                    help="ragged budgets / the 720p shape: plain usv_block_sparse_attn (query blocks in index order) instead "
+                         "of usv_attn_work_order + usv_block_sparse_attn_ordered")
     ap.add_argument("--path", default="attention", choices=["attention", "reorder", "two_branch", "merge", "raster", "raster_two_branch", "raster_cubes"],
                     help="attention: the three-stage hot path (the headline metric); reorder: the raster <-> "
                          "cube-major token reorder either side of it (gather Q, K, V + scatter O); two_branch: the "
@@ -405,8 +405,11 @@ def main():
     ws = torch.empty(usv.workspace_bytes(B, Hh, N, min(w.seq_valid, N), d, w.dtype), dtype=torch.uint8, device=dev)
     idx = torch.empty((B, Hh, nb, kmax), dtype=torch.int32, device=dev)
     cnt = torch.empty((B, Hh, nb), dtype=torch.int32, device=dev)
-    # ragged budgets: the attention launch walks each head's query blocks longest list first (usv_attn_work_order)
-    ordered = budgets is not None and not raster and not two_branch and w.dtype == "bf16" and not args.no_work_order
+    # the attention launch walks each head's query blocks in the order of usv_attn_work_order (longest lists first, lists
+    # that lie alike next to each other) where that pays: ragged budgets, or a head's K and V many times an XCD's 4 MiB L2
+    kv_head_bytes = 2 * w.seq_len * w.head_dim * (2 if w.dtype == "bf16" else 4)
+    ordered = ((budgets is not None or kv_head_bytes > 8 * (4 << 20)) and not raster and not two_branch and w.dtype == "bf16"
+               and not args.no_work_order)
     work_order = torch.empty((B, Hh, nb), dtype=torch.int32, device=dev) if ordered else None
     out = torch.empty((B, Hh, w.seq_valid if raster else N, d), dtype=out_dtype, device=dev)
     if two_branch:
@@ -432,7 +435,7 @@ def main():
         usv.select_topk(S, k=keep_k, seq_valid=topk_valid, budgets=budgets, kmax=kmax, idx=idx, cnt=cnt,
                         force_local=two_branch)
         if ordered:  # timed with the selection
-            usv.attn_work_order(cnt, kmax, out=work_order)
+            usv.attn_work_order(cnt, kmax, idx=idx, out=work_order)
         if events is not None:
             events[2].record()
         if two_branch:  # the cube-level branch first: the attention kernel folds it and the gates into its store

@@ -172,18 +172,25 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v,
                                  void* stream);
 
 /*
- * Longest-list-first work order for ragged budgets (per-row budgets, or any
- * caller-made lists of very different length).  Stage 3 is the same whichever
- * query block a workgroup takes, so its launch may walk the query blocks of a
- * head in any order; walking them by list length, longest first, keeps the
- * workgroups that run together on lists of similar length (their sweeps over
- * the head's K/V then stay together in the L2) and leaves the shortest lists
- * for the last round (measured on MI355X at the merged 480p shape, budgets
- * uniform in 8..64: 12 % faster than index order).
+ * Work order of the attention launch.  Stage 3 is the same whichever query
+ * block a workgroup takes, so its launch may walk the query blocks of a head in
+ * any order.  Walking them sorted by
+ *     (list length descending, where the list lies ascending, block index)
+ * keeps the workgroups that run together on lists of similar length and
+ * similar placement: their ascending sweeps over the head's K/V then stay
+ * together in the 4 MiB L2 of the XCD they share, and the last round of the
+ * launch is made of the shortest lists.  "Where the list lies" = its entries at
+ * 1/4, 1/2 and 3/4 of its length, each reduced to one of 64 equal buckets of
+ * the block range, compared lexicographically.  Measured on MI355X: per-row
+ * budgets uniform in 8..64 at the merged 480p shape 12 % faster than index
+ * order; uniform budgets at the 720p shape (59 of 1182 blocks, where a head's
+ * K and V are ten times the L2) 20 % faster; uniform budgets at the 480p shape
+ * 1 % (there the sort costs what it gains).  It pays when the lists are ragged
+ * or when a head's K and V are many times the L2.
  *
  *   usv_attn_work_order   work_order[b,h,s] = the query block that slot s of head
- *                         (b,h) takes: the blocks of the head sorted by cnt,
- *                         descending (order among equal counts unspecified)
+ *                         (b,h) takes; deterministic.  idx == NULL: by list
+ *                         length (and block index) only.
  *   usv_block_sparse_attn_ordered   usv_block_sparse_attn with that table;
  *                         work_order == NULL is usv_block_sparse_attn.  The
  *                         output does not depend on the table as long as every
@@ -191,11 +198,13 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v,
  *                         clamped into range; a block named twice is computed
  *                         twice, a block never named is not written).  fp32
  *                         inputs ignore the table.
+ * idx        : NULL or [B, Hh, nb, kmax] int32 (device, read only), ascending lists
+ *              as written by stage 2 (other lists only make the order less useful)
  * cnt        : [B, Hh, nb] int32 (device, read only), as written by stage 2
  * work_order : [B, Hh, nb] int32 (device)
  */
-usv_status usv_attn_work_order(const int32_t* cnt, const usv_shape* shape, int32_t kmax,
-                               int32_t* work_order, void* stream);
+usv_status usv_attn_work_order(const int32_t* idx, const int32_t* cnt, const usv_shape* shape,
+                               int32_t kmax, int32_t* work_order, void* stream);
 usv_status usv_block_sparse_attn_ordered(const void* q, const void* k, const void* v,
                                          const usv_shape* shape, const int32_t* idx,
                                          const int32_t* cnt, int32_t kmax,

@@ -120,7 +120,7 @@ def lib() -> ctypes.CDLL:
     L.usv_entropy_allocate.argtypes = [vp, i32, f32, f32, f32, f32, vp]
     L.usv_block_sparse_attn.restype = i32
     L.usv_block_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, i32, f32, i32, vp, vp, vp]
-    L.usv_attn_work_order.restype, L.usv_attn_work_order.argtypes = i32, [vp, sp, i32, vp, vp]
+    L.usv_attn_work_order.restype, L.usv_attn_work_order.argtypes = i32, [vp, vp, sp, i32, vp, vp]
     L.usv_block_sparse_attn_ordered.restype = i32
     L.usv_block_sparse_attn_ordered.argtypes = [vp, vp, vp, sp, vp, vp, i32, vp, f32, i32, vp, vp, vp]
     gp, stp = ctypes.POINTER(UsvGrid), ctypes.POINTER(UsvStrides)
@@ -248,14 +248,17 @@ def select_topk(scores, k=0, seq_valid=None, budgets=None, kmax=None, idx=None, 
     return idx, cnt
 
 
-def attn_work_order(cnt, kmax, out=None):
-    """usv_attn_work_order: per head, the query blocks sorted by list length, longest first -> int32 [B, Hh, nb]."""
+def attn_work_order(cnt, kmax, idx=None, out=None):
+    """usv_attn_work_order: per head, the query blocks sorted by (list length descending, where the list lies
+    [needs idx], block index) -> int32 [B, Hh, nb]."""
     B, Hh, nb = cnt.shape
     sh = UsvShape(B, Hh, nb * BLOCK, nb * BLOCK, 0, BLOCK, USV_F32)
     if out is None:
         out = torch.empty((B, Hh, nb), dtype=torch.int32, device=cnt.device)
-    _check(lib().usv_attn_work_order(_dev(cnt, "cnt", torch.int32), ctypes.byref(sh), int(kmax),
-                                     _dev(out, "work_order", torch.int32), _stream()))
+    if idx is not None and (tuple(idx.shape[:3]) != (B, Hh, nb) or idx.shape[3] != kmax):
+        raise ValueError("idx must be [B, Hh, nb, kmax]")
+    _check(lib().usv_attn_work_order(None if idx is None else _dev(idx, "idx", torch.int32), _dev(cnt, "cnt", torch.int32),
+                                     ctypes.byref(sh), int(kmax), _dev(out, "work_order", torch.int32), _stream()))
     return out
 
 

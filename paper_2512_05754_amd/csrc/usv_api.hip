@@ -233,14 +233,15 @@ usv_status usv_block_sparse_attn(const void* q, const void* k, const void* v, co
                                      lse, stream);
 }
 
-usv_status usv_attn_work_order(const int32_t* cnt, const usv_shape* shape, int32_t kmax, int32_t* work_order,
-                               void* stream) {
+usv_status usv_attn_work_order(const int32_t* idx, const int32_t* cnt, const usv_shape* shape, int32_t kmax,
+                               int32_t* work_order, void* stream) {
   usv::Dims s;
   USV_TRY(check_shape(shape, false, &s));
+  if (idx) USV_TRY(check_ptr(idx, "idx"));
   USV_TRY(check_ptr(cnt, "cnt"));
   USV_TRY(check_ptr(work_order, "work_order"));
   if (kmax < 1 || kmax > s.nb) return fail(USV_ERR_INVALID_ARG, "kmax (%d) must be in [1, blocks = %d]", kmax, s.nb);
-  return hip_result(usv::launch_attn_work_order(cnt, s, kmax, work_order, static_cast<hipStream_t>(stream)),
+  return hip_result(usv::launch_attn_work_order(idx, cnt, s, kmax, work_order, static_cast<hipStream_t>(stream)),
                     "usv_attn_work_order launch");
 }
 

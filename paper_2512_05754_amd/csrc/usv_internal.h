@@ -81,7 +81,8 @@ hipError_t launch_attn_bf16_raster(const void* q, const void* k, const void* v, 
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,
                             const FuseArgs& fuse, hipStream_t st, const int32_t* work_order = nullptr);
-hipError_t launch_attn_work_order(const int32_t* cnt, const Dims& s, int kmax, int32_t* work_order, hipStream_t st);
+hipError_t launch_attn_work_order(const int32_t* idx, const int32_t* cnt, const Dims& s, int kmax, int32_t* work_order,
+                                  hipStream_t st);  // idx == nullptr: by list length only
 
 // gather: raster -> cube-major (+ zeroed padding); else cube-major -> raster.  Strides of the raster tensor in BYTES.
 hipError_t launch_cube_order(int32_t* order, const CubeGrid& g, int N, int Nv, hipStream_t stream);

@@ -204,52 +204,65 @@ hipError_t run(const float* scores, const Dims& s, int k, const int32_t* budgets
   return hipGetLastError();
 }
 
-// Longest-list-first work order of the attention launch: per (batch, head) the query blocks sorted by list
-// length, descending (a counting sort in LDS: histogram of the lengths, starts from the long end, one slot per
-// row by an LDS atomic; the order among rows of equal length is whatever the atomics make it, which the
-// attention result does not depend on).  One workgroup per (batch, head).
-__global__ __launch_bounds__(256) void attn_work_order(const int32_t* __restrict__ cnt, int32_t* __restrict__ order, int nb,
-                                                       int kmax) {
-  extern __shared__ int hist[];  // kmax + 1 bins, then 256 partial sums
-  int* part = hist + kmax + 1;
+// Work order of the attention launch: per (batch, head) the query blocks sorted by
+//   (list length descending, where the list lies ascending, block index ascending),
+// "where the list lies" being the entries at 1/4, 1/2 and 3/4 of the list, each reduced to one of 64 buckets
+// of the block range and compared lexicographically.  Workgroups that run together then have lists of similar
+// length and similar placement: their ascending sweeps over the head's K/V stay together in the XCD's L2, and
+// the last round of the launch is made of the shortest lists.  One workgroup per (batch, head): the keys,
+// packed with the block index into 64 bits (all distinct, so the result is deterministic), are sorted in LDS
+// with a bitonic network.
+constexpr int kOrderThreads = 1024;
+
+__global__ __launch_bounds__(kOrderThreads) void attn_work_order(const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+                                                                 int32_t* __restrict__ order, int nb, int kmax, int n2) {
+  extern __shared__ unsigned long long keys[];  // n2 = nb rounded up to a power of two
   const int tid = threadIdx.x;
-  const int32_t* c = cnt + (long long)blockIdx.x * nb;
-  int32_t* o = order + (long long)blockIdx.x * nb;
-  for (int b = tid; b <= kmax; b += 256) hist[b] = 0;
+  const long long row0 = (long long)blockIdx.x * nb;
+  for (int i = tid; i < n2; i += kOrderThreads) {
+    unsigned long long key = ~0ull;  // padding sorts last
+    if (i < nb) {
+      const int c = min(max(cnt[row0 + i], 0), kmax);
+      unsigned pos = 0u;
+      if (idx && c > 0) {
+        const int32_t* list = idx + (row0 + i) * kmax;
+#pragma unroll
+        for (int quarter = 1; quarter <= 3; ++quarter) {
+          const int j = min(max(list[(c - 1) * quarter / 4], 0), nb - 1);
+          pos = (pos << 6) | (unsigned)((long long)j * 64 / nb);
+        }
+      }
+      key = ((unsigned long long)(kmax - c) << 30) | ((unsigned long long)pos << 12) | (unsigned)i;
+    }
+    keys[i] = key;
+  }
   __syncthreads();
-  for (int i = tid; i < nb; i += 256) atomicAdd(&hist[min(max(c[i], 0), kmax)], 1);
-  __syncthreads();
-  // start[b] = rows with a longer list than b: suffix sums, each thread over a contiguous run of bins
-  const int per = (kmax + 256) / 256;  // bins per thread
-  const int hi = kmax - tid * per, lo = max(hi - per + 1, 0);  // thread 0 owns the longest lists
-  int sum = 0;
-  for (int b = hi; b >= lo; --b) sum += hist[b];
-  part[tid] = hi >= 0 ? sum : 0;
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int t = 0; t < 256; ++t) {
-      const int v = part[t];
-      part[t] = run;
-      run += v;
+  for (int k = 2; k <= n2; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < n2 / 2; t += kOrderThreads) {
+        const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));  // the lower index of pair t at distance j
+        const int hi = lo | j;
+        const unsigned long long a = keys[lo], b = keys[hi];
+        const bool up = (lo & k) == 0;
+        if ((a > b) == up) {
+          keys[lo] = b;
+          keys[hi] = a;
+        }
+      }
+      __syncthreads();
     }
   }
-  __syncthreads();
-  int run = part[tid];
-  for (int b = hi; b >= lo; --b) {
-    const int v = hist[b];
-    hist[b] = run;
-    run += v;
-  }
-  __syncthreads();
-  for (int i = tid; i < nb; i += 256) o[atomicAdd(&hist[min(max(c[i], 0), kmax)], 1)] = i;
+  for (int s = tid; s < nb; s += kOrderThreads) order[row0 + s] = (int32_t)(keys[s] & 0xfffu);
 }
 
 }  // namespace
 
-hipError_t launch_attn_work_order(const int32_t* cnt, const Dims& s, int kmax, int32_t* work_order, hipStream_t st) {
-  const size_t lds = (size_t)(kmax + 1 + 256) * sizeof(int);
-  attn_work_order<<<(unsigned)s.bh(), 256, lds, st>>>(cnt, work_order, s.nb, kmax);
+hipError_t launch_attn_work_order(const int32_t* idx, const int32_t* cnt, const Dims& s, int kmax, int32_t* work_order,
+                                  hipStream_t st) {
+  int n2 = 2;
+  while (n2 < s.nb) n2 <<= 1;  // <= 4096: 32 KiB of LDS
+  attn_work_order<<<(unsigned)s.bh(), kOrderThreads, (size_t)n2 * sizeof(unsigned long long), st>>>(idx, cnt, work_order, s.nb,
+                                                                                                      kmax, n2);
   return hipGetLastError();
 }
 

@@ -462,8 +462,27 @@ def test_three_stages_replay_from_a_hip_graph(usv):
 # --------------------------------------------------------------------------- #
 # longest-list-first work order
 # --------------------------------------------------------------------------- #
-def test_work_order_sorts_by_list_length_and_does_not_change_the_result(usv):
-    """usv_attn_work_order: per head a permutation of the query blocks with non-increasing list lengths;
+def expected_work_order(idx, cnt, kmax):
+    """The documented key, on the host: (kmax - len, buckets of the entries at 1/4, 1/2, 3/4 of the list, block index)."""
+    B, Hh, nb = cnt.shape
+    out = np.empty((B, Hh, nb), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hh):
+            c = np.clip(cnt[b, h], 0, kmax).astype(np.int64)
+            pos = np.zeros(nb, dtype=np.int64)
+            if idx is not None:
+                for quarter in (1, 2, 3):
+                    e = np.maximum(c - 1, 0) * quarter // 4
+                    j = np.clip(idx[b, h, np.arange(nb), e], 0, nb - 1).astype(np.int64)
+                    pos = (pos << 6) | np.where(c > 0, j * 64 // nb, 0)
+                pos = np.where(c > 0, pos, 0)
+            key = ((kmax - c) << 30) | (pos << 12) | np.arange(nb)
+            out[b, h] = np.argsort(key, kind="stable")
+    return out
+
+
+def test_work_order_is_the_documented_sort_and_does_not_change_the_result(usv):
+    """usv_attn_work_order: per head the query blocks sorted by (list length descending, where the list lies, index);
     usv_block_sparse_attn_ordered: the same bits as usv_block_sparse_attn whatever permutation it is given."""
     w = Workload("ragged_small", 2, 3, 40 * 64 - 17, 128, "bf16", 2.0, 0, budget_lo=0, budget_hi=24, seed=77)
     Q, K, V = synth.gen_qkv(w)
@@ -472,13 +491,15 @@ def test_work_order_sorts_by_list_length_and_does_not_change_the_result(usv):
     budgets[0, 0, :5] = [0, 24, 24, 1, 0]
     S = usv.block_scores(q, k, seq_valid=w.seq_valid)
     idx, cnt = usv.select_topk(S, seq_valid=w.seq_valid, budgets=gu.up(budgets), kmax=w.kmax)
-    order = usv.attn_work_order(cnt, w.kmax)
-    o_h, c_h = gu.down(order), gu.down(cnt)
+    i_h, c_h = gu.down(idx), gu.down(cnt)
+    order = usv.attn_work_order(cnt, w.kmax, idx=idx)
+    o_h = gu.down(order)
+    np.testing.assert_array_equal(o_h, expected_work_order(i_h, c_h, w.kmax))
+    np.testing.assert_array_equal(gu.down(usv.attn_work_order(cnt, w.kmax)), expected_work_order(None, c_h, w.kmax))
     for b in range(w.batch):
         for h in range(w.heads):
             assert sorted(o_h[b, h].tolist()) == list(range(w.nb))
-            lens = c_h[b, h][o_h[b, h]]
-            assert (np.diff(lens) <= 0).all()
+            assert (np.diff(c_h[b, h][o_h[b, h]]) <= 0).all()
     ref, lse_ref = usv.block_sparse_attn(q, k, v, idx, cnt, seq_valid=w.seq_valid, out_dtype=torch.float32, return_lse=True)
     rng = np.random.default_rng(3)
     shuffled = np.stack([np.stack([rng.permutation(w.nb) for _ in range(w.heads)]) for _ in range(w.batch)]).astype(np.int32)
@@ -488,17 +509,21 @@ def test_work_order_sorts_by_list_length_and_does_not_change_the_result(usv):
         assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
         assert torch.equal(lse.view(torch.int32), lse_ref.view(torch.int32))
     # and the ordered call against the oracle
-    O, _ = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), gu.down(idx), c_h, w.seq_valid)
+    O, _ = orc.block_sparse_attn(synth.as_f32(Q), synth.as_f32(K), synth.as_f32(V), i_h, c_h, w.seq_valid)
     gu.assert_attn_close(gu.down(ref), O, "bf16", "ragged lists")
 
 
-def test_work_order_long_lists_and_large_kmax(usv):
-    """kmax up to the block count (the histogram has kmax + 1 bins) and more rows than one pass of the workgroup."""
-    rng = np.random.default_rng(5)
-    B, Hh, nb = 1, 2, 700
-    cnt = rng.integers(0, nb + 1, size=(B, Hh, nb), dtype=np.int32)
-    cnt[0, 0, :3] = [nb, 0, nb]
-    order = gu.down(usv.attn_work_order(gu.up(cnt), nb))
+@pytest.mark.parametrize("nb,kmax", [(700, 700), (1, 1), (2, 1), (64, 7), (1182, 59), (4096, 16)])
+def test_work_order_sizes(usv, nb, kmax):
+    """Block counts that are no power of two (the sort pads), one block, the largest supported count, kmax = nb."""
+    rng = np.random.default_rng(5 + nb)
+    B, Hh = 1, 2
+    cnt = rng.integers(0, kmax + 1, size=(B, Hh, nb), dtype=np.int32)
+    idx = np.full((B, Hh, nb, kmax), -1, dtype=np.int32)
     for h in range(Hh):
-        assert sorted(order[0, h].tolist()) == list(range(nb))
-        assert (np.diff(cnt[0, h][order[0, h]]) <= 0).all()
+        for i in range(nb):
+            idx[0, h, i, :cnt[0, h, i]] = np.sort(rng.choice(nb, size=cnt[0, h, i], replace=False))
+    cnt[0, 0, :2] = [kmax, 0][:min(2, nb)]
+    idx[0, 0, 0, :kmax] = np.sort(rng.choice(nb, size=kmax, replace=False))
+    order = gu.down(usv.attn_work_order(gu.up(cnt), kmax, idx=gu.up(idx)))
+    np.testing.assert_array_equal(order, expected_work_order(idx, cnt, kmax))
