@@ -357,6 +357,8 @@ typedef struct {
   usv_strides in_strides;  /* element strides of q, k, v; token == 0 means contiguous [B, Hh, Nv, d] */
   usv_strides out_strides; /* element strides of out; token == 0 means contiguous [B, Hh, Nv, d] */
   const int32_t* block_valid; /* NULL, or device [seq_len / 64] int32 from usv_cube_order_padded: see there */
+  const int32_t* work_order;  /* NULL, or device [B, Hh, seq_len / 64] int32 from usv_attn_work_order: the attention
+                                 launch walks each head's query blocks in that order (same output) */
 } usv_raster;
 
 usv_status usv_cube_order(const usv_shape* shape, const usv_grid* grid, int32_t* order, void* stream);

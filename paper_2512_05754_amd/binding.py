@@ -80,7 +80,7 @@ class UsvStrides(ctypes.Structure):
 
 class UsvRaster(ctypes.Structure):
     _fields_ = [("order", ctypes.c_void_p), ("in_strides", UsvStrides), ("out_strides", UsvStrides),
-                ("block_valid", ctypes.c_void_p)]
+                ("block_valid", ctypes.c_void_p), ("work_order", ctypes.c_void_p)]
 
 
 def lib_path() -> str:
@@ -530,13 +530,14 @@ def cube_order_padded(grid, cube=(4, 4, 4), device="cuda:0"):
     return order, valid
 
 
-def _view(order, st, ost, block_valid):
+def _view(order, st, ost, block_valid, work_order=None):
     bv = None
     if block_valid is not None:
         if block_valid.numel() * BLOCK != order.numel():
             raise ValueError("block_valid must hold one count per 64 entries of order")
         bv = _dev(block_valid, "block_valid", torch.int32)
-    return UsvRaster(_dev(order, "order", torch.int32), st, ost, bv)
+    wo = None if work_order is None else _dev(work_order, "work_order", torch.int32)
+    return UsvRaster(_dev(order, "order", torch.int32), st, ost, bv, wo)
 
 
 def _raster_shape(x, order):
@@ -585,7 +586,7 @@ def coarse_attn_raster(scores, v, order, out=None, workspace=None, block_valid=N
 
 
 def block_sparse_attn_raster(q, k, v, order, idx, cnt, scale=0.0, out=None, out_dtype=None, return_lse=False,
-                             coarse=None, gate_fine=None, gate_coarse=None, block_valid=None):
+                             coarse=None, gate_fine=None, gate_coarse=None, block_valid=None, work_order=None):
     """usv_block_sparse_attn_raster(_fused): raster-ordered q, k, v [B, Hh, Nv, d] -> out [B, Hh, Nv, d] in raster order.
 
     coarse (+ optional raster-order gates laid out like q): out = gate_fine * attention + gate_coarse * coarse[cube]."""
@@ -603,7 +604,9 @@ def block_sparse_attn_raster(q, k, v, order, idx, cnt, scale=0.0, out=None, out_
         out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
     op, ost = _raster(out, "out")
     lse = torch.empty((sh.batch, sh.heads, sh.seq_valid), dtype=torch.float32, device=q.device) if return_lse else None
-    view = _view(order, st, ost, block_valid)
+    if work_order is not None and tuple(work_order.shape) != (sh.batch, sh.heads, sh.seq_len // BLOCK):
+        raise ValueError("work_order must be [B, Hh, nb]")
+    view = _view(order, st, ost, block_valid, work_order)
     gates = []
     for name, g_ in (("gate_fine", gate_fine), ("gate_coarse", gate_coarse)):
         if g_ is None:

@@ -569,8 +569,9 @@ usv_status usv_block_sparse_attn_raster_fused(const void* q, const void* k, cons
   if (gate_coarse && !aligned16(gate_coarse)) return fail(USV_ERR_INVALID_ARG, "gate_coarse is not 16-byte aligned");
   if (scale <= 0.f) scale = 1.0f / std::sqrt((float)s.d);
   const usv::FuseArgs fuse{coarse, static_cast<const uint16_t*>(gate_fine), static_cast<const uint16_t*>(gate_coarse)};
+  if (view->work_order) USV_TRY(check_ptr(view->work_order, "work_order"));
   return hip_result(usv::launch_attn_bf16_raster(q, k, v, s, ras, idx, cnt, kmax, scale, out, out_dtype == USV_F32, lse,
-                                                 fuse, static_cast<hipStream_t>(stream)),
+                                                 fuse, static_cast<hipStream_t>(stream), view->work_order),
                     "usv_block_sparse_attn_raster launch");
 }
 

@@ -821,8 +821,10 @@ hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const D
 // Raster-order tensors: the sparse shape (3-slot ring, 2 workgroups per CU) plus the order ring.
 hipError_t launch_attn_bf16_raster(const void* q, const void* k, const void* v, const Dims& s, const RasterArgs& ras,
                                    const int32_t* idx, const int32_t* cnt, int kmax, float scale, void* out,
-                                   bool out_f32, float* lse, const FuseArgs& fuse, hipStream_t st) {
-#define USV_RASTER_CASE(DD, F32) return run<DD, F32, 3, 2, true>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st, ras)
+                                   bool out_f32, float* lse, const FuseArgs& fuse, hipStream_t st,
+                                   const int32_t* work_order) {
+#define USV_RASTER_CASE(DD, F32) \
+  return run<DD, F32, 3, 2, true>(q, k, v, s, idx, cnt, kmax, scale, out, lse, fuse, st, ras, work_order)
   if (s.d == 128) {
     if (out_f32) USV_RASTER_CASE(128, true);
     USV_RASTER_CASE(128, false);

@@ -76,7 +76,8 @@ hipError_t launch_block_scores(const void* q, const void* k, const Dims& s, floa
                                hipStream_t st, const RasterArgs* ras = nullptr);
 hipError_t launch_attn_bf16_raster(const void* q, const void* k, const void* v, const Dims& s, const RasterArgs& ras,
                                    const int32_t* idx, const int32_t* cnt, int kmax, float scale, void* out,
-                                   bool out_f32, float* lse, const FuseArgs& fuse, hipStream_t st);
+                                   bool out_f32, float* lse, const FuseArgs& fuse, hipStream_t st,
+                                   const int32_t* work_order = nullptr);
 // work_order == nullptr: workgroup slot s of a head takes query block s; otherwise block work_order[head * nb + s]
 hipError_t launch_attn_bf16(const void* q, const void* k, const void* v, const Dims& s, const int32_t* idx,
                             const int32_t* cnt, int kmax, float scale, void* out, bool out_f32, float* lse,

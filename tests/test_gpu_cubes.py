@@ -68,6 +68,11 @@ def test_cube_faithful_stages_against_oracle(usv, grid, cube, B, Hh, d, keep):
     # the bf16-stored output is the fp32-stored one rounded to nearest even
     out_bf = usv.block_sparse_attn_raster(c["q"], c["k"], c["v"], c["order"], c["idx"], c["cnt"], block_valid=c["bv"])
     gu.assert_bf16_store_is_rne(out_bf, c["out"], "cube-faithful")
+    # a work order changes which workgroup takes which cube, not a bit of the result
+    wo = usv.attn_work_order(c["cnt"], keep, idx=c["idx"])
+    out_wo, lse_wo = usv.block_sparse_attn_raster(c["q"], c["k"], c["v"], c["order"], c["idx"], c["cnt"], out_dtype=torch.float32,
+                                                  return_lse=True, block_valid=c["bv"], work_order=wo)
+    assert torch.equal(out_wo.view(torch.int32), c["out"].view(torch.int32)) and torch.equal(lse_wo, c["lse"])
     if Nv == N:  # no cube is cut: bit for bit what the packed order gives
         order0 = usv.cube_order(grid, cube)
         assert torch.equal(order0, c["order"])
