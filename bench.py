@@ -55,6 +55,9 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (the three calls) in a HIP graph and time --steps replays of it; the per-stage "
                          "times then come from a second, eager pass (attention and raster paths only)")
+    ap.add_argument("--merge-plan-one-workgroup", action="store_true",
+                    help="--path merge: usv_merge_plan without a workspace (one workgroup per batch element instead of "
+                         "the radix select spread over the chip)")
     ap.add_argument("--settle-ms", type=float, default=150.0,
                     help="untimed steps run ahead of the --warmup steps until this much GPU time has passed: after an "
                          "idle period the chip takes some 50 ms of sustained load to reach its steady clock, and a short "
@@ -269,6 +272,9 @@ def merge_main(args):
     ws = torch.empty(B * N * (d + 1) * 4, dtype=torch.uint8, device=dev)
     row_of = torch.empty((B, N), dtype=torch.int32, device=dev)
     src_of = torch.empty((B, Nm), dtype=torch.int32, device=dev)
+    # --merge-plan-one-workgroup: usv_merge_plan without a workspace (one workgroup per batch element)
+    plan_ws = False if args.merge_plan_one_workgroup else torch.empty(usv.merge_plan_workspace_bytes(B, grid, mb, r),
+                                                                       dtype=torch.uint8, device=dev)
     merged = [torch.empty((B, Hh, Np, d), dtype=torch.bfloat16, device=dev) for _ in range(3)]
     o_merged = torch.randn((B, Hh, Np, d), device=dev, generator=gen)  # stands for the fp32 attention output
     o_raster = torch.empty((B, Hh, N, d), dtype=torch.float32, device=dev)
@@ -279,7 +285,7 @@ def merge_main(args):
         rec(0)
         usv.merge_similarity(k, grid, mb, out=u, blk=blk, workspace=ws)
         rec(1)
-        usv.merge_plan(u, blk, grid, mb, r, row_of=row_of, src_of=src_of)
+        usv.merge_plan(u, blk, grid, mb, r, row_of=row_of, src_of=src_of, workspace=plan_ws)
         rec(2)
         for x, y in zip((q, k, v), merged):
             usv.merge_apply(x, grid, mb, row_of, src_of, seq_len=Np, out=y)

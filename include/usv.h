@@ -460,9 +460,17 @@ usv_status usv_merge_similarity(const void* k, const usv_shape* shape, const usv
  *          not validated)
  * row_of : [B, T*H*W] int32 (device, written): the merged row token k reads back
  * src_of : [B, N - r] int32 (device, written): the raster index of the token that
- *          owns each merged row */
+ *          owns each merged row
+ * ws     : NULL, or device scratch of at least usv_merge_plan_workspace_bytes
+ *          bytes (contents on return unspecified).  Without it one workgroup per
+ *          batch element does the whole selection (fine for a few thousand
+ *          tokens); with it the selection is a radix select spread over the chip
+ *          (five short launches), which is what video-sized grids want.  The
+ *          result is the same, bit for bit. */
+size_t usv_merge_plan_workspace_bytes(const usv_shape* shape, const usv_grid* grid);
 usv_status usv_merge_plan(const float* u, const int32_t* blk, const usv_shape* shape,
-                          const usv_grid* grid, int32_t* row_of, int32_t* src_of, void* stream);
+                          const usv_grid* grid, int32_t* row_of, int32_t* src_of,
+                          void* ws, size_t ws_bytes, void* stream);
 
 /* x   : [B, Hh, T*H*W, d] of shape->dtype, raster order (device, read only)
  * out : [B, Hh, seq_len, d] of shape->dtype (device, written); means are taken in

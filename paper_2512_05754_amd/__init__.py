@@ -12,6 +12,7 @@ _BINDING_NAMES = (
     "attn_work_order",
     "merge_similarity",
     "merge_plan",
+    "merge_plan_workspace_bytes",
     "merge_apply",
     "unmerge_apply",
     "attn_entropy",

@@ -34,6 +34,7 @@ EXPORTED_SYMBOLS = (
     "usv_merge_workspace_bytes",
     "usv_merge_similarity",
     "usv_merge_plan",
+    "usv_merge_plan_workspace_bytes",
     "usv_merge_apply",
     "usv_unmerge_apply",
     "usv_cube_order",
@@ -129,7 +130,8 @@ def lib() -> ctypes.CDLL:
     L.usv_cube_scatter.restype, L.usv_cube_scatter.argtypes = i32, [vp, sp, gp, vp, stp, vp]
     L.usv_merge_workspace_bytes.restype, L.usv_merge_workspace_bytes.argtypes = sz, [sp, gp]
     L.usv_merge_similarity.restype, L.usv_merge_similarity.argtypes = i32, [vp, sp, gp, vp, vp, vp, sz, vp]
-    L.usv_merge_plan.restype, L.usv_merge_plan.argtypes = i32, [vp, vp, sp, gp, vp, vp, vp]
+    L.usv_merge_plan.restype, L.usv_merge_plan.argtypes = i32, [vp, vp, sp, gp, vp, vp, vp, sz, vp]
+    L.usv_merge_plan_workspace_bytes.restype, L.usv_merge_plan_workspace_bytes.argtypes = sz, [sp, gp]
     L.usv_merge_apply.restype, L.usv_merge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp, vp]
     L.usv_unmerge_apply.restype, L.usv_unmerge_apply.argtypes = i32, [vp, sp, gp, vp, vp, vp]
     rp = ctypes.POINTER(UsvRaster)
@@ -465,8 +467,20 @@ def merge_similarity(k, grid, mblock, out=None, blk=None, workspace=None):
     return out, blk
 
 
-def merge_plan(u, blk, grid, mblock, r, row_of=None, src_of=None):
-    """usv_merge_plan: u [B, T*H*W] fp32 and the partition blk -> row_of [B, T*H*W], src_of [B, T*H*W - r] (int32)."""
+MERGE_PLAN_WIDE_TOKENS = 8192  # from here on merge_plan brings a workspace by itself: the selection runs chip-wide
+
+
+def merge_plan_workspace_bytes(B, grid, mblock, r) -> int:
+    sh = _merge_shape(B, 1, 64, torch.float32, grid, r)
+    g = _grid(grid, mblock)
+    return int(lib().usv_merge_plan_workspace_bytes(ctypes.byref(sh), ctypes.byref(g)))
+
+
+def merge_plan(u, blk, grid, mblock, r, row_of=None, src_of=None, workspace=None):
+    """usv_merge_plan: u [B, T*H*W] fp32 and the partition blk -> row_of [B, T*H*W], src_of [B, T*H*W - r] (int32).
+
+    workspace: uint8 device tensor of merge_plan_workspace_bytes(...) -> the selection is spread over the chip; False ->
+    one workgroup per batch element; None -> a workspace is allocated from MERGE_PLAN_WIDE_TOKENS tokens on."""
     B, N = u.shape
     sh = _merge_shape(B, 1, 64, torch.float32, grid, r)
     g = _grid(grid, mblock)
@@ -474,8 +488,15 @@ def merge_plan(u, blk, grid, mblock, r, row_of=None, src_of=None):
         row_of = torch.empty((B, N), dtype=torch.int32, device=u.device)
     if src_of is None:
         src_of = torch.empty((B, max(N - int(r), 1)), dtype=torch.int32, device=u.device)[:, : N - int(r)]
+    if workspace is None and N >= MERGE_PLAN_WIDE_TOKENS:
+        workspace = torch.empty(int(lib().usv_merge_plan_workspace_bytes(ctypes.byref(sh), ctypes.byref(g))), dtype=torch.uint8,
+                                device=u.device)
+    if workspace is None or workspace is False:
+        wptr, wbytes = None, 0
+    else:
+        wptr, wbytes = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
     _check(lib().usv_merge_plan(_dev(u, "u", torch.float32), _dev(blk, "blk", torch.int32), ctypes.byref(sh), ctypes.byref(g),
-                                _dev(row_of, "row_of", torch.int32), _dev(src_of, "src_of", torch.int32), _stream()))
+                                _dev(row_of, "row_of", torch.int32), _dev(src_of, "src_of", torch.int32), wptr, wbytes, _stream()))
     return row_of, src_of
 
 

@@ -413,8 +413,16 @@ usv_status usv_merge_similarity(const void* k, const usv_shape* shape, const usv
                     "usv_merge_similarity launch");
 }
 
+size_t usv_merge_plan_workspace_bytes(const usv_shape* shape, const usv_grid* grid) {
+  usv::Dims s;
+  usv::MergeGrid g;
+  int N, r;
+  if (check_merge(shape, grid, &s, &g, &N, &r) != USV_OK) return 0;
+  return usv::merge_plan_workspace_bytes(s.B, N);
+}
+
 usv_status usv_merge_plan(const float* u, const int32_t* blk, const usv_shape* shape, const usv_grid* grid,
-                          int32_t* row_of, int32_t* src_of, void* stream) {
+                          int32_t* row_of, int32_t* src_of, void* ws, size_t ws_bytes, void* stream) {
   usv::Dims s;
   usv::MergeGrid g;
   int N, r;
@@ -423,7 +431,12 @@ usv_status usv_merge_plan(const float* u, const int32_t* blk, const usv_shape* s
   USV_TRY(check_ptr(blk, "blk"));
   USV_TRY(check_ptr(row_of, "row_of"));
   USV_TRY(check_ptr(src_of, "src_of"));
-  return hip_result(usv::launch_merge_select(u, blk, g, s.B, N, r, row_of, src_of, static_cast<hipStream_t>(stream)),
+  if (ws) {
+    const size_t need = usv::merge_plan_workspace_bytes(s.B, N);
+    if (!aligned16(ws) || ws_bytes < need)
+      return fail(USV_ERR_WORKSPACE, "workspace needs %zu bytes, 16-byte aligned (got %zu)", need, ws_bytes);
+  }
+  return hip_result(usv::launch_merge_select(u, blk, g, s.B, N, r, row_of, src_of, ws, static_cast<hipStream_t>(stream)),
                     "usv_merge_plan launch");
 }
 

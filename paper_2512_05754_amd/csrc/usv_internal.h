@@ -94,8 +94,9 @@ hipError_t launch_cube_move(bool gather, const void* src, void* dst, const CubeG
 // Token merging.  `s` describes the MERGED tensors (s.N padded rows, s.Nv = N - r valid rows); N = raster tokens.
 hipError_t launch_merge_similarity(const void* k, const Dims& s, const MergeGrid& g, int N, float* u, int32_t* blk,
                                    float* ws, hipStream_t st);
+size_t merge_plan_workspace_bytes(int B, int N);
 hipError_t launch_merge_select(const float* u, const int32_t* blk, const MergeGrid& g, int B, int N, int r, int32_t* row_of,
-                               int32_t* src_of, hipStream_t st);
+                               int32_t* src_of, void* ws, hipStream_t st);
 hipError_t launch_merge_rows(const void* x, const Dims& s, const MergeGrid& g, int N, const int32_t* row_of,
                              const int32_t* src_of, void* out, hipStream_t st);
 hipError_t launch_unmerge_rows(const void* y, const Dims& s, int N, const int32_t* row_of, void* out, hipStream_t st);

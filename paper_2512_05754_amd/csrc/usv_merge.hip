@@ -371,6 +371,273 @@ __global__ __launch_bounds__(kSelThreads) void merge_select(const float* __restr
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same selection spread over the chip (used when the caller brings a workspace): a radix select
+// over the 32-bit keys in three levels (8 + 12 + 12 bits), every level one launch of G = ceil(N / 2048)
+// workgroups per batch element, then one launch that counts per slice and one that assigns the rows.
+// Launches on one stream run one after the other, which is the only ordering used: no workgroup ever
+// waits for another.  All counts are integers, so the atomic additions give the same result in any
+// order, and ties are ranked by token index exactly as in the single-workgroup kernel.
+//
+// Workspace (int32) per batch element b:  state[8] = {D0, r1, D1, r2, thr, need_eq, -, -};
+// hist1[4096], hist2[4096] (cleared by the first launch, filled by atomics); slice_hist0[G][256]
+// (plain stores); slice_cnt[G][2] = {keys equal to thr, source keys below thr} of every slice.
+constexpr int kRsThreads = 256, kRsPer = 8, kRsSlice = kRsThreads * kRsPer;
+constexpr int kRsBins0 = 256, kRsBins = 4096, kRsState = 8;
+
+struct RadixWs {
+  int* state;        // [B][kRsState]
+  int* hist1;        // [B][kRsBins]
+  int* hist2;        // [B][kRsBins]
+  int* slice_hist0;  // [B][G][kRsBins0]
+  int* slice_cnt;    // [B][G][2]
+};
+
+// keys and partition words of the 8 consecutive tokens i0 .. i0 + 7 of batch element `ub`
+__device__ __forceinline__ void rs_load(const float* __restrict__ ub, const int32_t* __restrict__ blk, int N, int i0,
+                                        uint32_t (&key)[kRsPer], int (&bk)[kRsPer]) {
+  float x[kRsPer];
+#pragma unroll
+  for (int e = 0; e < kRsPer; ++e) x[e] = 0.f, bk[e] = (int)0x80000000;
+  if ((N & 3) == 0 && i0 + kRsPer - 1 < N) {  // rows of u and blk are 16-byte aligned
+#pragma unroll
+    for (int h = 0; h < kRsPer; h += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(ub + i0 + h);
+      const int4 k4 = *reinterpret_cast<const int4*>(blk + i0 + h);
+      x[h] = v.x; x[h + 1] = v.y; x[h + 2] = v.z; x[h + 3] = v.w;
+      bk[h] = k4.x; bk[h + 1] = k4.y; bk[h + 2] = k4.z; bk[h + 3] = k4.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < kRsPer; ++e)
+      if (i0 + e < N) x[e] = ub[i0 + e], bk[e] = blk[i0 + e];
+  }
+#pragma unroll
+  for (int e = 0; e < kRsPer; ++e) {
+    const uint32_t k = order_key(x[e]);
+    key[e] = (i0 + e < N && bk[e] >= 0) ? (k ? k : 1u) : 0u;
+  }
+}
+
+// Exclusive prefix of one int per thread over the 256 threads, and the total.  `lds` holds 4 ints.
+__device__ __forceinline__ int rs_block_exclusive(int v, int* lds, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();  // the previous use of lds is over
+  if (lane == 63) lds[wave] = inc;
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kRsThreads / 64; ++w) {
+    before += w < wave ? lds[w] : 0;
+    all += lds[w];
+  }
+  *total = all;
+  return before + inc - v;
+}
+
+// The digit D that holds the r-th largest key of a level, given the level's counts h[0 .. BINS) in LDS
+// (r >= 1 and at most the sum of the counts), and the rank that remains inside that digit:
+// out[0] = D, out[1] = r - (keys with a larger digit).  Thread t owns BINS / 256 digits, highest first.
+template <int BINS>
+__device__ __forceinline__ void rs_pick(const int* h, int r, int* scan4, int* out) {
+  constexpr int P = BINS / kRsThreads;
+  const int top = BINS - 1 - (int)threadIdx.x * P;
+  int own = 0;
+#pragma unroll
+  for (int p = 0; p < P; ++p) own += h[top - p];
+  int total;
+  int above = rs_block_exclusive(own, scan4, &total);
+  if (threadIdx.x == 0) out[0] = 0, out[1] = 0;  // r == 0 or r beyond the total: no digit (callers do not use it then)
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    const int c = h[top - p];
+    if (above < r && r <= above + c) out[0] = top - p, out[1] = r - above;
+    above += c;
+  }
+  __syncthreads();
+}
+
+// 4096 counts of an earlier launch -> LDS, with all sixteen loads of a thread in flight together
+__device__ __forceinline__ void rs_fetch_counts(const int* __restrict__ src, int* h) {
+  int t[kRsBins / kRsThreads];
+#pragma unroll
+  for (int k = 0; k < kRsBins / kRsThreads; ++k) t[k] = src[k * kRsThreads + threadIdx.x];
+#pragma unroll
+  for (int k = 0; k < kRsBins / kRsThreads; ++k) h[k * kRsThreads + threadIdx.x] = t[k];
+}
+
+// level 0: counts of the top 8 key bits of this slice; the first slice also clears the level-1/2 counts
+__global__ __launch_bounds__(kRsThreads) void rs_hist0(const float* __restrict__ u, const int32_t* __restrict__ blk, int N,
+                                                       RadixWs ws) {
+  __shared__ int h[kRsBins0];
+  const int b = blockIdx.y, g = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
+  h[tid] = 0;
+  __syncthreads();
+  uint32_t key[kRsPer];
+  int bk[kRsPer];
+  rs_load(u + (long long)b * N, blk, N, g * kRsSlice + tid * kRsPer, key, bk);
+#pragma unroll
+  for (int e = 0; e < kRsPer; ++e)
+    if (key[e]) atomicAdd(&h[key[e] >> 24], 1);
+  __syncthreads();
+  ws.slice_hist0[((long long)b * G + g) * kRsBins0 + tid] = h[tid];
+  if (g == 0) {
+    for (int i = tid; i < kRsBins; i += kRsThreads) ws.hist1[(long long)b * kRsBins + i] = 0, ws.hist2[(long long)b * kRsBins + i] = 0;
+  }
+}
+
+// levels 1 and 2: pick the digit of the level above from its counts, then count this level's 12 bits over the keys
+// that carry the digits picked so far
+template <int LEVEL>
+__global__ __launch_bounds__(kRsThreads) void rs_hist12(const float* __restrict__ u, const int32_t* __restrict__ blk, int N,
+                                                        int r, RadixWs ws) {
+  __shared__ int h[kRsBins];
+  __shared__ int scan4[4], out[2];
+  const int b = blockIdx.y, g = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
+  int* state = ws.state + (long long)b * kRsState;
+  // every global read this workgroup needs is requested up front (the words of the earlier launches come from
+  // another XCD's writes, i.e. from memory: a couple of microseconds each if they were taken one after the other)
+  const int st0 = LEVEL == 2 ? state[0] : 0, st1 = LEVEL == 2 ? state[1] : 0;
+  uint32_t key[kRsPer];
+  int bk[kRsPer];
+  rs_load(u + (long long)b * N, blk, N, g * kRsSlice + tid * kRsPer, key, bk);
+  uint32_t prefix;  // the key bits above this level's 12
+  if constexpr (LEVEL == 1) {
+    int s = 0;
+#pragma unroll 8
+    for (int gg = 0; gg < G; ++gg) s += ws.slice_hist0[((long long)b * G + gg) * kRsBins0 + tid];
+    h[tid] = s;
+    __syncthreads();
+    rs_pick<kRsBins0>(h, r, scan4, out);
+    if (g == 0 && tid == 0) state[0] = out[0], state[1] = out[1];
+    prefix = (uint32_t)out[0];
+  } else {
+    rs_fetch_counts(ws.hist1 + (long long)b * kRsBins, h);
+    __syncthreads();
+    rs_pick<kRsBins>(h, st1, scan4, out);
+    if (g == 0 && tid == 0) state[2] = out[0], state[3] = out[1];
+    prefix = ((uint32_t)st0 << 12) | (uint32_t)out[0];
+  }
+  __syncthreads();  // everyone has read h and out
+  for (int i = tid; i < kRsBins; i += kRsThreads) h[i] = 0;
+  __syncthreads();
+  constexpr int SHIFT = LEVEL == 1 ? 12 : 0;
+#pragma unroll
+  for (int e = 0; e < kRsPer; ++e)
+    if (key[e] && (key[e] >> (SHIFT + 12)) == prefix) atomicAdd(&h[(key[e] >> SHIFT) & (kRsBins - 1)], 1);
+  __syncthreads();
+  int* dst = (LEVEL == 1 ? ws.hist1 : ws.hist2) + (long long)b * kRsBins;
+  for (int i = tid; i < kRsBins; i += kRsThreads)
+    if (h[i]) atomicAdd(&dst[i], h[i]);
+}
+
+// the threshold key and the number of ties to take, then this slice's counts against it
+__global__ __launch_bounds__(kRsThreads) void rs_count(const float* __restrict__ u, const int32_t* __restrict__ blk, int N,
+                                                       int r, RadixWs ws) {
+  __shared__ int h[kRsBins];
+  __shared__ int scan4[4], out[2];
+  const int b = blockIdx.y, g = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
+  int* state = ws.state + (long long)b * kRsState;
+  const int st0 = state[0], st2 = state[2], st3 = state[3];  // (unused garbage when r == 0)
+  uint32_t key[kRsPer];
+  int bk[kRsPer];
+  rs_load(u + (long long)b * N, blk, N, g * kRsSlice + tid * kRsPer, key, bk);
+  uint32_t thr = 0xffffffffu;  // r == 0: nothing is merged (no key is that large)
+  int need_eq = 0;
+  if (r > 0) {
+    rs_fetch_counts(ws.hist2 + (long long)b * kRsBins, h);
+    __syncthreads();
+    rs_pick<kRsBins>(h, st3, scan4, out);
+    thr = ((uint32_t)st0 << 24) | ((uint32_t)st2 << 12) | (uint32_t)out[0];
+    need_eq = out[1];
+  }
+  if (g == 0 && tid == 0) state[4] = (int)thr, state[5] = need_eq;
+  int eq = 0, lt = 0;
+#pragma unroll
+  for (int e = 0; e < kRsPer; ++e) {
+    eq += key[e] == thr ? 1 : 0;
+    lt += (key[e] != 0u && key[e] < thr) ? 1 : 0;
+  }
+  int eq_all, lt_all;
+  rs_block_exclusive(eq, scan4, &eq_all);
+  rs_block_exclusive(lt, scan4, &lt_all);
+  if (tid == 0) {
+    ws.slice_cnt[((long long)b * G + g) * 2] = eq_all;
+    ws.slice_cnt[((long long)b * G + g) * 2 + 1] = lt_all;
+  }
+}
+
+// rows of the merged sequence: the ordered sweep of the single-workgroup kernel, one slice per workgroup, with the
+// counts of the slices before it as its carry
+__global__ __launch_bounds__(kRsThreads) void rs_assign(const float* __restrict__ u, const int32_t* __restrict__ blk,
+                                                        int32_t* __restrict__ row_of, int32_t* __restrict__ src_of, int N,
+                                                        int n_dst, int r, RadixWs ws) {
+  __shared__ int scan4[4];
+  const int b = blockIdx.y, g = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
+  const int* state = ws.state + (long long)b * kRsState;
+  const uint32_t thr = (uint32_t)state[4];
+  const int need_eq = state[5];
+  const int i0 = g * kRsSlice + tid * kRsPer;
+  uint32_t key[kRsPer];
+  int bk[kRsPer];
+  rs_load(u + (long long)b * N, blk, N, i0, key, bk);
+  const int n_unmerged = N - n_dst - r;
+  int32_t* rob = row_of + (long long)b * N;
+  int32_t* sob = src_of + (long long)b * (N - r);
+  // ties and lower keys in the slices before this one
+  int eq_b = 0, lt_b = 0;
+  for (int gg = tid; gg < g; gg += kRsThreads) {
+    eq_b += ws.slice_cnt[((long long)b * G + gg) * 2];
+    lt_b += ws.slice_cnt[((long long)b * G + gg) * 2 + 1];
+  }
+  int eq_before, lt_before;
+  rs_block_exclusive(eq_b, scan4, &eq_before);
+  rs_block_exclusive(lt_b, scan4, &lt_before);
+  const int un_before = lt_before + max(0, eq_before - need_eq);  // ties beyond the first need_eq stay unmerged
+
+  int eq = 0;
+#pragma unroll
+  for (int e = 0; e < kRsPer; ++e) eq += key[e] == thr ? 1 : 0;
+  int unused;
+  int eq_rank = eq_before + rs_block_exclusive(eq, scan4, &unused);
+  unsigned merged_bits = 0u;
+  int un = 0;
+#pragma unroll
+  for (int e = 0; e < kRsPer; ++e) {
+    const bool is_eq = key[e] == thr;
+    const bool merged = key[e] != 0u && (key[e] > thr || (is_eq && eq_rank < need_eq));
+    eq_rank += is_eq ? 1 : 0;
+    un += (key[e] != 0u && !merged) ? 1 : 0;
+    merged_bits |= merged ? 1u << e : 0u;
+  }
+  int un_rank = un_before + rs_block_exclusive(un, scan4, &unused);
+  if (i0 >= N) return;
+  int row[kRsPer];
+#pragma unroll
+  for (int e = 0; e < kRsPer; ++e) {
+    const bool merged = (merged_bits >> e) & 1u;
+    // a destination's row, and the row a merged source reads back: the block's rank among the destinations
+    row[e] = (key[e] == 0u || merged) ? n_unmerged + (bk[e] & 0x7fffffff) : un_rank++;
+    // (the bound holds by construction; it keeps a partition array that does not belong to this grid from writing past src_of)
+    if (i0 + e < N && !merged && (unsigned)row[e] < (unsigned)(N - r)) sob[row[e]] = i0 + e;
+  }
+  if ((N & 3) == 0 && i0 + kRsPer - 1 < N) {
+    *reinterpret_cast<int4*>(rob + i0) = make_int4(row[0], row[1], row[2], row[3]);
+    *reinterpret_cast<int4*>(rob + i0 + 4) = make_int4(row[4], row[5], row[6], row[7]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < kRsPer; ++e)
+      if (i0 + e < N) rob[i0 + e] = row[e];
+  }
+}
+
 // grid = (ceil(Np / rows_per_wg), Hh, B): merged rows.  Nm = N - r valid merged rows.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void merge_rows(const T* __restrict__ x, const int32_t* __restrict__ row_of,
@@ -494,9 +761,32 @@ hipError_t launch_merge_similarity(const void* k, const Dims& s, const MergeGrid
   return hipGetLastError();
 }
 
+size_t merge_plan_workspace_bytes(int B, int N) {
+  const size_t G = (size_t)(N + kRsSlice - 1) / kRsSlice;
+  return (size_t)B * (kRsState + 2 * kRsBins + G * (kRsBins0 + 2)) * sizeof(int);
+}
+
 hipError_t launch_merge_select(const float* u, const int32_t* blk, const MergeGrid& g, int B, int N, int r, int32_t* row_of,
-                               int32_t* src_of, hipStream_t st) {
+                               int32_t* src_of, void* ws, hipStream_t st) {
   const int n_dst = g.nT * g.nH * g.nW;
+  if (ws) {
+    const unsigned G = (unsigned)((N + kRsSlice - 1) / kRsSlice);
+    RadixWs w;
+    w.state = static_cast<int*>(ws);
+    w.hist1 = w.state + (size_t)B * kRsState;
+    w.hist2 = w.hist1 + (size_t)B * kRsBins;
+    w.slice_hist0 = w.hist2 + (size_t)B * kRsBins;
+    w.slice_cnt = w.slice_hist0 + (size_t)B * G * kRsBins0;
+    const dim3 grid(G, (unsigned)B);
+    if (r > 0) {
+      rs_hist0<<<grid, kRsThreads, 0, st>>>(u, blk, N, w);
+      rs_hist12<1><<<grid, kRsThreads, 0, st>>>(u, blk, N, r, w);
+      rs_hist12<2><<<grid, kRsThreads, 0, st>>>(u, blk, N, r, w);
+    }
+    rs_count<<<grid, kRsThreads, 0, st>>>(u, blk, N, r, w);
+    rs_assign<<<grid, kRsThreads, 0, st>>>(u, blk, row_of, src_of, N, n_dst, r, w);
+    return hipGetLastError();
+  }
   if (N <= kSelThreads * 4 * 8)
     merge_select<8><<<(unsigned)B, kSelThreads, 0, st>>>(u, blk, row_of, src_of, N, n_dst, r);
   else if (N <= kSelThreads * 4 * 20)

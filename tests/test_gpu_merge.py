@@ -41,6 +41,16 @@ def expected_blk(grid, mb):
     return rank.astype(np.uint32).view(np.int32)
 
 
+def both_plans(usv, u, blk, grid, mb, r):
+    """usv_merge_plan both ways: one workgroup per batch element (no workspace) and the radix select spread over the chip
+    (workspace, handed over full of garbage: nothing in it is assumed clear).  The two must agree bit for bit."""
+    one = usv.merge_plan(u, blk, grid, mb, r, workspace=False)
+    ws = torch.full((usv.merge_plan_workspace_bytes(u.shape[0], grid, mb, r),), 0xA5, dtype=torch.uint8, device=u.device)
+    wide = usv.merge_plan(u, blk, grid, mb, r, workspace=ws)
+    assert torch.equal(one[0], wide[0]) and torch.equal(one[1], wide[1]), f"r={r}: the two selections differ"
+    return wide
+
+
 def bf16_round_ok(got, ref):
     return np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.maximum(1, np.abs(ref))
 
@@ -61,7 +71,7 @@ def test_merge_pipeline(usv, grid, mb, B, Hh, d, dtype):
     gu.assert_f32_close(u_h, u_ref, "similarity")
     n_src = int((~np.isneginf(u_ref[0])).sum())
     for r in sorted({0, 1, n_src // 3, n_src // 2, n_src}):
-        row_of, src_of = usv.merge_plan(u, blk, grid, mb, r)
+        row_of, src_of = both_plans(usv, u, blk, grid, mb, r)
         rr, rs = orc.merge_plan(u_h, grid, mb, r)
         np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
         np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
@@ -94,7 +104,7 @@ def test_merge_plan_ties_and_special_values(usv):
     u[:, dst == np.arange(N)] = -np.inf
     n_src = int((dst != np.arange(N)).sum())
     for r in (1, 37, 1000, 1024, 1500, n_src - 1, n_src):
-        row_of, src_of = usv.merge_plan(gu.up(u), gu.up(expected_blk(grid, mb)), grid, mb, r)
+        row_of, src_of = both_plans(usv, gu.up(u), gu.up(expected_blk(grid, mb)), grid, mb, r)
         rr, rs = orc.merge_plan(u, grid, mb, r)
         np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
         np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
@@ -142,7 +152,7 @@ def test_full_size_480p_half_merged(usv):
     u, blk = usv.merge_similarity(k, grid, mb)
     u_h = gu.down(u)
     gu.assert_f32_close(u_h, orc.merge_similarity(gu.down(k).astype(np.float64), grid, mb), "similarity 480p")
-    row_of, src_of = usv.merge_plan(u, blk, grid, mb, r)
+    row_of, src_of = both_plans(usv, u, blk, grid, mb, r)
     rr, rs = orc.merge_plan(u_h, grid, mb, r)
     np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
     np.testing.assert_array_equal(src_of.cpu().numpy(), rs)
@@ -170,8 +180,12 @@ def test_merge_plan_large_token_counts(usv, grid, mb):
     u[1] = rng.standard_normal(N).astype(np.float32)                             # and a row without ties
     u[:, dst == np.arange(N)] = -np.inf
     n_src = int((dst != np.arange(N)).sum())
-    for r in (N // 2 if N // 2 <= n_src else n_src, 4097, n_src):
-        row_of, src_of = usv.merge_plan(gu.up(u), gu.up(blk), grid, mb, r)
+    u[0, 5::97] = np.nan
+    u[0, 11::89] = -0.0
+    u[0, 17::83] = np.inf
+    u[:, dst == np.arange(N)] = -np.inf
+    for r in (N // 2 if N // 2 <= n_src else n_src, 4097, 1, n_src - 1, n_src, 0):
+        row_of, src_of = both_plans(usv, gu.up(u), gu.up(blk), grid, mb, r)
         rr, rs = orc.merge_plan(u, grid, mb, r)
         np.testing.assert_array_equal(row_of.cpu().numpy(), rr)
         np.testing.assert_array_equal(src_of.cpu().numpy(), rs)

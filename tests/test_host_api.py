@@ -290,10 +290,15 @@ def test_merge_calls_reject_bad_arguments_before_launch():
     many = shape(seq_len=256, seq_valid=193)  # more rows than tokens
     for bad in (few, many):
         assert L.usv_merge_workspace_bytes(ctypes.byref(bad), ctypes.byref(g)) == 0
-        assert name(L.usv_merge_plan(FAKE, FAKE, ctypes.byref(bad), ctypes.byref(g), FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
-    assert name(L.usv_merge_plan(FAKE, FAKE, ctypes.byref(ok), None, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
-    assert name(L.usv_merge_plan(None, FAKE, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
-    assert name(L.usv_merge_plan(FAKE, None, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+        assert name(L.usv_merge_plan(FAKE, FAKE, ctypes.byref(bad), ctypes.byref(g), FAKE, FAKE, None, 0, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_merge_plan(FAKE, FAKE, ctypes.byref(ok), None, FAKE, FAKE, None, 0, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_merge_plan(None, FAKE, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, None, 0, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_merge_plan(FAKE, None, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, None, 0, None)) == "USV_ERR_INVALID_ARG"
+    # the chip-wide selection's scratch: state, two 4096-bin count arrays, and 256 + 2 ints per slice of 2048 tokens
+    need_plan = L.usv_merge_plan_workspace_bytes(ctypes.byref(ok), ctypes.byref(g))
+    assert need_plan == (8 + 2 * 4096 + 1 * 258) * 4
+    assert L.usv_merge_plan_workspace_bytes(ctypes.byref(few), ctypes.byref(g)) == 0
+    assert name(L.usv_merge_plan(FAKE, FAKE, ctypes.byref(ok), ctypes.byref(g), FAKE, FAKE, FAKE, need_plan - 1, None)) == "USV_ERR_WORKSPACE"
     zero = binding.UsvGrid(4, 6, 8, 2, 0, 2)
     assert name(L.usv_merge_apply(FAKE, ctypes.byref(ok), ctypes.byref(zero), FAKE, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
     need = L.usv_merge_workspace_bytes(ctypes.byref(ok), ctypes.byref(g))
