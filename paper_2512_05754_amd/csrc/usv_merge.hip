@@ -14,6 +14,13 @@
 //   unmerge_rows       gather: token k reads row row_of[k]
 #include "usv_internal.h"
 
+#ifndef USV_MERGE_DESC_HEADS
+#define USV_MERGE_DESC_HEADS 12  // heads whose pieces merge_descriptors keeps in flight
+#endif
+#ifndef USV_MERGE_COPY_ROWS
+#define USV_MERGE_COPY_ROWS 2  // rows a lane group copies in usv_merge_apply
+#endif
+
 namespace usv {
 namespace {
 
@@ -73,6 +80,25 @@ struct Row<uint16_t> {
   }
 };
 
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned chunk_t;  // 16 bytes
+
+// 16 bytes of a row as they lie in memory -> floats
+template <typename T>
+__device__ __forceinline__ void widen(const chunk_t& c, float (&o)[Row<T>::kElems]);
+template <>
+__device__ __forceinline__ void widen<float>(const chunk_t& c, float (&o)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = __uint_as_float(c[i]);
+}
+template <>
+__device__ __forceinline__ void widen<uint16_t>(const chunk_t& c, float (&o)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    o[2 * i] = __uint_as_float(c[i] << 16);
+    o[2 * i + 1] = __uint_as_float(c[i] & 0xffff0000u);
+  }
+}
+
 // grid = (ceil(N / rows_per_wg), B); a group of LPR lanes owns one token.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void merge_descriptors(const T* __restrict__ k, float* __restrict__ m,
@@ -86,14 +112,19 @@ __global__ __launch_bounds__(256) void merge_descriptors(const T* __restrict__ k
     const T* src = k + ((long long)b * Hh * N + row) * D + c0;
     const long long hs = (long long)N * D;
     int h = 0;
-    for (; h + 6 <= Hh; h += 6) {  // six heads in flight (twelve heads = two trips)
-      float x[6][VEC];
+    // that many heads in flight, as raw 16-byte pieces; streaming reads (nothing here touches a byte of K twice, and a
+    // read that leaves its lines in the caches costs this kernel a third of its time: 30 -> 21 us at 480p)
+    for (; h + USV_MERGE_DESC_HEADS <= Hh; h += USV_MERGE_DESC_HEADS) {
+      chunk_t raw[USV_MERGE_DESC_HEADS];
 #pragma unroll
-      for (int u = 0; u < 6; ++u) Row<T>::load(src + (h + u) * hs, x[u]);
+      for (int u = 0; u < USV_MERGE_DESC_HEADS; ++u) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(src + (h + u) * hs));
 #pragma unroll
-      for (int u = 0; u < 6; ++u)
+      for (int u = 0; u < USV_MERGE_DESC_HEADS; ++u) {  // ascending heads: the order of the additions does not depend on the batch
+        float xv[VEC];
+        widen<T>(raw[u], xv);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] += x[u][e];
+        for (int e = 0; e < VEC; ++e) acc[e] += xv[e];
+      }
     }
     for (; h < Hh; ++h) {
       float x[VEC];
@@ -638,75 +669,106 @@ __global__ __launch_bounds__(kRsThreads) void rs_assign(const float* __restrict_
   }
 }
 
-// grid = (ceil(Np / rows_per_wg), Hh, B): merged rows.  Nm = N - r valid merged rows.
-template <typename T, int D>
+// grid = (dst_wgs + copy_wgs, Hh, B).  Nm = N - r valid merged rows, of which the last nT * nH * nW are the
+// destinations in ascending raster order and the others copies of token src_of[p]; rows Nm <= p < Np are padding.
+// A group of D / VEC lanes owns a row piece by piece (16 bytes per lane, kept as raw chunks while in flight).
+// The first dst_wgs workgroups take the destination and padding rows, one per lane group: they cost several dependent
+// reads each, so they start first.  The others copy CR rows per lane group, all their loads in flight together.
+template <typename T, int D, int CR>
 __global__ __launch_bounds__(256) void merge_rows(const T* __restrict__ x, const int32_t* __restrict__ row_of,
                                                   const int32_t* __restrict__ src_of, T* __restrict__ out, MergeGrid g,
-                                                  int N, int Nm, int Np, int Hh) {
+                                                  int N, int Nm, int Np, int Hh, int dst_wgs) {
   constexpr int VEC = Row<T>::kElems, LPR = D / VEC, RPW = 256 / LPR;
-  // workgroups are dealt from the END of the merged sequence: the destination rows live there and cost several
-  // dependent reads each, so they start first and the cheap copy rows fill in behind them
-  const int b = blockIdx.z, h = blockIdx.y, p = (gridDim.x - 1 - blockIdx.x) * RPW + threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * VEC;
+  const int b = blockIdx.z, h = blockIdx.y, lg = threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * VEC;
+  const int n_unmerged = Nm - g.nT * g.nH * g.nW;
+  const T* xb = x + ((long long)(b * Hh + h) * N) * D + c0;
+  T* ob = out + ((long long)(b * Hh + h) * Np) * D + c0;
+  if ((int)blockIdx.x >= dst_wgs) {  // copies, byte for byte
+    const int p0 = ((int)blockIdx.x - dst_wgs) * (RPW * CR) + lg;
+    int src[CR];
+#pragma unroll
+    for (int k = 0; k < CR; ++k) src[k] = src_of[(long long)b * Nm + min(p0 + k * RPW, n_unmerged - 1)];
+    chunk_t raw[CR];
+#pragma unroll
+    for (int k = 0; k < CR; ++k) raw[k] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(xb + (long long)src[k] * D));
+#pragma unroll
+    for (int k = 0; k < CR; ++k)
+      if (p0 + k * RPW < n_unmerged) *reinterpret_cast<chunk_t*>(ob + (long long)(p0 + k * RPW) * D) = raw[k];
+    return;
+  }
+  const int p = n_unmerged + (int)blockIdx.x * RPW + lg;
   if (p >= Np) return;
+  ob += (long long)p * D;
+  if (p >= Nm) {  // padding rows are written as zero
+    *reinterpret_cast<chunk_t*>(ob) = chunk_t{0u, 0u, 0u, 0u};
+    return;
+  }
+  // the destination's coordinates follow from the row number alone: no look-up waits for src_of
+  const int rank = p - n_unmerged, bt = rank / (g.nH * g.nW), rem = rank - bt * g.nH * g.nW, bh = rem / g.nW;
+  Tok c;
+  c.t = bt * g.st;
+  c.h = bh * g.sh;
+  c.w = (rem - bh * g.nW) * g.sw;
+  const int s = (c.t * g.H + c.h) * g.W + c.w;
+  // A destination: the mean of itself and the tokens of its block that read back from row p.  2x2x2 blocks (the usual
+  // case) have all seven look-ups in flight together, then eight row pieces without a branch between them: a slot
+  // that does not take part re-reads the destination's own piece (the same cache line) and is left out of the sum.
+  const int32_t* ro = row_of + (long long)b * N;
+  const int et = min(g.st, g.T - c.t), eh = min(g.sh, g.H - c.h), ew = min(g.sw, g.W - c.w);
   float acc[VEC];
+  int count = 1;
+  if (g.st == 2 && g.sh == 2 && g.sw == 2) {
+    int kk[8], rk[8];
+    kk[0] = s;
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-  if (p < Nm) {
-    const int s = src_of[(long long)b * Nm + p];
-    const T* xb = x + ((long long)(b * Hh + h) * N) * D + c0;
-    const Tok c = coords(g, s);
+    for (int q = 1; q < 8; ++q) {
+      const int lw = q & 1, lh = (q >> 1) & 1, lt = q >> 2;
+      const bool inside = lt < et && lh < eh && lw < ew;
+      kk[q] = inside ? ((c.t + lt) * g.H + c.h + lh) * g.W + c.w + lw : s;
+      rk[q] = ro[kk[q]];  // (the destination's own word is p as well: `inside` keeps it out)
+      rk[q] = inside ? rk[q] : -1;
+    }
+    bool use[8];
+#pragma unroll
+    for (int q = 1; q < 8; ++q) {
+      use[q] = rk[q] == p;
+      kk[q] = use[q] ? kk[q] : s;
+    }
+    chunk_t raw[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) raw[q] = *reinterpret_cast<const chunk_t*>(xb + (long long)kk[q] * D);
+    widen<T>(raw[0], acc);
+#pragma unroll
+    for (int q = 1; q < 8; ++q) {  // same order of additions as the general walk below
+      float v[VEC];
+      widen<T>(raw[q], v);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] = use[q] ? acc[e] + v[e] : acc[e];
+      count += use[q] ? 1 : 0;
+    }
+  } else {  // any other block shape: walk the block
     Row<T>::load(xb + (long long)s * D, acc);
-    if (is_dst(g, c)) {
-      // the merged sources of this destination are the tokens of its block that read back from row p
-      const int32_t* ro = row_of + (long long)b * N;
-      const int et = min(g.st, g.T - c.t), eh = min(g.sh, g.H - c.h), ew = min(g.sw, g.W - c.w);
-      int count = 1;
-      if (g.st == 2 && g.sh == 2 && g.sw == 2) {
-        // the usual 2x2x2 block: the seven look-ups are in flight together, then the row loads they select
-        // (same order of additions as the general loop)
-        int kk[8], rk[8];
+    for (int lt = 0; lt < et; ++lt)
+      for (int lh = 0; lh < eh; ++lh)
+        for (int lw = 0; lw < ew; ++lw) {
+          const int k = ((c.t + lt) * g.H + c.h + lh) * g.W + c.w + lw;
+          if (k != s && ro[k] == p) {
+            float v[VEC];
+            Row<T>::load(xb + (long long)k * D, v);
 #pragma unroll
-        for (int q = 1; q < 8; ++q) {
-          const int lw = q & 1, lh = (q >> 1) & 1, lt = q >> 2;
-          kk[q] = ((c.t + lt) * g.H + c.h + lh) * g.W + c.w + lw;
-          rk[q] = (lt < et && lh < eh && lw < ew) ? ro[kk[q]] : -1;
-        }
-        float v[8][VEC];
-#pragma unroll
-        for (int q = 1; q < 8; ++q)
-          if (rk[q] == p) Row<T>::load(xb + (long long)kk[q] * D, v[q]);
-#pragma unroll
-        for (int q = 1; q < 8; ++q)
-          if (rk[q] == p) {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += v[q][e];
+            for (int e = 0; e < VEC; ++e) acc[e] += v[e];
             ++count;
           }
-      } else {
-        for (int lt = 0; lt < et; ++lt)
-          for (int lh = 0; lh < eh; ++lh)
-            for (int lw = 0; lw < ew; ++lw) {
-              const int k = ((c.t + lt) * g.H + c.h + lh) * g.W + c.w + lw;
-              if (k != s && ro[k] == p) {
-                float v[VEC];
-                Row<T>::load(xb + (long long)k * D, v);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] += v[e];
-                ++count;
-              }
-            }
-      }
-      if (count > 1) {
-        const float inv = 1.0f / (float)count;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] *= inv;
-      }
-    }
+        }
   }
-  Row<T>::store(out + ((long long)(b * Hh + h) * Np + p) * D + c0, acc);
+  if (count > 1) {
+    const float inv = 1.0f / (float)count;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] *= inv;
+  }
+  Row<T>::store(ob, acc);
 }
 
-typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned chunk_t;  // 16 bytes
 
 // grid = (ceil(N / 64), B*Hh): 64 raster tokens per workgroup, <= 4 pieces of 16 bytes per lane.
 template <int CHUNKS>
@@ -799,9 +861,13 @@ hipError_t launch_merge_select(const float* u, const int32_t* blk, const MergeGr
 hipError_t launch_merge_rows(const void* x, const Dims& s, const MergeGrid& g, int N, const int32_t* row_of,
                              const int32_t* src_of, void* out, hipStream_t st) {
   const int vec = s.bf16 ? 8 : 4, rpw = 256 / (s.d / vec);
-  const dim3 grid((unsigned)((s.N + rpw - 1) / rpw), (unsigned)s.Hh, (unsigned)s.B);
-#define USV_MERGE_ROWS(T, DD) \
-  merge_rows<T, DD><<<grid, 256, 0, st>>>(static_cast<const T*>(x), row_of, src_of, static_cast<T*>(out), g, N, s.Nv, s.N, s.Hh)
+  constexpr int CR = USV_MERGE_COPY_ROWS;
+  const int n_unmerged = s.Nv - g.nT * g.nH * g.nW;
+  const int dst_wgs = (s.N - n_unmerged + rpw - 1) / rpw, copy_wgs = (n_unmerged + rpw * CR - 1) / (rpw * CR);
+  const dim3 grid((unsigned)(dst_wgs + copy_wgs), (unsigned)s.Hh, (unsigned)s.B);
+#define USV_MERGE_ROWS(T, DD)                                                                                               \
+  merge_rows<T, DD, CR><<<grid, 256, 0, st>>>(static_cast<const T*>(x), row_of, src_of, static_cast<T*>(out), g, N, s.Nv, s.N, \
+                                              s.Hh, dst_wgs)
   if (s.bf16) {
     if (s.d == 128) USV_MERGE_ROWS(uint16_t, 128);
     else USV_MERGE_ROWS(uint16_t, 64);
