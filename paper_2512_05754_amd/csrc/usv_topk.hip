@@ -18,12 +18,8 @@ namespace {
 
 constexpr int kRowsPerWg = 4;  // 4 wavefronts, one row each
 
-// Order-preserving key of a canonicalised fp32 (bit pattern b): -0 == +0, NaN -> 0 (below -inf's key).
-__device__ __forceinline__ uint32_t order_key_bits(uint32_t b) {
-  if ((b & 0x7fffffffu) > 0x7f800000u) return 0u;  // NaN
-  if (b == 0x80000000u) b = 0u;                    // -0 -> +0
-  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
+// The order-preserving key of a canonicalised fp32 with bit pattern b (never formed per element, see above):
+//   NaN -> 0 (below -inf's key);  -0 -> the key of +0;  negative floats -> ~b;  the others -> b | 0x80000000.
 
 // The float t(c) with  x >= t(c)  <=>  order_key(x) >= c  for every candidate key c >= 1:
 //   c <= key(-inf): every number (NaN excluded) qualifies -> -inf;  keys of the negative floats are the
