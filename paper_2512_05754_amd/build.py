@@ -63,6 +63,25 @@ def build_tools(verbose: bool = True) -> str:
     return PEAK_TOOL
 
 
+DEMO_TOOL = os.path.join(TOOLS_DIR, "usv_demo")
+
+
+def build_demo(verbose: bool = True) -> str:
+    """Compiles tools/usv_demo.c, a plain C99 program that drives the three stages through the C ABI, with gcc."""
+    rocm = os.path.dirname(os.path.dirname(os.path.realpath(hipcc())))
+    cmd = [shutil.which("gcc") or "gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"), os.path.join(TOOLS_DIR, "usv_demo.c"),
+           "-o", DEMO_TOOL, "-L", PKG_DIR, "-l:libusv.so", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + res.stdout + res.stderr)
+    return DEMO_TOOL
+
+
 if __name__ == "__main__":
     print(build_library(extra_flags=tuple(sys.argv[1:])))
     print(build_tools())
+    print(build_demo())

@@ -348,3 +348,16 @@ def test_traffic_figures_belong_to_the_kernel_sources_in_the_tree():
     from paper_2512_05754_amd import traffic
 
     assert traffic.check() == 0, "stale entry in profiles/traffic.json: run the rocprofv3 passes again and record them"
+
+
+# --------------------------------------------------------------------------- #
+# the C ABI from C: tools/usv_demo.c compiles as C99 against include/usv.h and links against libusv.so
+# --------------------------------------------------------------------------- #
+def test_c_demo_builds_and_reports_usage():
+    import subprocess
+
+    from paper_2512_05754_amd.build import build_demo
+
+    exe = build_demo(verbose=False)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert res.returncode == 1 and "usage" in res.stderr
