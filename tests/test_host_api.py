@@ -361,3 +361,41 @@ def test_c_demo_builds_and_reports_usage():
     exe = build_demo(verbose=False)
     res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert res.returncode == 1 and "usage" in res.stderr
+
+
+# --------------------------------------------------------------------------- #
+# work order, ordered attention, static stage 1, padded cube order: validation before any launch
+# --------------------------------------------------------------------------- #
+def test_order_static_and_padded_cube_calls_reject_bad_arguments():
+    L = binding.lib()
+    name = lambda rc: L.usv_status_string(rc).decode()
+    ok = shape()
+    nb = ok.seq_len // 64
+    # usv_attn_work_order: idx may be NULL (lengths only); cnt, the table and kmax are checked
+    assert name(L.usv_attn_work_order(None, None, ctypes.byref(ok), 4, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_attn_work_order(None, FAKE, ctypes.byref(ok), 4, None, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_attn_work_order(FAKE + 4, FAKE, ctypes.byref(ok), 4, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    for kmax in (0, nb + 1):
+        assert name(L.usv_attn_work_order(None, FAKE, ctypes.byref(ok), kmax, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_attn_work_order(None, FAKE, None, 4, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    # usv_block_sparse_attn_ordered: a misaligned table is refused; everything else as usv_block_sparse_attn
+    args = (FAKE, FAKE, FAKE, ctypes.byref(ok), FAKE, FAKE, 4)
+    assert name(L.usv_block_sparse_attn_ordered(*args, FAKE + 4, 0.0, ok.dtype, FAKE, None, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_block_sparse_attn_ordered(*args, FAKE, float("nan"), ok.dtype, FAKE, None, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_block_sparse_attn_ordered(*args, FAKE, 0.0, ok.dtype, None, None, None)) == "USV_ERR_INVALID_ARG"
+    # usv_block_scores_static: pointers and shape are checked like usv_block_scores; the size limit has its own status
+    assert name(L.usv_block_scores_static(None, FAKE, ctypes.byref(ok), FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_block_scores_static(FAKE, FAKE, ctypes.byref(ok), None, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_block_scores_static(FAKE, FAKE, ctypes.byref(shape(block=32)), FAKE, None)) == "USV_ERR_UNSUPPORTED"
+    big = shape(batch=2, heads=33, seq_len=1024 * 64, seq_valid=1024 * 64, head_dim=128)
+    assert L.usv_workspace_bytes(ctypes.byref(big)) > (64 << 20)
+    assert name(L.usv_block_scores_static(FAKE, FAKE, ctypes.byref(big), FAKE, None)) == "USV_ERR_WORKSPACE"
+    # usv_cube_count / usv_cube_order_padded
+    g = binding.UsvGrid(21, 30, 52, 4, 4, 4)
+    assert L.usv_cube_count(ctypes.byref(g)) == 6 * 8 * 13
+    assert L.usv_cube_count(ctypes.byref(binding.UsvGrid(21, 30, 52, 4, 0, 4))) == 0
+    assert L.usv_cube_count(None) == 0
+    assert name(L.usv_cube_order_padded(None, FAKE, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_cube_order_padded(ctypes.byref(g), None, FAKE, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_cube_order_padded(ctypes.byref(g), FAKE, FAKE + 2, None)) == "USV_ERR_INVALID_ARG"
+    assert name(L.usv_cube_order_padded(ctypes.byref(binding.UsvGrid(4, 4, 4, 8, 8, 8)), FAKE, FAKE, None)) == "USV_ERR_UNSUPPORTED"
