@@ -16,7 +16,10 @@ pytestmark = pytest.mark.gpu
 
 
 def test_three_stages_from_a_c_program(tmp_path):
-    assert os.path.exists(DEMO_TOOL), "tools/usv_demo is not built: python -m paper_2512_05754_amd.build"
+    if not os.path.exists(DEMO_TOOL):  # a host program (gcc, seconds): built here if the tree came without it
+        from paper_2512_05754_amd.build import build_demo
+
+        build_demo(verbose=False)
     w = synth.Workload("c_demo", 2, 3, 11 * 64 - 17, 128, "bf16", 2.0, 4, seed=7301)
     Q, K, V = synth.gen_qkv(w)
     for name, x in (("q", Q), ("k", K), ("v", V)):
