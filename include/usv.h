@@ -472,8 +472,12 @@ usv_status usv_merge_plan(const float* u, const int32_t* blk, const usv_shape* s
                           const usv_grid* grid, int32_t* row_of, int32_t* src_of,
                           void* ws, size_t ws_bytes, void* stream);
 
-/* x   : [B, Hh, T*H*W, d] of shape->dtype, raster order (device, read only)
- * out : [B, Hh, seq_len, d] of shape->dtype (device, written); means are taken in
+/* x      : [B, Hh, T*H*W, d] of shape->dtype, raster order (device, read only)
+ * row_of, src_of : as written by usv_merge_plan for the same shape and grid (device,
+ *       read only; not validated).  The layout of the merged sequence is relied on:
+ *       the destinations own its last rows in ascending raster order, and row p of
+ *       the others is a copy of token src_of[p].
+ * out    : [B, Hh, seq_len, d] of shape->dtype (device, written); means are taken in
  *       fp32 and rounded once; rows seq_valid <= p < seq_len are written as zero */
 usv_status usv_merge_apply(const void* x, const usv_shape* shape, const usv_grid* grid,
                            const int32_t* row_of, const int32_t* src_of, void* out, void* stream);
