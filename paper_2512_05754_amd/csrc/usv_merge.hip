@@ -687,7 +687,8 @@ __global__ __launch_bounds__(256) void merge_rows(const T* __restrict__ x, const
     const int p0 = ((int)blockIdx.x - dst_wgs) * (RPW * CR) + lg;
     int src[CR];
 #pragma unroll
-    for (int k = 0; k < CR; ++k) src[k] = src_of[(long long)b * Nm + min(p0 + k * RPW, n_unmerged - 1)];
+    for (int k = 0; k < CR; ++k)  // (device contents are not trusted with addresses: the token index is clamped into the grid)
+      src[k] = min(max(src_of[(long long)b * Nm + min(p0 + k * RPW, n_unmerged - 1)], 0), N - 1);
     chunk_t raw[CR];
 #pragma unroll
     for (int k = 0; k < CR; ++k) raw[k] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(xb + (long long)src[k] * D));
@@ -780,7 +781,7 @@ __global__ __launch_bounds__(CHUNKS >= 32 ? 512 : 256) void unmerge_rows(const u
   constexpr int kRowBytes = CHUNKS * 16, PER_THREAD = kBlock * CHUNKS / kThreads;
   __shared__ int row[kBlock];
   const int tid = threadIdx.x, k0 = blockIdx.x * kBlock, bh = blockIdx.y, b = bh / Hh;
-  if (tid < kBlock) row[tid] = k0 + tid < N ? row_of[(long long)b * N + k0 + tid] : 0;
+  if (tid < kBlock) row[tid] = k0 + tid < N ? min(max(row_of[(long long)b * N + k0 + tid], 0), Np - 1) : 0;  // clamped into y
   __syncthreads();
   const unsigned char* src = y + (long long)bh * Np * kRowBytes;
   unsigned char* dst = out + ((long long)bh * N + k0) * kRowBytes;
