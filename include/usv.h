@@ -353,7 +353,8 @@ usv_status usv_cube_scatter(const void* cube, const usv_shape* shape, const usv_
  *                                 out (and lse, [B, Hh, seq_valid]) in raster order
  */
 typedef struct {
-  const int32_t* order;    /* device, [seq_len] int32, from usv_cube_order (any permutation works) */
+  const int32_t* order;    /* device, [seq_len] int32, from usv_cube_order (any permutation works); NOT validated:
+                              every entry is used as a token index and must lie in [0, seq_valid) */
   usv_strides in_strides;  /* element strides of q, k, v; token == 0 means contiguous [B, Hh, Nv, d] */
   usv_strides out_strides; /* element strides of out; token == 0 means contiguous [B, Hh, Nv, d] */
   const int32_t* block_valid; /* NULL, or device [seq_len / 64] int32 from usv_cube_order_padded: see there */
