@@ -17,8 +17,10 @@ pytestmark = pytest.mark.gpu
 
 def test_three_stages_from_a_c_program(tmp_path):
     if not os.path.exists(DEMO_TOOL):  # a host program (gcc, seconds): built here if the tree came without it
+        from paper_2512_05754_amd import binding
         from paper_2512_05754_amd.build import build_demo
 
+        binding.lib()
         build_demo(verbose=False)
     w = synth.Workload("c_demo", 2, 3, 11 * 64 - 17, 128, "bf16", 2.0, 4, seed=7301)
     Q, K, V = synth.gen_qkv(w)

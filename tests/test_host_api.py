@@ -358,6 +358,7 @@ def test_c_demo_builds_and_reports_usage():
 
     from paper_2512_05754_amd.build import build_demo
 
+    binding.lib()  # the program links against libusv.so: make sure it exists
     exe = build_demo(verbose=False)
     res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert res.returncode == 1 and "usage" in res.stderr
